@@ -1,0 +1,121 @@
+"""The oracle's hop schedules (Section 3.4, Appendix B) against plain definitions."""
+import numpy as np
+import pytest
+
+from oracle import dq_oracle as O
+
+
+def grads(n, n_sg, seed, dtype=np.float32):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        g = (rng.standard_normal(n_sg * 256) * 1e-3).astype(np.float32)
+        if dtype == np.uint16:
+            g = (g.view(np.uint32) >> 16).astype(np.uint16)
+        out.append(g)
+    return out
+
+
+def widen(g):
+    return g if g.dtype == np.float32 else (g.astype(np.uint32) << 16).view(np.float32)
+
+
+def vnmse(out, gs):
+    s = sum(widen(g).astype(np.float64) for g in gs)
+    e = np.concatenate(out).astype(np.float64) - s
+    return float((e ** 2).sum() / (s ** 2).sum())
+
+
+def test_split_bucket_covers_every_super_group_once():
+    chunks = O.split_bucket([5, 9, 2], 4, first_sg=100)
+    assert [c.first_sg for c in chunks] == [100, 104, 108, 112]
+    assert [list(c.n_sg) for c in chunks] == [[4, 0, 0], [1, 3, 0], [0, 4, 0], [0, 2, 2]]
+    with pytest.raises(AssertionError):
+        O.split_bucket([5, 9, 1], 4)
+
+
+def test_ring_two_workers_is_compress_then_decompress_add():
+    orc = O.Oracle(2, seed=3)
+    gs = grads(2, 4, 1)
+    out = O.ring_reduce_scatter(orc, gs, [0, 4, 0])
+    chunks = O.split_bucket([0, 4, 0], 2)
+    for c in range(2):
+        sl = slice(c * 512, (c + 1) * 512)
+        msg = orc.compress(chunks[c], c, gs[c][sl])
+        want = orc.decompress(chunks[c], msg, gs[(c + 1) % 2][sl])
+        assert np.array_equal(out[c], want)
+
+
+def test_ring_trace_and_ranks():
+    """Chunk c is compressed by worker c, re-encoded by c+1..c+n-2, finished by c+n-1."""
+    n = 4
+    orc = O.Oracle(n, seed=5)
+    gs = grads(n, 8, 2)
+    trace = {}
+    out = O.ring_reduce_scatter(orc, gs, [2, 4, 2], trace=trace)
+    chunks = O.split_bucket([2, 4, 2], n)
+    for c in range(n):
+        sl = slice(c * 512, (c + 1) * 512)
+        msg = orc.compress(chunks[c], c, gs[c][sl])
+        assert np.array_equal(trace[(0, c)], msg)
+        for t in (1, 2):
+            msg = orc.dar_hop(chunks[c], (c + t) % n, msg, gs[(c + t) % n][sl])
+            assert np.array_equal(trace[(t, c)], msg)
+        assert np.array_equal(out[c], orc.decompress(chunks[c], msg, gs[(c + 3) % n][sl]))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+def test_reduce_scatter_approximates_the_sum(dtype):
+    n = 8
+    orc = O.Oracle(n, seed=7)
+    gs = grads(n, 16, 3, dtype)
+    e8 = vnmse(O.ring_reduce_scatter(orc, gs, [0, 0, 16]), gs)
+    e4 = vnmse(O.ring_reduce_scatter(orc, gs, [0, 16, 0]), gs)
+    e2 = vnmse(O.ring_reduce_scatter(orc, gs, [16, 0, 0]), gs)
+    assert e8 < 1e-3 and e8 < e4 < e2
+    b4 = vnmse(O.butterfly_reduce_scatter(orc, gs, [0, 16, 0]), gs)
+    assert b4 < e4  # shorter aggregation paths re-quantize less often (Appendix B)
+
+
+def test_butterfly_two_workers_equals_ring_two_workers():
+    orc = O.Oracle(2, seed=11)
+    gs = grads(2, 4, 4)
+    ring = O.ring_reduce_scatter(orc, gs, [1, 2, 1])
+    bfly = O.butterfly_reduce_scatter(orc, gs, [1, 2, 1])
+    # ring: chunk c is compressed by worker c and ends at worker c+1; butterfly: worker w keeps
+    # chunk w and receives it compressed by w^1.  Same pairs, opposite roles.
+    chunks = O.split_bucket([1, 2, 1], 2)
+    for w in range(2):
+        sl = slice(w * 512, (w + 1) * 512)
+        msg = orc.compress(chunks[w], w ^ 1, gs[w ^ 1][sl])
+        assert np.array_equal(bfly[w], orc.decompress(chunks[w], msg, gs[w][sl]))
+    assert len(ring) == len(bfly) == 2
+
+
+def test_butterfly_four_workers_by_hand():
+    """n = 4: step 1 exchanges halves with w^2, step 2 quarters with w^1 (Appendix B)."""
+    n = 4
+    orc = O.Oracle(n, seed=13)
+    gs = grads(n, 8, 5)
+    ch = O.split_bucket([0, 8, 0], n)
+    m = 512
+
+    def sl(c):
+        return slice(c * m, (c + 1) * m)
+
+    out = O.butterfly_reduce_scatter(orc, gs, [0, 8, 0])
+    # worker 0 ends with chunk 0.  Step 1: worker 2 sends compress(chunks 0,1) to worker 0.
+    # Step 2: worker 1 (which got chunks 0,1 from worker 3) re-encodes chunk 0 for worker 0.
+    m_3to1 = orc.compress(ch[0], 3, gs[3][sl(0)])
+    m_1to0 = orc.dar_hop(ch[0], 1, m_3to1, gs[1][sl(0)])
+    m_2to0 = orc.compress(ch[0], 2, gs[2][sl(0)])
+    acc0 = orc.decompress(ch[0], m_2to0, gs[0][sl(0)])
+    want = orc.decompress(ch[0], m_1to0, acc0)
+    assert np.array_equal(out[0], want)
+
+
+def test_single_worker_passthrough():
+    orc = O.Oracle(1)
+    gs = grads(1, 2, 6)
+    out = O.ring_reduce_scatter(orc, gs, [0, 2, 0])
+    assert np.array_equal(out[0], gs[0])
