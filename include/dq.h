@@ -1,0 +1,148 @@
+/*
+ * dq.h -- C ABI of the MI355X (gfx950) hot path of DynamiQ's compressed multi-hop
+ * all-reduce (arxiv 2602.08923): first-hop compress, the fused
+ * decompress-accumulate-recompress (DAR) hop, decompress(+accumulate), a driver that
+ * replays ring / butterfly reduce-scatter hops for N simulated workers inside one
+ * GPU's HBM, and the same three calls for the OCP-MX comparison codec.
+ *
+ * Conventions shared by every call
+ *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned
+ *     (DQ_EALIGN otherwise).  Descriptor structs (dq_config, dq_chunk, dq_replay_desc
+ *     and the arrays they point to) are HOST memory, read during the call only.
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
+ *     and return without synchronising; the library allocates device memory only in
+ *     dq_create / dq_replay_create and never per call.
+ *   - Errors are return codes only; on any error nothing has been enqueued.  Inputs
+ *     must be finite and partial sums must stay below the largest bf16; otherwise the
+ *     codes are unspecified (but no access leaves the buffers).
+ *   - The result of a call is a pure function of (config, chunk descriptor, rank,
+ *     input bytes): it does not depend on grid size, batching or call order.
+ *
+ * Data model (paper Section 5 "configuration", Section 3.5): entries come in groups of
+ * 16 sharing a u8 scale and super-groups (SG) of 256 = 16 groups sharing a bf16 scale and
+ * a code width of 2, 4 or 8 bits.  A chunk is a run of SGs already reordered by increasing
+ * width.  Packed chunk layout (structure of arrays, each array 16-byte aligned, SG order):
+ *   [2-bit codes, 64 B per SG][4-bit codes, 128 B per SG][8-bit codes, 256 B per SG]
+ *   [group scales, 16 u8 per SG][SG scales, one u16 bf16 pattern per SG], rounded up to 16 B.
+ * Entry k of an SG sits at bit offset k*b of the SG's code block (little-endian);
+ * code = sign << (b-1) | level index.
+ */
+#ifndef DQ_H_
+#define DQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dq_ctx dq_ctx;       /* opaque: level tables on the device + PRNG key */
+typedef struct dq_replay dq_replay; /* opaque: a prepared hop schedule */
+
+typedef enum { DQ_OK = 0, DQ_EINVAL = 1, DQ_EALIGN = 2, DQ_EUNSUPPORTED = 3, DQ_EHIP = 4 } dq_status;
+typedef enum { DQ_F32 = 0, DQ_BF16 = 1 } dq_dtype;
+typedef enum { DQ_DYNAMIQ = 0, DQ_MXFP8_E4M3 = 1, DQ_MXFP6_E3M2 = 2, DQ_MXFP4_E2M1 = 3 } dq_codec;
+typedef enum { DQ_RING = 0, DQ_BUTTERFLY = 1, DQ_CHAIN = 2 } dq_topology;
+
+typedef struct {
+  double g4, g8;      /* 1 + 2*eps^2 of the 4-bit and 8-bit level sets (Section 3.3); the
+                         paper does not print eps; 1.3 and 1.02 are this library's defaults */
+  uint64_t seed;      /* PRNG seed shared by all workers (Section 2.4) */
+  uint32_t round;     /* training round: a new round draws fresh random numbers */
+  uint32_t n_workers; /* n of the correlated rounding u_i = (pi_i + gamma_i)/n, 1..8192 */
+} dq_config;
+
+typedef struct {
+  uint64_t first_sg; /* global (post-reorder) index of the chunk's first SG; keys the PRNG */
+  uint32_t n_sg[3];  /* SGs at 2, 4, 8 bits, in this order */
+} dq_chunk;
+
+/* Build the level tables f(eps, r) of Section 3.3 and upload them.  DQ_EINVAL for a null
+ * pointer, n_workers outside 1..8192 or level sets that are not strictly increasing in
+ * binary32; DQ_EUNSUPPORTED if a level set is too fine for the kernels' search table. */
+dq_status dq_create(const dq_config *cfg, dq_ctx **out);
+void dq_destroy(dq_ctx *ctx);
+/* Start a new training round (changes the PRNG counter only). */
+dq_status dq_set_round(dq_ctx *ctx, uint32_t round);
+
+/* Bytes of the packed form of a chunk (pure; layout above). */
+size_t dq_packed_bytes(const dq_chunk *chunk);
+
+/* Leaf node of the aggregation topology (Section 3.4 "Fused kernels", kernel 1 of Section 4):
+ * quantize the local chunk.  local: chunk entries, contiguous, `dtype`.  rank: the worker
+ * doing the compression (0..n_workers-1).  packed_out: dq_packed_bytes(chunk) bytes. */
+dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const dq_chunk *chunk, uint32_t rank,
+                      void *packed_out, void *hip_stream);
+
+/* Internal node (kernel 3 of Section 4): decode the received partial sum, add the local
+ * slice, re-quantize; intermediates never leave registers.  packed_out may alias packed_in. */
+dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const dq_chunk *chunk,
+                     uint32_t rank, void *packed_out, void *hip_stream);
+
+/* Sink of the reduce-scatter, non-last parents of a butterfly node, all-gather receivers
+ * (kernels 2 and 4 of Section 4): out = decode(packed_in) [+ local].  local_or_null may be
+ * NULL (then dtype is ignored); out (fp32, one per entry) may alias an fp32 local. */
+dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
+                        const dq_chunk *chunk, float *out, void *hip_stream);
+
+/* ---- OCP Microscaling comparison codec (blocks of 32, E8M0 shared scale, elements
+ * E4M3 / E3M2 / E2M1, round-to-nearest-even, saturating; the formats the paper compares
+ * against in Section 5 "Baseline compression schemes").  n_entries must be a multiple of
+ * 256.  Packed layout: [element codes: 32 / 24 / 16 B per block][one E8M0 byte per block],
+ * each array 16-byte aligned.  MXFP6 packs 4 codes into 3 bytes, little-endian. */
+size_t dq_mx_packed_bytes(dq_codec fmt, uint64_t n_entries);
+dq_status dq_mx_compress(dq_codec fmt, const void *local, dq_dtype dtype, uint64_t n_entries, void *packed_out,
+                         void *hip_stream);
+dq_status dq_mx_dar_hop(dq_codec fmt, const void *packed_in, const void *local, dq_dtype dtype, uint64_t n_entries,
+                        void *packed_out, void *hip_stream);
+dq_status dq_mx_decompress(dq_codec fmt, const void *packed_in, const void *local_or_null, dq_dtype dtype,
+                           uint64_t n_entries, float *out, void *hip_stream);
+
+/* ---- Hop replay (Section 3.4 "Reduce-scatter", Appendix B): N simulated workers whose
+ * reordered gradients all live in this GPU's HBM; a transfer between workers is a pointer
+ * hand-off.  One kernel launch per schedule step covers every (worker, chunk) job of that
+ * step.  DQ_RING / DQ_BUTTERFLY: worker_grads[w] holds worker w's n_buckets buckets back to
+ * back, each n_sg_bucket SGs (a multiple of n_workers; butterfly needs a power of two);
+ * bucket b uses widths n_sg_by_width[3*b..3*b+2] and global SG indices starting at
+ * first_sg + b*n_sg_bucket; `out` receives the reduced buckets (the SUM over workers, fp32,
+ * same order as the inputs).  DQ_CHAIN: the path of one ring chunk: worker_grads[i] is
+ * worker i's slice of that chunk (n_buckets = 1, n_sg_bucket = the chunk's SG count); worker
+ * 0 compresses, workers 1..n-2 run DAR, worker n-1 decompresses and adds.
+ * codec: DQ_DYNAMIQ or an MX format (then n_sg_by_width is ignored). */
+typedef struct {
+  dq_topology topology;
+  dq_codec codec;
+  dq_dtype dtype;
+  uint32_t n_buckets;
+  uint64_t n_sg_bucket;
+  const uint32_t *n_sg_by_width; /* host, [n_buckets][3] */
+  uint64_t first_sg;
+} dq_replay_desc;
+
+/* Device scratch the replay needs (job tables, packed messages, fp32 keep-buffers). */
+size_t dq_replay_scratch_bytes(const dq_ctx *ctx, const dq_replay_desc *desc);
+/* Build the schedule and upload its job tables into `scratch` (synchronous).
+ * worker_grads: host array of n_workers device pointers.  scratch and out must stay valid
+ * until dq_replay_destroy. */
+dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *const *worker_grads, void *scratch,
+                           size_t scratch_bytes, float *out, dq_replay **plan);
+uint32_t dq_replay_n_steps(const dq_replay *plan);
+/* Enqueue every step of the schedule.  step_ms: NULL, or a host array of n_steps floats that
+ * receives each step's duration measured with HIP events on `hip_stream` (this variant
+ * synchronises the stream before returning). */
+dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream);
+/* Per step: kind (0 compress, 1 DAR, 2 decompress-accumulate, 3 DAR + decompress-accumulate
+ * in one launch) and the entries it processes, for throughput accounting. */
+dq_status dq_replay_step_info(const dq_replay *plan, uint32_t step, uint32_t *kind, uint64_t *entries_dar,
+                              uint64_t *entries_other);
+void dq_replay_destroy(dq_replay *plan);
+
+const char *dq_status_str(dq_status s);
+/* Last HIP error string seen by this library on the calling thread (for DQ_EHIP). */
+const char *dq_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DQ_H_ */

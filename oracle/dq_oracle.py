@@ -317,3 +317,64 @@ def butterfly_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None):
         assert lo[w] == w and ln[w] == 1
         out.append(orc.decompress(chunks[w], inbox[w].pop(w), acc[w][w]))
     return out
+
+
+# ------------------------------------------------------------------ MX comparison codec
+
+MXFP8, MXFP6, MXFP4 = 1, 2, 3
+MX_CODE_BITS = {1: 8, 2: 6, 3: 4}
+
+
+def mx_packed_bytes(fmt, n):
+    return lib().mxo_packed_bytes(fmt, n)
+
+
+def mx_compress(fmt, local):
+    n = local.size
+    out = np.zeros(mx_packed_bytes(fmt, n), np.uint8)
+    lib().mxo_compress(fmt, n, _p(local), _dtype_code(local), _p(out))
+    return out
+
+
+def mx_dar_hop(fmt, packed_in, local):
+    n = local.size
+    out = np.zeros(mx_packed_bytes(fmt, n), np.uint8)
+    lib().mxo_dar_hop(fmt, n, _p(packed_in), _p(local), _dtype_code(local), _p(out))
+    return out
+
+
+def mx_decompress(fmt, packed_in, n, local=None):
+    out = np.empty(n, np.float32)
+    lib().mxo_decompress(fmt, n, _p(packed_in), None if local is None else _p(local),
+                         0 if local is None else _dtype_code(local), _p(out))
+    return out
+
+
+def mx_encode_elem(fmt, v, e):
+    return lib().mxo_encode_elem(fmt, float(v), int(e))
+
+
+def mx_decode_elem(fmt, code, e):
+    return lib().mxo_decode_elem(fmt, int(code), int(e))
+
+
+def mx_block_scale(fmt, m):
+    return lib().mxo_block_scale(fmt, float(m))
+
+
+def mx_ring_reduce_scatter(fmt, grads, trace=None):
+    """The ring path of ring_reduce_scatter with the MX codec: n equal chunks."""
+    n = len(grads)
+    m = grads[0].size // n
+    out = []
+    for c in range(n):
+        sl = slice(c * m, (c + 1) * m)
+        msg = mx_compress(fmt, np.ascontiguousarray(grads[c][sl]))
+        if trace is not None:
+            trace[(0, c)] = msg
+        for t in range(1, n - 1):
+            msg = mx_dar_hop(fmt, msg, np.ascontiguousarray(grads[(c + t) % n][sl]))
+            if trace is not None:
+                trace[(t, c)] = msg
+        out.append(mx_decompress(fmt, msg, m, np.ascontiguousarray(grads[(c + n - 1) % n][sl])))
+    return out

@@ -1,0 +1,270 @@
+"""Thin ctypes binding of libdq.so: same names as include/dq.h, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the path runs in the HIP
+kernels.  There is no fallback: if the library is not built, or no GPU is present when a
+compute call is made, the call raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdq.so")
+
+DQ_OK, DQ_EINVAL, DQ_EALIGN, DQ_EUNSUPPORTED, DQ_EHIP = range(5)
+DQ_F32, DQ_BF16 = 0, 1
+DQ_DYNAMIQ, DQ_MXFP8_E4M3, DQ_MXFP6_E3M2, DQ_MXFP4_E2M1 = 0, 1, 2, 3
+DQ_RING, DQ_BUTTERFLY, DQ_CHAIN = 0, 1, 2
+
+EXPORTS = [
+    "dq_create", "dq_destroy", "dq_set_round", "dq_packed_bytes", "dq_compress", "dq_dar_hop", "dq_decompress",
+    "dq_mx_packed_bytes", "dq_mx_compress", "dq_mx_dar_hop", "dq_mx_decompress",
+    "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_step_info",
+    "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
+]
+
+
+class DqError(RuntimeError):
+    pass
+
+
+class Config(C.Structure):
+    _fields_ = [("g4", C.c_double), ("g8", C.c_double), ("seed", C.c_uint64), ("round", C.c_uint32),
+                ("n_workers", C.c_uint32)]
+
+
+class Chunk(C.Structure):
+    _fields_ = [("first_sg", C.c_uint64), ("n_sg", C.c_uint32 * 3)]
+
+
+class ReplayDesc(C.Structure):
+    _fields_ = [("topology", C.c_int), ("codec", C.c_int), ("dtype", C.c_int), ("n_buckets", C.c_uint32),
+                ("n_sg_bucket", C.c_uint64), ("n_sg_by_width", C.POINTER(C.c_uint32)), ("first_sg", C.c_uint64)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libdq.so (built in-tree by build.py).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise DqError(f"{LIB_PATH} is not built: run `python -m paper_2602_08923_amd.build` "
+                          "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, u32, u64, i = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
+        L.dq_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+        L.dq_destroy.argtypes = [vp]
+        L.dq_destroy.restype = None
+        L.dq_set_round.argtypes = [vp, u32]
+        L.dq_packed_bytes.argtypes = [C.POINTER(Chunk)]
+        L.dq_packed_bytes.restype = C.c_size_t
+        L.dq_compress.argtypes = [vp, vp, i, C.POINTER(Chunk), u32, vp, vp]
+        L.dq_dar_hop.argtypes = [vp, vp, vp, i, C.POINTER(Chunk), u32, vp, vp]
+        L.dq_decompress.argtypes = [vp, vp, vp, i, C.POINTER(Chunk), vp, vp]
+        L.dq_status_str.argtypes = [i]
+        L.dq_status_str.restype = C.c_char_p
+        L.dq_last_hip_error.restype = C.c_char_p
+        L.dq_mx_packed_bytes.argtypes = [i, u64]
+        L.dq_mx_packed_bytes.restype = C.c_size_t
+        L.dq_mx_compress.argtypes = [i, vp, i, u64, vp, vp]
+        L.dq_mx_dar_hop.argtypes = [i, vp, vp, i, u64, vp, vp]
+        L.dq_mx_decompress.argtypes = [i, vp, vp, i, u64, vp, vp]
+        L.dq_replay_scratch_bytes.argtypes = [vp, C.POINTER(ReplayDesc)]
+        L.dq_replay_scratch_bytes.restype = C.c_size_t
+        L.dq_replay_create.argtypes = [vp, C.POINTER(ReplayDesc), C.POINTER(vp), vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.dq_replay_n_steps.argtypes = [vp]
+        L.dq_replay_n_steps.restype = u32
+        L.dq_replay_run.argtypes = [vp, C.POINTER(C.c_float), vp]
+        L.dq_replay_step_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u64)]
+        L.dq_replay_destroy.argtypes = [vp]
+        L.dq_replay_destroy.restype = None
+        _lib = L
+    return _lib
+
+
+def _check(st):
+    if st != DQ_OK:
+        L = lib()
+        msg = L.dq_status_str(st).decode()
+        if st == DQ_EHIP:
+            msg += ": " + L.dq_last_hip_error().decode()
+        raise DqError(msg)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise DqError("tensors must be contiguous CUDA tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _dtype(t):
+    if t.dtype == torch.float32:
+        return DQ_F32
+    if t.dtype == torch.bfloat16:
+        return DQ_BF16
+    raise DqError("local slices must be float32 or bfloat16")
+
+
+def make_chunk(first_sg, n_sg):
+    ch = Chunk()
+    ch.first_sg = int(first_sg)
+    for k in range(3):
+        ch.n_sg[k] = int(n_sg[k])
+    return ch
+
+
+def dq_packed_bytes(chunk):
+    return lib().dq_packed_bytes(C.byref(chunk))
+
+
+def _entries(chunk):
+    return (chunk.n_sg[0] + chunk.n_sg[1] + chunk.n_sg[2]) * 256
+
+
+class Context:
+    """dq_ctx: level tables on the device + PRNG key (seed, round) + worker count."""
+
+    def __init__(self, n_workers, seed=0, round=0, g4=1.3, g8=1.02):
+        self.h = C.c_void_p()
+        self.n_workers = n_workers
+        cfg = Config(g4, g8, seed, round, n_workers)
+        _check(lib().dq_create(C.byref(cfg), C.byref(self.h)))
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().dq_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def set_round(self, r):
+        _check(lib().dq_set_round(self.h, r))
+
+    def dq_compress(self, local, chunk, rank, packed_out=None):
+        if local.numel() != _entries(chunk):
+            raise DqError("local slice does not match the chunk")
+        if packed_out is None:
+            packed_out = torch.zeros(dq_packed_bytes(chunk), dtype=torch.uint8, device=local.device)
+        if packed_out.numel() < dq_packed_bytes(chunk):
+            raise DqError("packed_out too small")
+        _check(lib().dq_compress(self.h, _ptr(local), _dtype(local), C.byref(chunk), rank, _ptr(packed_out), _stream()))
+        return packed_out
+
+    def dq_dar_hop(self, packed_in, local, chunk, rank, packed_out=None):
+        if local.numel() != _entries(chunk) or packed_in.numel() < dq_packed_bytes(chunk):
+            raise DqError("buffers do not match the chunk")
+        if packed_out is None:
+            packed_out = torch.zeros(dq_packed_bytes(chunk), dtype=torch.uint8, device=local.device)
+        if packed_out.numel() < dq_packed_bytes(chunk):
+            raise DqError("packed_out too small")
+        _check(lib().dq_dar_hop(self.h, _ptr(packed_in), _ptr(local), _dtype(local), C.byref(chunk), rank,
+                                _ptr(packed_out), _stream()))
+        return packed_out
+
+    def dq_decompress(self, packed_in, chunk, local=None, out=None):
+        if packed_in.numel() < dq_packed_bytes(chunk) or (local is not None and local.numel() != _entries(chunk)):
+            raise DqError("buffers do not match the chunk")
+        if out is None:
+            out = torch.empty(_entries(chunk), dtype=torch.float32, device=packed_in.device)
+        if out.numel() != _entries(chunk) or out.dtype != torch.float32:
+            raise DqError("out must be float32 with one element per entry")
+        _check(lib().dq_decompress(self.h, _ptr(packed_in), _ptr(local), 0 if local is None else _dtype(local),
+                                   C.byref(chunk), _ptr(out), _stream()))
+        return out
+
+
+# ---- MX comparison codec -------------------------------------------------------------
+
+def dq_mx_packed_bytes(fmt, n_entries):
+    return lib().dq_mx_packed_bytes(fmt, n_entries)
+
+
+def dq_mx_compress(fmt, local, packed_out=None):
+    n = local.numel()
+    if packed_out is None:
+        packed_out = torch.zeros(dq_mx_packed_bytes(fmt, n), dtype=torch.uint8, device=local.device)
+    _check(lib().dq_mx_compress(fmt, _ptr(local), _dtype(local), n, _ptr(packed_out), _stream()))
+    return packed_out
+
+
+def dq_mx_dar_hop(fmt, packed_in, local, packed_out=None):
+    n = local.numel()
+    if packed_in.numel() < dq_mx_packed_bytes(fmt, n):
+        raise DqError("packed_in too small")
+    if packed_out is None:
+        packed_out = torch.zeros(dq_mx_packed_bytes(fmt, n), dtype=torch.uint8, device=local.device)
+    _check(lib().dq_mx_dar_hop(fmt, _ptr(packed_in), _ptr(local), _dtype(local), n, _ptr(packed_out), _stream()))
+    return packed_out
+
+
+def dq_mx_decompress(fmt, packed_in, n_entries, local=None, out=None):
+    if packed_in.numel() < dq_mx_packed_bytes(fmt, n_entries):
+        raise DqError("packed_in too small")
+    if out is None:
+        out = torch.empty(n_entries, dtype=torch.float32, device=packed_in.device)
+    _check(lib().dq_mx_decompress(fmt, _ptr(packed_in), _ptr(local), 0 if local is None else _dtype(local), n_entries,
+                                  _ptr(out), _stream()))
+    return out
+
+
+# ---- hop replay ------------------------------------------------------------------------
+
+class Replay:
+    """dq_replay: a prepared ring / butterfly / chain schedule over N simulated workers."""
+
+    def __init__(self, ctx, topology, codec, worker_grads, n_sg_bucket, n_sg_by_width=None, n_buckets=1, first_sg=0):
+        self.ctx = ctx
+        self.grads = list(worker_grads)
+        dev = self.grads[0].device
+        n = len(self.grads)
+        flat = (C.c_uint32 * (3 * n_buckets))()
+        if n_sg_by_width is not None:
+            for b in range(n_buckets):
+                for k in range(3):
+                    flat[3 * b + k] = int(n_sg_by_width[b][k])
+        self._widths = flat
+        desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg)
+        self.desc = desc
+        entries = n_sg_bucket * 256 * n_buckets
+        for g in self.grads:
+            if g.numel() != entries or _dtype(g) != desc.dtype:
+                raise DqError("every worker gradient must hold n_buckets * n_sg_bucket * 256 entries of one dtype")
+        nbytes = lib().dq_replay_scratch_bytes(ctx.h, C.byref(desc))
+        if nbytes == 0:
+            raise DqError("invalid replay description")
+        self.scratch = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        self.out = torch.empty(entries, dtype=torch.float32, device=dev)
+        ptrs = (C.c_void_p * n)(*[g.data_ptr() for g in self.grads])
+        self.h = C.c_void_p()
+        _check(lib().dq_replay_create(ctx.h, C.byref(desc), ptrs, _ptr(self.scratch), nbytes, _ptr(self.out),
+                                      C.byref(self.h)))
+        self.n_steps = lib().dq_replay_n_steps(self.h)
+
+    def run(self, timed=False):
+        if timed:
+            ms = (C.c_float * self.n_steps)()
+            _check(lib().dq_replay_run(self.h, ms, _stream()))
+            return list(ms)
+        _check(lib().dq_replay_run(self.h, None, _stream()))
+        return None
+
+    def step_info(self, step):
+        kind, a, b = C.c_uint32(), C.c_uint64(), C.c_uint64()
+        _check(lib().dq_replay_step_info(self.h, step, C.byref(kind), C.byref(a), C.byref(b)))
+        return kind.value, a.value, b.value
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().dq_replay_destroy(self.h)
+            self.h = None
+
+    __del__ = close

@@ -1,0 +1,247 @@
+// Host side of libdq: context (level tables, search tables, PRNG key), argument checks and
+// the three single-chunk entry points declared in dq.h.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "dq_device.h"
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+bool hip_ok(hipError_t e) {
+  if (e == hipSuccess) return true;
+  g_hip_error = hipGetErrorString(e);
+  return false;
+}
+
+uint32_t fbits(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  return u;
+}
+
+// f(eps, r) = (g^r - 1)/(g^R - 1), g = 1 + 2 eps^2, r = 0..R  (Section 3.3), powers by
+// repeated multiplication in double, ends pinned to 0 and 1.
+bool build_levels(int R, double g, std::vector<float> &T, std::vector<float> &D) {
+  T.assign(R + 1, 0.0f);
+  D.assign(R + 1, 0.0f);
+  if (R == 1) {
+    T[1] = 1.0f;
+  } else {
+    std::vector<double> pw(R + 1);
+    pw[0] = 1.0;
+    for (int r = 1; r <= R; ++r) pw[r] = pw[r - 1] * g;
+    const double den = pw[R] - 1.0;
+    for (int r = 1; r < R; ++r) {
+      const double q = (pw[r] - 1.0) / den;
+      T[r] = (float)q;
+    }
+    T[R] = 1.0f;
+  }
+  for (int r = 0; r < R; ++r) {
+    D[r] = T[r + 1] - T[r];
+    if (!(D[r] > 0.0f)) return false;
+  }
+  D[R] = 0.0f;  // at the top level T + u*D = 1 is never below x'
+  return true;
+}
+
+// Search table over q = round(x * 2^m): the closed bin [(q-1/2)/2^m, (q+1/2)/2^m] holds at
+// most one level boundary, so the level at or below x is rc(q) or rc(q)+1.
+bool build_search(const std::vector<float> &T, int R, int *m_out, std::vector<uint32_t> &lut) {
+  float min_gap = 1.0f;
+  for (int r = 0; r < R; ++r) min_gap = fminf(min_gap, T[r + 1] - T[r]);
+  for (int m = 1; m <= 12; ++m) {
+    const double w = ldexp(1.0, -m);
+    if (!(w < (double)min_gap)) continue;
+    const int n = (1 << m) + 1;
+    lut.assign(2 * (size_t)n, 0u);
+    bool ok = true;
+    for (int q = 0; q < n && ok; ++q) {
+      const double lo = fmax(0.0, ((double)q - 0.5) * w), hi = fmin(1.0, ((double)q + 0.5) * w);
+      int rc = 0;
+      while (rc < R && (double)T[rc + 1] <= lo) ++rc;
+      if (rc > R - 1) ok = false;
+      else if (rc + 2 <= R && !((double)T[rc + 2] > hi)) ok = false;
+      else {
+        lut[2 * q] = fbits(T[rc + 1]);
+        lut[2 * q + 1] = (uint32_t)rc;
+      }
+    }
+    if (ok) {
+      *m_out = m;
+      return true;
+    }
+  }
+  return false;
+}
+
+void append_aligned(std::vector<uint32_t> &blob, const std::vector<uint32_t> &part, uint32_t *off) {
+  while (blob.size() % 4) blob.push_back(0);
+  *off = (uint32_t)blob.size();
+  blob.insert(blob.end(), part.begin(), part.end());
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint64_t chunk_sgs(const dq_chunk *ch) { return (uint64_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2]; }
+
+dq_status check_chunk(const dq_ctx *ctx, const dq_chunk *ch, uint32_t rank) {
+  if (!ctx || !ch) return DQ_EINVAL;
+  const uint64_t n = chunk_sgs(ch);
+  if (n >= (1ull << 31)) return DQ_EUNSUPPORTED;
+  if (rank >= ctx->cfg.n_workers) return DQ_EINVAL;
+  if (ch->first_sg + n < ch->first_sg || (ch->first_sg + n) >> 59) return DQ_EINVAL;  // 16*index must fit 64 bits
+  return DQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dq_status_str(dq_status s) {
+  switch (s) {
+    case DQ_OK: return "ok";
+    case DQ_EINVAL: return "invalid argument";
+    case DQ_EALIGN: return "pointer not 16-byte aligned";
+    case DQ_EUNSUPPORTED: return "unsupported configuration";
+    case DQ_EHIP: return "HIP error";
+  }
+  return "unknown";
+}
+
+const char *dq_last_hip_error(void) { return g_hip_error.c_str(); }
+
+dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
+  if (!cfg || !out) return DQ_EINVAL;
+  *out = nullptr;
+  if (cfg->n_workers < 1 || cfg->n_workers > 8192) return DQ_EINVAL;
+  if (!(cfg->g4 > 1.0) || !(cfg->g8 > 1.0) || !isfinite(cfg->g4) || !isfinite(cfg->g8)) return DQ_EINVAL;
+
+  const int Rs[3] = {1, 7, 127};
+  const double gs[3] = {2.0, cfg->g4, cfg->g8};
+  std::vector<uint32_t> blob;
+  dq::Params P;
+  memset(&P, 0, sizeof(P));
+  for (int wi = 0; wi < 3; ++wi) {
+    const int R = Rs[wi], b = 2 << wi;  // widths 2, 4, 8
+    std::vector<float> T, D;
+    if (!build_levels(R, gs[wi], T, D)) return DQ_EINVAL;
+    // signed decode table indexed by the whole code: sign << (b-1) | r
+    std::vector<uint32_t> dec((size_t)1 << b);
+    for (int code = 0; code < (1 << b); ++code) {
+      const float t = T[code & R];
+      dec[code] = fbits((code >> (b - 1)) ? -t : t);
+    }
+    append_aligned(blob, dec, &P.off_dec[wi]);
+    if (wi == 0) continue;  // levels {0,1}: the kernels need no search
+    int m = 0;
+    std::vector<uint32_t> lut;
+    if (!build_search(T, R, &m, lut)) return DQ_EUNSUPPORTED;
+    append_aligned(blob, lut, &P.off_lut[wi]);
+    std::vector<uint32_t> tab(2 * (size_t)(R + 1));
+    for (int r = 0; r <= R; ++r) {
+      tab[2 * r] = fbits(T[r]);
+      tab[2 * r + 1] = fbits(D[r]);
+    }
+    append_aligned(blob, tab, &P.off_tab[wi]);
+    P.magic[wi] = (float)ldexp(1.0, 23 - m);
+  }
+  while (blob.size() % 4) blob.push_back(0);
+  if (blob.size() * 4 > 60 * 1024) return DQ_EUNSUPPORTED;
+
+  dq_ctx *ctx = new (std::nothrow) dq_ctx;
+  if (!ctx) return DQ_EINVAL;
+  ctx->cfg = *cfg;
+  ctx->blob_dev = nullptr;
+  hipDeviceProp_t prop;
+  if (!hip_ok(hipGetDevice(&ctx->device)) || !hip_ok(hipGetDeviceProperties(&prop, ctx->device)) ||
+      !hip_ok(hipMalloc(&ctx->blob_dev, blob.size() * 4)) ||
+      !hip_ok(hipMemcpy(ctx->blob_dev, blob.data(), blob.size() * 4, hipMemcpyHostToDevice))) {
+    if (ctx->blob_dev) (void)hipFree(ctx->blob_dev);
+    delete ctx;
+    return DQ_EHIP;
+  }
+  ctx->n_cu = (uint32_t)prop.multiProcessorCount;
+  P.blob = ctx->blob_dev;
+  P.blob_dwords = (uint32_t)blob.size();
+  P.key0 = (uint32_t)cfg->seed;
+  P.key1 = (uint32_t)(cfg->seed >> 32);
+  P.round = cfg->round;
+  P.n_workers = cfg->n_workers;
+  P.n_mask = (cfg->n_workers & (cfg->n_workers - 1)) == 0 ? cfg->n_workers - 1 : 0xFFFFFFFFu;
+  P.inv_n = 1.0f / (float)cfg->n_workers;
+  P.s_n = P.inv_n * (1.0f / 256.0f);
+  ctx->params = P;
+  *out = ctx;
+  return DQ_OK;
+}
+
+void dq_destroy(dq_ctx *ctx) {
+  if (!ctx) return;
+  if (ctx->blob_dev) (void)hipFree(ctx->blob_dev);
+  delete ctx;
+}
+
+dq_status dq_set_round(dq_ctx *ctx, uint32_t round) {
+  if (!ctx) return DQ_EINVAL;
+  ctx->cfg.round = round;
+  ctx->params.round = round;
+  return DQ_OK;
+}
+
+size_t dq_packed_bytes(const dq_chunk *ch) {
+  if (!ch) return 0;
+  const size_t n = (size_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2];
+  const size_t sz = 64 * (size_t)ch->n_sg[0] + 128 * (size_t)ch->n_sg[1] + 256 * (size_t)ch->n_sg[2] + 18 * n;
+  return (sz + 15) & ~(size_t)15;
+}
+
+dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const dq_chunk *chunk, uint32_t rank,
+                      void *packed_out, void *hip_stream) {
+  dq_status st = check_chunk(ctx, chunk, rank);
+  if (st != DQ_OK) return st;
+  if (chunk_sgs(chunk) == 0) return DQ_OK;  // nothing to do
+  if (!local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
+  if (!aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
+  dq::Job j{nullptr, local, packed_out, chunk->first_sg, {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, rank};
+  return hip_ok(dq::launch_one(dq::kCompress, dtype, true, j, ctx->params, ctx->n_cu, (hipStream_t)hip_stream))
+             ? DQ_OK
+             : DQ_EHIP;
+}
+
+dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const dq_chunk *chunk,
+                     uint32_t rank, void *packed_out, void *hip_stream) {
+  dq_status st = check_chunk(ctx, chunk, rank);
+  if (st != DQ_OK) return st;
+  if (chunk_sgs(chunk) == 0) return DQ_OK;
+  if (!packed_in || !local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
+  if (!aligned16(packed_in) || !aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
+  dq::Job j{(const uint8_t *)packed_in, local, packed_out, chunk->first_sg,
+            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, rank};
+  return hip_ok(dq::launch_one(dq::kDar, dtype, true, j, ctx->params, ctx->n_cu, (hipStream_t)hip_stream)) ? DQ_OK
+                                                                                                          : DQ_EHIP;
+}
+
+dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
+                        const dq_chunk *chunk, float *out, void *hip_stream) {
+  dq_status st = check_chunk(ctx, chunk, 0);
+  if (st != DQ_OK) return st;
+  if (chunk_sgs(chunk) == 0) return DQ_OK;
+  if (!packed_in || !out) return DQ_EINVAL;
+  if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
+  if (!aligned16(packed_in) || !aligned16(out) || !aligned16(local_or_null)) return DQ_EALIGN;
+  dq::Job j{(const uint8_t *)packed_in, local_or_null, out, chunk->first_sg,
+            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, 0};
+  return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->n_cu,
+                               (hipStream_t)hip_stream))
+             ? DQ_OK
+             : DQ_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Internal declarations shared by the HIP translation units of libdq (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dq.h"
+
+namespace dq {
+
+constexpr int kGroup = 16;        // entries per group (Section 5 "configuration")
+constexpr int kSG = 256;          // entries per super-group
+constexpr int kGroupsPerSG = 16;
+constexpr int kWaveSGs = 4;       // one wave64 = 64 groups = 4 super-groups per tile
+constexpr int kBlockThreads = 256;
+constexpr int kBlockWaves = kBlockThreads / 64;
+
+// One unit of work: a chunk of one simulated worker.
+struct Job {
+  const uint8_t *in;   // packed partial sum (DAR, decompress) or nullptr (compress)
+  const void *local;   // local slice, may be nullptr for decompress
+  void *out;           // packed (compress, DAR) or fp32 (decompress)
+  uint64_t first_sg;   // global index of the chunk's first super-group
+  uint32_t n_sg[3];    // super-groups at 2, 4, 8 bits
+  uint32_t rank;       // worker doing the compression (feeds the random streams)
+};
+
+// Everything the kernels need besides the job: PRNG key, worker count, table blob.
+struct Params {
+  const uint32_t *blob;  // device copy of the table blob, blob_dwords long (multiple of 4)
+  uint32_t blob_dwords;
+  uint32_t off_dec[3];   // dword offsets: signed decode table, 2^b floats
+  uint32_t off_lut[3];   // search table: (2^m + 1) pairs {next level, candidate index}
+  uint32_t off_tab[3];   // level/gap pairs {T[r], D[r]}, r = 0..R (D[R] = 0)
+  float magic[3];        // 2^(23-m): adding it leaves round(x * 2^m) in the low mantissa bits
+  uint32_t key0, key1, round;
+  uint32_t n_workers;
+  uint32_t n_mask;       // n-1 if n is a power of two, else 0xFFFFFFFF (meaning: use %)
+  float inv_n, s_n;
+};
+
+enum Kind { kCompress = 0, kDar = 1, kDecompress = 2 };
+
+// kernel launchers (dq_kernels.hip); grid_x = 0 lets the launcher choose
+hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t n_cu,
+                      hipStream_t stream);
+hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, const Job *jobs_dev, uint32_t n_jobs,
+                        uint32_t max_tiles_per_job, const Params &p, uint32_t n_cu, hipStream_t stream);
+
+struct MxJob {
+  const uint8_t *in;
+  const void *local;
+  void *out;
+  uint64_t n_entries;
+};
+hipError_t mx_launch_one(Kind kind, dq_codec fmt, dq_dtype dtype, bool has_local, const MxJob &job, uint32_t n_cu,
+                         hipStream_t stream);
+hipError_t mx_launch_batch(Kind kind, dq_codec fmt, dq_dtype dtype, bool has_local, const MxJob *jobs_dev,
+                           uint32_t n_jobs, uint64_t max_entries_per_job, uint32_t n_cu, hipStream_t stream);
+
+}  // namespace dq
+
+// context internals shared between dq_api.cpp and dq_replay.cpp
+struct dq_ctx {
+  dq_config cfg;
+  dq::Params params;
+  uint32_t *blob_dev;
+  uint32_t n_cu;
+  int device;
+};

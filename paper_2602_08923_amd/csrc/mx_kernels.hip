@@ -1,0 +1,284 @@
+// OCP Microscaling (MXFP8 E4M3 / MXFP6 E3M2 / MXFP4 E2M1) versions of compress, DAR and
+// decompress(+accumulate) -- the comparison codec of the paper's evaluation (Section 5,
+// "Baseline compression schemes") run in the same hop loop.  Conversion per the OCP MX v1.0
+// specification: shared exponent floor(log2 max|v|) - emax_elem stored as an E8M0 byte,
+// elements rounded to nearest-even and clamped to the largest normal.
+//
+// Mapping: one lane owns one block of 32 entries (its maximum is in-lane); a wave64 covers
+// 2048 entries per tile.  Element conversion is pure integer/exponent arithmetic on the
+// binary32 pattern, so it is exact and identical for every launch shape.
+#include "dq_device.h"
+
+namespace dq {
+namespace {
+
+struct NoLocal {};
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+template <int FMT>
+struct Fmt;
+template <>
+struct Fmt<DQ_MXFP8_E4M3> { static constexpr int ebits = 4, mbits = 3, bias = 7, emax = 8, cb = 8; };
+template <>
+struct Fmt<DQ_MXFP6_E3M2> { static constexpr int ebits = 3, mbits = 2, bias = 3, emax = 4, cb = 6; };
+template <>
+struct Fmt<DQ_MXFP4_E2M1> { static constexpr int ebits = 2, mbits = 1, bias = 1, emax = 2, cb = 4; };
+
+// magnitude code (exponent field | mantissa) of a >= 0 in element format F, RNE, saturating
+template <typename F>
+__device__ __forceinline__ uint32_t quantize_mag(float a) {
+  constexpr int drop = 23 - F::mbits;
+  constexpr int emin = 1 - F::bias;
+  // largest normal: exponent field all ones (E4M3 keeps mantissa 111 for NaN), mantissa all ones
+  constexpr uint32_t max_code = F::ebits == 4 ? 0x7Eu : ((1u << (F::ebits + F::mbits)) - 1u);
+  // below 2^emin the quantum is fixed at 2^(emin-mbits): adding 2^(23+emin-mbits) leaves the
+  // count of quanta (rounded to nearest even) in the low mantissa bits
+  const float c_sub = u2f((uint32_t)(127 + 23 + emin - F::mbits) << 23);
+  const uint32_t sub = f2u(a + c_sub) - f2u(c_sub);
+  // at or above 2^emin: round the mantissa to mbits bits, ties to even, on the bit pattern
+  const uint32_t b = f2u(a);
+  const uint32_t rounded = (b + ((b >> drop) & 1u) + ((1u << (drop - 1)) - 1u)) >> drop;
+  const uint32_t nrm = rounded - ((uint32_t)(127 - F::bias) << F::mbits);
+  const uint32_t code = (a < u2f((uint32_t)(127 + emin) << 23)) ? sub : nrm;
+  return code < max_code ? code : max_code;
+}
+
+template <typename LT>
+__device__ __forceinline__ void load_local32(const void *base, size_t first, float (&v)[32]) {
+  if constexpr (sizeof(LT) == 4) {
+    const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + first);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float4 t = p[i];
+      v[4 * i] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
+    }
+  } else {
+    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + first);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 t = p[i];
+      const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[8 * i + 2 * j] = u2f(w[j] << 16);
+        v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
+      }
+    }
+  }
+}
+
+template <int FMT, Kind KIND, typename LT>
+__device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t n_blocks) {
+  using F = Fmt<FMT>;
+  constexpr bool kHasLocal = !__is_same(LT, NoLocal);
+  constexpr int cw = F::cb;  // dwords of codes per block (cb*32/32)
+  const size_t scale_off = (size_t)n_blocks * (cw * 4);
+  float v[32];
+  if constexpr (kHasLocal) load_local32<LT>(job.local, (size_t)bi * 32, v);
+
+  if constexpr (KIND != kCompress) {
+    uint32_t w[cw + 1];
+    const uint8_t *src = job.in + (size_t)bi * (cw * 4);
+    if constexpr (cw == 8) {
+      const uint4 a = *reinterpret_cast<const uint4 *>(src), b = *reinterpret_cast<const uint4 *>(src + 16);
+      w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+    } else if constexpr (cw == 6) {
+      const uint2 a = *reinterpret_cast<const uint2 *>(src), b = *reinterpret_cast<const uint2 *>(src + 8),
+                  c = *reinterpret_cast<const uint2 *>(src + 16);
+      w[0] = a.x; w[1] = a.y; w[2] = b.x; w[3] = b.y; w[4] = c.x; w[5] = c.y;
+    } else {
+      const uint4 a = *reinterpret_cast<const uint4 *>(src);
+      w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+    }
+    w[cw] = 0;
+    const uint32_t e = job.in[scale_off + bi];
+    const float X = e ? u2f(e << 23) : u2f(0x00400000u);  // 2^(e-127); e = 0 is a binary32 subnormal
+    const float unbias = u2f((uint32_t)(254 - F::bias) << 23);  // 2^(127-bias)
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      const int bit = k * F::cb;
+      const uint64_t pair = (uint64_t)w[bit >> 5] | ((uint64_t)w[(bit >> 5) + 1] << 32);
+      const uint32_t code = (uint32_t)(pair >> (bit & 31)) & ((1u << F::cb) - 1u);
+      const uint32_t mag = code & ((1u << (F::cb - 1)) - 1u);
+      // the magnitude bits read as a binary32 pattern are the element value / 2^(127-bias)
+      const float el = u2f((mag << (23 - F::mbits)) | ((code >> (F::cb - 1)) << 31)) * unbias;
+      if constexpr (kHasLocal) v[k] = __builtin_fmaf(el, X, v[k]);
+      else v[k] = el * X;
+    }
+  }
+
+  if constexpr (KIND == kDecompress) {
+    float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(job.out) + (size_t)bi * 32);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+  } else {
+    float m = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) m = fmaxf(m, fabsf(v[k]));
+    // E8M0 byte: floor(log2 m) - emax + 127, clamped to [0, 254]; the biased exponent field of
+    // m is floor(log2 m) + 127 for normal m and 0 for zero / subnormal m (which clamp to 0 anyway)
+    int e = (int)(f2u(m) >> 23) - F::emax;
+    e = e < 0 ? 0 : (e > 254 ? 254 : e);
+    uint32_t ow[cw];
+#pragma unroll
+    for (int i = 0; i < cw; ++i) ow[i] = 0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      const float a = ldexpf(fabsf(v[k]), 127 - e);
+      const uint32_t code = quantize_mag<F>(a) | ((f2u(v[k]) >> 31) << (F::cb - 1));
+      const int bit = k * F::cb;
+      ow[bit >> 5] |= code << (bit & 31);
+      if ((bit & 31) + F::cb > 32) ow[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+    }
+    uint8_t *dst = static_cast<uint8_t *>(job.out) + (size_t)bi * (cw * 4);
+    if constexpr (cw == 8) {
+      *reinterpret_cast<uint4 *>(dst) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+      *reinterpret_cast<uint4 *>(dst + 16) = make_uint4(ow[4], ow[5], ow[6], ow[7]);
+    } else if constexpr (cw == 6) {
+      *reinterpret_cast<uint2 *>(dst) = make_uint2(ow[0], ow[1]);
+      *reinterpret_cast<uint2 *>(dst + 8) = make_uint2(ow[2], ow[3]);
+      *reinterpret_cast<uint2 *>(dst + 16) = make_uint2(ow[4], ow[5]);
+    } else {
+      *reinterpret_cast<uint4 *>(dst) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    }
+    static_cast<uint8_t *>(job.out)[scale_off + bi] = (uint8_t)e;
+  }
+}
+
+template <int FMT, Kind KIND, typename LT>
+__device__ __forceinline__ void mx_run(const MxJob &job) {
+  const uint64_t n_blocks = job.n_entries / 32;
+  const uint64_t stride = (uint64_t)gridDim.x * kBlockThreads;
+  for (uint64_t bi = (uint64_t)blockIdx.x * kBlockThreads + threadIdx.x; bi < n_blocks; bi += stride)
+    mx_block<FMT, KIND, LT>(job, bi, n_blocks);
+}
+
+template <int FMT, Kind KIND, typename LT>
+__global__ __launch_bounds__(kBlockThreads) void mx_one(MxJob job) {
+  mx_run<FMT, KIND, LT>(job);
+}
+template <int FMT, Kind KIND, typename LT>
+__global__ __launch_bounds__(kBlockThreads) void mx_batch(const MxJob *jobs) {
+  const MxJob job = jobs[blockIdx.y];
+  mx_run<FMT, KIND, LT>(job);
+}
+
+template <int FMT, Kind KIND, typename LT>
+hipError_t go(const MxJob *one, const MxJob *jobs, uint32_t n_jobs, uint64_t max_entries, uint32_t n_cu, hipStream_t s) {
+  const uint64_t blocks_needed = (max_entries / 32 + kBlockThreads - 1) / kBlockThreads;
+  if (blocks_needed == 0 || n_jobs == 0) return hipSuccess;
+  uint64_t cap = ((uint64_t)n_cu * 8 + n_jobs - 1) / n_jobs;
+  if (cap < 1) cap = 1;
+  const uint32_t blocks = (uint32_t)(blocks_needed < cap ? blocks_needed : cap);
+  if (one) hipLaunchKernelGGL((mx_one<FMT, KIND, LT>), dim3(blocks), dim3(kBlockThreads), 0, s, *one);
+  else hipLaunchKernelGGL((mx_batch<FMT, KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), 0, s, jobs);
+  return hipGetLastError();
+}
+
+template <int FMT>
+hipError_t dispatch(Kind kind, dq_dtype dtype, bool has_local, const MxJob *one, const MxJob *jobs, uint32_t n_jobs,
+                    uint64_t max_entries, uint32_t n_cu, hipStream_t s) {
+  const bool f32 = dtype == DQ_F32;
+  switch (kind) {
+    case kCompress:
+      return f32 ? go<FMT, kCompress, float>(one, jobs, n_jobs, max_entries, n_cu, s)
+                 : go<FMT, kCompress, uint16_t>(one, jobs, n_jobs, max_entries, n_cu, s);
+    case kDar:
+      return f32 ? go<FMT, kDar, float>(one, jobs, n_jobs, max_entries, n_cu, s)
+                 : go<FMT, kDar, uint16_t>(one, jobs, n_jobs, max_entries, n_cu, s);
+    default:
+      if (!has_local) return go<FMT, kDecompress, NoLocal>(one, jobs, n_jobs, max_entries, n_cu, s);
+      return f32 ? go<FMT, kDecompress, float>(one, jobs, n_jobs, max_entries, n_cu, s)
+                 : go<FMT, kDecompress, uint16_t>(one, jobs, n_jobs, max_entries, n_cu, s);
+  }
+}
+
+hipError_t dispatch_fmt(Kind kind, dq_codec fmt, dq_dtype dtype, bool has_local, const MxJob *one, const MxJob *jobs,
+                        uint32_t n_jobs, uint64_t max_entries, uint32_t n_cu, hipStream_t s) {
+  switch (fmt) {
+    case DQ_MXFP8_E4M3: return dispatch<DQ_MXFP8_E4M3>(kind, dtype, has_local, one, jobs, n_jobs, max_entries, n_cu, s);
+    case DQ_MXFP6_E3M2: return dispatch<DQ_MXFP6_E3M2>(kind, dtype, has_local, one, jobs, n_jobs, max_entries, n_cu, s);
+    case DQ_MXFP4_E2M1: return dispatch<DQ_MXFP4_E2M1>(kind, dtype, has_local, one, jobs, n_jobs, max_entries, n_cu, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t mx_launch_one(Kind kind, dq_codec fmt, dq_dtype dtype, bool has_local, const MxJob &job, uint32_t n_cu,
+                         hipStream_t s) {
+  return dispatch_fmt(kind, fmt, dtype, has_local, &job, nullptr, 1, job.n_entries, n_cu, s);
+}
+hipError_t mx_launch_batch(Kind kind, dq_codec fmt, dq_dtype dtype, bool has_local, const MxJob *jobs, uint32_t n_jobs,
+                           uint64_t max_entries, uint32_t n_cu, hipStream_t s) {
+  return dispatch_fmt(kind, fmt, dtype, has_local, nullptr, jobs, n_jobs, max_entries, n_cu, s);
+}
+
+}  // namespace dq
+
+// ---- C ABI ----------------------------------------------------------------------------
+namespace {
+bool al16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool is_mx_fmt(dq_codec f) { return f == DQ_MXFP8_E4M3 || f == DQ_MXFP6_E3M2 || f == DQ_MXFP4_E2M1; }
+int code_bits(dq_codec f) { return f == DQ_MXFP8_E4M3 ? 8 : f == DQ_MXFP6_E3M2 ? 6 : 4; }
+uint32_t device_cus() {
+  static thread_local int cached = 0;
+  if (!cached) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cached = prop.multiProcessorCount;
+    else
+      cached = 256;
+  }
+  return (uint32_t)cached;
+}
+}  // namespace
+
+extern "C" {
+
+size_t dq_mx_packed_bytes(dq_codec fmt, uint64_t n_entries) {
+  if (!is_mx_fmt(fmt) || n_entries % 256) return 0;
+  const uint64_t blocks = n_entries / 32;
+  const uint64_t sz = blocks * (uint64_t)(code_bits(fmt) * 4) + blocks;
+  return (size_t)((sz + 15) & ~(uint64_t)15);
+}
+
+dq_status dq_mx_compress(dq_codec fmt, const void *local, dq_dtype dtype, uint64_t n_entries, void *packed_out,
+                         void *hip_stream) {
+  if (!is_mx_fmt(fmt) || !local || !packed_out || n_entries % 256 || (dtype != DQ_F32 && dtype != DQ_BF16))
+    return DQ_EINVAL;
+  if (!al16(local) || !al16(packed_out)) return DQ_EALIGN;
+  dq::MxJob j{nullptr, local, packed_out, n_entries};
+  return dq::mx_launch_one(dq::kCompress, fmt, dtype, true, j, device_cus(), (hipStream_t)hip_stream) == hipSuccess
+             ? DQ_OK
+             : DQ_EHIP;
+}
+
+dq_status dq_mx_dar_hop(dq_codec fmt, const void *packed_in, const void *local, dq_dtype dtype, uint64_t n_entries,
+                        void *packed_out, void *hip_stream) {
+  if (!is_mx_fmt(fmt) || !packed_in || !local || !packed_out || n_entries % 256 ||
+      (dtype != DQ_F32 && dtype != DQ_BF16))
+    return DQ_EINVAL;
+  if (!al16(packed_in) || !al16(local) || !al16(packed_out)) return DQ_EALIGN;
+  dq::MxJob j{(const uint8_t *)packed_in, local, packed_out, n_entries};
+  return dq::mx_launch_one(dq::kDar, fmt, dtype, true, j, device_cus(), (hipStream_t)hip_stream) == hipSuccess
+             ? DQ_OK
+             : DQ_EHIP;
+}
+
+dq_status dq_mx_decompress(dq_codec fmt, const void *packed_in, const void *local_or_null, dq_dtype dtype,
+                           uint64_t n_entries, float *out, void *hip_stream) {
+  if (!is_mx_fmt(fmt) || !packed_in || !out || n_entries % 256) return DQ_EINVAL;
+  if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
+  if (!al16(packed_in) || !al16(out) || !al16(local_or_null)) return DQ_EALIGN;
+  dq::MxJob j{(const uint8_t *)packed_in, local_or_null, out, n_entries};
+  return dq::mx_launch_one(dq::kDecompress, fmt, dtype, local_or_null != nullptr, j, device_cus(),
+                           (hipStream_t)hip_stream) == hipSuccess
+             ? DQ_OK
+             : DQ_EHIP;
+}
+
+}  // extern "C"

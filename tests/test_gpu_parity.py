@@ -1,0 +1,319 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bar: packed codes, u8 group scales, bf16 super-group scales and E8M0 bytes bit-exact;
+fp32 decoded sums within 1e-6 relative (they are expected to be bit-exact too, the slack is
+the tolerance the benchmark spec states for floating point).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dq_oracle as O
+from paper_2602_08923_amd import binding as B
+from paper_2602_08923_amd import prep, workloads
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def to_dev(a, dev):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    return torch.from_numpy(a).to(dev)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def make_local(rng, n, dtype, scale=1e-3):
+    x = (rng.standard_normal(n) * scale).astype(np.float32)
+    if dtype == "bf16":
+        return (x.view(np.uint32) >> 16).astype(np.uint16)
+    return x
+
+
+def assert_close_f32(got, want):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    tol = RTOL * np.maximum(np.abs(want), np.abs(got)) + 1e-30
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), f"{bad.sum()} of {bad.size} entries differ, first at {np.argmax(bad)}"
+
+
+CASES = [
+    # n_workers, n_sg (2,4,8 bit), first_sg, rank
+    (4, [5, 7, 3], 0, 1),
+    (8, [0, 9, 0], 2 ** 33 + 11, 7),
+    (3, [1, 0, 2], 12345, 2),        # worker count that is not a power of two
+    (64, [13, 0, 0], 7, 63),
+    (1, [0, 1, 1], 0, 0),
+    (100, [2, 66, 5], 999, 42),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", CASES)
+def test_single_chunk_calls_match_oracle(dev, dtype, case):
+    n, n_sg, first_sg, rank = case
+    seed, rnd = 0xC0FFEE1234, 5
+    rng = np.random.default_rng(n * 1000 + sum(n_sg))
+    entries = sum(n_sg) * 256
+    orc = O.Oracle(n, seed=seed, round=rnd)
+    ctx = B.Context(n, seed=seed, round=rnd)
+    och, gch = O.make_chunk(first_sg, n_sg), B.make_chunk(first_sg, n_sg)
+    assert B.dq_packed_bytes(gch) == O.Oracle.packed_bytes(och)
+
+    a = make_local(rng, entries, dtype)
+    b = make_local(rng, entries, dtype)
+    c = make_local(rng, entries, dtype)
+    # leaf
+    want1 = orc.compress(och, rank, a)
+    got1 = ctx.dq_compress(to_dev(a, dev), gch, rank)
+    assert np.array_equal(host(got1), want1)
+    # internal node (a different worker re-encodes)
+    rank2 = (rank + 1) % n
+    want2 = orc.dar_hop(och, rank2, want1, b)
+    got2 = ctx.dq_dar_hop(got1, to_dev(b, dev), gch, rank2)
+    assert np.array_equal(host(got2), want2)
+    # in place
+    got2b = got1.clone()
+    ctx.dq_dar_hop(got2b, to_dev(b, dev), gch, rank2, packed_out=got2b)
+    assert np.array_equal(host(got2b), want2)
+    # sink, and plain decompress
+    assert_close_f32(host(ctx.dq_decompress(got2, gch, local=to_dev(c, dev))), orc.decompress(och, want2, c))
+    assert_close_f32(host(ctx.dq_decompress(got2, gch)), orc.decompress(och, want2))
+    assert np.array_equal(host(ctx.dq_decompress(got2, gch)), orc.decompress(och, want2))
+    ctx.close()
+
+
+def test_new_round_draws_new_numbers(dev):
+    n_sg = [1, 2, 1]
+    rng = np.random.default_rng(4)
+    a = make_local(rng, 4 * 256, "f32")
+    ctx = B.Context(4, seed=9, round=0)
+    gch = B.make_chunk(0, n_sg)
+    p0 = host(ctx.dq_compress(to_dev(a, dev), gch, 0))
+    ctx.set_round(1)
+    p1 = host(ctx.dq_compress(to_dev(a, dev), gch, 0))
+    assert not np.array_equal(p0, p1)
+    assert np.array_equal(p1, O.Oracle(4, seed=9, round=1).compress(O.make_chunk(0, n_sg), 0, a))
+
+
+def test_degenerate_inputs(dev):
+    """All-zero chunk, signed zeros, values below the flush threshold, denormal groups,
+    one huge outlier, exact powers of two."""
+    n, n_sg = 4, [2, 2, 2]
+    entries = 6 * 256
+    rng = np.random.default_rng(31)
+    orc, ctx = O.Oracle(n, seed=1), B.Context(n, seed=1)
+    och, gch = O.make_chunk(3, n_sg), B.make_chunk(3, n_sg)
+    variants = []
+    z = np.zeros(entries, np.float32)
+    variants.append(z)
+    s = z.copy(); s[::3] = -0.0
+    variants.append(s)
+    variants.append(np.full(entries, 2.0 ** -110, np.float32))
+    d = (rng.standard_normal(entries) * 1e-3).astype(np.float32); d[16:48] = 1e-42; d[300:316] = 0.0
+    variants.append(d)
+    o = (rng.standard_normal(entries) * 1e-3).astype(np.float32); o[700] = 3.0e4
+    variants.append(o)
+    p = np.ldexp(1.0, rng.integers(-20, 3, entries)).astype(np.float32) * rng.choice([-1.0, 1.0], entries).astype(np.float32)
+    variants.append(p)
+    prev_o = prev_g = None
+    for v in variants:
+        w = orc.compress(och, 2, v)
+        g = ctx.dq_compress(to_dev(v, dev), gch, 2)
+        assert np.array_equal(host(g), w)
+        if prev_o is not None:
+            w2 = orc.dar_hop(och, 3, prev_o, v)
+            g2 = ctx.dq_dar_hop(prev_g, to_dev(v, dev), gch, 3)
+            assert np.array_equal(host(g2), w2)
+            assert np.array_equal(host(ctx.dq_decompress(g2, gch, local=to_dev(v, dev))), orc.decompress(och, w2, v))
+        prev_o, prev_g = w, g
+
+
+def test_empty_chunk_and_bad_arguments(dev):
+    ctx = B.Context(4)
+    empty = B.make_chunk(0, [0, 0, 0])
+    assert B.dq_packed_bytes(empty) == 0
+    buf = torch.zeros(16, dtype=torch.uint8, device=dev)
+    loc = torch.zeros(0, dtype=torch.float32, device=dev)
+    ctx.dq_compress(loc, empty, 0, packed_out=buf)  # nothing to do, no launch
+    torch.cuda.synchronize()
+    assert int(buf.sum()) == 0
+    ch = B.make_chunk(0, [0, 1, 0])
+    x = torch.zeros(256, dtype=torch.float32, device=dev)
+    with pytest.raises(B.DqError):  # rank outside 0..n-1
+        ctx.dq_compress(x, ch, 4)
+    with pytest.raises(B.DqError):  # misaligned local
+        ctx.dq_compress(torch.zeros(257, dtype=torch.float32, device=dev)[1:], ch, 0)
+    with pytest.raises(B.DqError):
+        B.Context(0)
+    with pytest.raises(B.DqError):
+        B.Context(4, g4=1.0)
+    with pytest.raises(B.DqError):  # 8-bit level set too fine for the search table
+        B.Context(4, g8=1.1)
+
+
+@pytest.mark.parametrize("g4,g8", [(2.0, 1.04), (1.05, 1.005)])
+def test_other_level_sets(dev, g4, g8):
+    n, n_sg = 8, [0, 6, 6]
+    rng = np.random.default_rng(77)
+    a, b = make_local(rng, 12 * 256, "bf16"), make_local(rng, 12 * 256, "bf16")
+    orc, ctx = O.Oracle(n, seed=3, g4=g4, g8=g8), B.Context(n, seed=3, g4=g4, g8=g8)
+    och, gch = O.make_chunk(50, n_sg), B.make_chunk(50, n_sg)
+    w1 = orc.compress(och, 0, a)
+    g1 = ctx.dq_compress(to_dev(a, dev), gch, 0)
+    assert np.array_equal(host(g1), w1)
+    assert np.array_equal(host(ctx.dq_dar_hop(g1, to_dev(b, dev), gch, 5)), orc.dar_hop(och, 5, w1, b))
+
+
+# ----------------------------------------------------------------------------- hop replay
+
+def prepared(wl, dev, entries=None, bucket=0):
+    """Worker gradients of one bucket on the device, reordered by the allocation."""
+    grads = [workloads.draw(wl, w, bucket, device="cpu", entries=entries) for w in range(wl.n_workers)]
+    re, counts, _ = prep.prepare_bucket(grads, wl.budget_bits, wl.n_workers)
+    return re, counts
+
+
+def test_ring_replay_config1_full(dev):
+    """BASELINE config 1 at full size: 4 workers, 2^20 fp32 entries each, b = 5."""
+    wl = workloads.CONFIGS[1]
+    re, counts = prepared(wl, dev)
+    assert sum(counts) == 4096 and counts[1] > 0
+    orc, ctx = O.Oracle(4, seed=11), B.Context(4, seed=11)
+    want = np.concatenate(O.ring_reduce_scatter(orc, [workloads.to_numpy(g) for g in re], counts))
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [g.to(dev) for g in re], 4096, [counts])
+    assert rp.n_steps == 4
+    rp.run()
+    torch.cuda.synchronize()
+    got = host(rp.out)
+    assert_close_f32(got, want)
+    assert np.array_equal(got, want)
+    # the sum is approximated, not garbage
+    true = sum(g.double() for g in re).numpy()
+    assert ((got - true) ** 2).sum() / (true ** 2).sum() < 0.05
+    # replays are deterministic
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+
+
+@pytest.mark.parametrize("n,n_sg_bucket,counts,buckets", [(2, 8, [[2, 4, 2]], 1), (4, 12, [[3, 6, 3], [0, 12, 0]], 2),
+                                                          (8, 40, [[7, 22, 11]], 1)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_butterfly_replay_small(dev, n, n_sg_bucket, counts, buckets, dtype):
+    rng = np.random.default_rng(n + buckets)
+    d = n_sg_bucket * 256
+    grads = [make_local(rng, d * buckets, dtype) for _ in range(n)]
+    orc, ctx = O.Oracle(n, seed=21, round=1), B.Context(n, seed=21, round=1)
+    want = []
+    for b in range(buckets):
+        want += O.butterfly_reduce_scatter(orc, [g[b * d:(b + 1) * d] for g in grads], counts[b],
+                                           first_sg=100 + b * n_sg_bucket)
+    want = np.concatenate(want)
+    rp = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], n_sg_bucket, counts,
+                  n_buckets=buckets, first_sg=100)
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ring_and_chain_replay_small(dev, dtype):
+    n, n_sg_bucket, counts = 4, 20, [[4, 11, 5], [20, 0, 0]]
+    rng = np.random.default_rng(5)
+    d = n_sg_bucket * 256
+    grads = [make_local(rng, 2 * d, dtype) for _ in range(n)]
+    orc, ctx = O.Oracle(n, seed=2), B.Context(n, seed=2)
+    want = []
+    for b in range(2):
+        want += O.ring_reduce_scatter(orc, [g[b * d:(b + 1) * d] for g in grads], counts[b], first_sg=b * n_sg_bucket)
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], n_sg_bucket, counts, n_buckets=2)
+    ms = rp.run(timed=True)
+    assert len(ms) == 4 and all(m >= 0 for m in ms)
+    assert [rp.step_info(i)[0] for i in range(4)] == [0, 1, 1, 2]
+    assert rp.step_info(1)[1] == 2 * d
+    assert np.array_equal(host(rp.out), np.concatenate(want))
+    # chain: the path of one chunk through all n workers
+    och = O.make_chunk(77, [3, 5, 2])
+    sl = [make_local(rng, 2560, dtype) for _ in range(n)]
+    msg = orc.compress(och, 0, sl[0])
+    for i in (1, 2):
+        msg = orc.dar_hop(och, i, msg, sl[i])
+    want = orc.decompress(och, msg, sl[3])
+    rc = B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, [to_dev(s, dev) for s in sl], 10, [[3, 5, 2]], first_sg=77)
+    rc.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rc.out), want)
+
+
+# ----------------------------------------------------------------------------- MX codec
+
+@pytest.mark.parametrize("fmt", [B.DQ_MXFP8_E4M3, B.DQ_MXFP6_E3M2, B.DQ_MXFP4_E2M1])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mx_calls_match_oracle(dev, fmt, dtype):
+    rng = np.random.default_rng(fmt)
+    n = 256 * 37
+    a = make_local(rng, n, dtype)
+    b = make_local(rng, n, dtype, scale=3e-3)
+    if dtype == "f32":
+        a[100:132] = 0.0           # an all-zero block
+        a[200] = 1e-41             # denormal
+        a[300] = 448.0 * 2.0 ** -3  # a block maximum exactly on a power-of-two boundary case
+        a[5000] = 3.0e38           # near the top of binary32
+    assert B.dq_mx_packed_bytes(fmt, n) == O.mx_packed_bytes(fmt, n)
+    w1 = O.mx_compress(fmt, a)
+    g1 = B.dq_mx_compress(fmt, to_dev(a, dev))
+    assert np.array_equal(host(g1), w1)
+    w2 = O.mx_dar_hop(fmt, w1, b)
+    g2 = B.dq_mx_dar_hop(fmt, g1, to_dev(b, dev))
+    assert np.array_equal(host(g2), w2)
+    assert np.array_equal(host(B.dq_mx_decompress(fmt, g2, n)), O.mx_decompress(fmt, w2, n))
+    assert np.array_equal(host(B.dq_mx_decompress(fmt, g2, n, local=to_dev(a, dev))), O.mx_decompress(fmt, w2, n, a))
+
+
+@pytest.mark.parametrize("fmt", [B.DQ_MXFP8_E4M3, B.DQ_MXFP6_E3M2, B.DQ_MXFP4_E2M1])
+def test_mx_every_code_roundtrips(dev, fmt):
+    """decode(encode) is the identity on every element code at several block scales."""
+    bits = O.MX_CODE_BITS[fmt]
+    codes = [c for c in range(1 << bits) if not (fmt == B.DQ_MXFP8_E4M3 and (c & 0x7F) == 0x7F)]
+    for e in (1, 100, 127, 200):
+        vals = np.array([O.mx_decode_elem(fmt, c, e) for c in codes], np.float32)
+        blocks = []
+        top = max(abs(float(v)) for v in vals)
+        # pad every block with the format's largest value so that the shared exponent is e
+        for i in range(0, len(vals), 31):
+            blk = np.full(32, top, np.float32)
+            part = vals[i:i + 31]
+            blk[1:1 + len(part)] = part
+            blocks.append(blk)
+        x = np.concatenate(blocks)
+        x = np.concatenate([x, np.zeros((-len(x)) % 256, np.float32)])
+        g = B.dq_mx_compress(fmt, to_dev(x, dev))
+        assert np.array_equal(host(g), O.mx_compress(fmt, x))
+        back = host(B.dq_mx_decompress(fmt, g, len(x)))
+        assert np.array_equal(back, x)
+
+
+def test_mx_ring_replay_small(dev):
+    n = 4
+    rng = np.random.default_rng(12)
+    grads = [make_local(rng, 16 * 256, "bf16") for _ in range(n)]
+    ctx = B.Context(n)
+    for fmt in (B.DQ_MXFP8_E4M3, B.DQ_MXFP6_E3M2, B.DQ_MXFP4_E2M1):
+        want = np.concatenate(O.mx_ring_reduce_scatter(fmt, grads))
+        rp = B.Replay(ctx, B.DQ_RING, fmt, [to_dev(g, dev) for g in grads], 16)
+        rp.run()
+        torch.cuda.synchronize()
+        assert np.array_equal(host(rp.out), want)
