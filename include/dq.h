@@ -132,6 +132,9 @@ uint32_t dq_replay_n_steps(const dq_replay *plan);
  * receives each step's duration measured with HIP events on `hip_stream` (this variant
  * synchronises the stream before returning). */
 dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream);
+/* Enqueue steps first .. first+count-1 only (so that a caller can bracket a run of hop steps
+ * with its own events); running all steps in order is the same as dq_replay_run. */
+dq_status dq_replay_run_steps(dq_replay *plan, uint32_t first, uint32_t count, void *hip_stream);
 /* Per step: kind (0 compress, 1 DAR, 2 decompress-accumulate, 3 DAR + decompress-accumulate
  * in one launch) and the entries it processes, for throughput accounting. */
 dq_status dq_replay_step_info(const dq_replay *plan, uint32_t step, uint32_t *kind, uint64_t *entries_dar,

@@ -20,7 +20,8 @@ DQ_RING, DQ_BUTTERFLY, DQ_CHAIN = 0, 1, 2
 EXPORTS = [
     "dq_create", "dq_destroy", "dq_set_round", "dq_packed_bytes", "dq_compress", "dq_dar_hop", "dq_decompress",
     "dq_mx_packed_bytes", "dq_mx_compress", "dq_mx_dar_hop", "dq_mx_decompress",
-    "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_step_info",
+    "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_run_steps",
+    "dq_replay_step_info",
     "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
 ]
 
@@ -78,6 +79,7 @@ def lib():
         L.dq_replay_n_steps.argtypes = [vp]
         L.dq_replay_n_steps.restype = u32
         L.dq_replay_run.argtypes = [vp, C.POINTER(C.c_float), vp]
+        L.dq_replay_run_steps.argtypes = [vp, u32, u32, vp]
         L.dq_replay_step_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u64)]
         L.dq_replay_destroy.argtypes = [vp]
         L.dq_replay_destroy.restype = None
@@ -256,6 +258,9 @@ class Replay:
             return list(ms)
         _check(lib().dq_replay_run(self.h, None, _stream()))
         return None
+
+    def run_steps(self, first, count):
+        _check(lib().dq_replay_run_steps(self.h, first, count, _stream()))
 
     def step_info(self, step):
         kind, a, b = C.c_uint32(), C.c_uint64(), C.c_uint64()

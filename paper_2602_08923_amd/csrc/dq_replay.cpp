@@ -337,6 +337,32 @@ dq_status dq_replay_step_info(const dq_replay *plan, uint32_t step, uint32_t *ki
   return DQ_OK;
 }
 
+static dq_status run_step(dq_replay *plan, size_t i, hipStream_t s) {
+  const bool mx = plan->codec != DQ_DYNAMIQ;
+  for (const Launch &L : plan->plan.steps[i].launches) {
+    if (L.jobs.empty()) continue;
+    hipError_t e;
+    if (mx)
+      e = dq::mx_launch_batch(L.kind, plan->codec, L.dtype, true,
+                              reinterpret_cast<const dq::MxJob *>(plan->scratch + L.table_off),
+                              (uint32_t)L.jobs.size(), L.max_entries, plan->ctx->n_cu, s);
+    else
+      e = dq::launch_batch(L.kind, L.dtype, true, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
+                           (uint32_t)L.jobs.size(), L.max_tiles, plan->ctx->params, plan->ctx->n_cu, s);
+    if (e != hipSuccess) return DQ_EHIP;
+  }
+  return DQ_OK;
+}
+
+dq_status dq_replay_run_steps(dq_replay *plan, uint32_t first, uint32_t count, void *hip_stream) {
+  if (!plan || (size_t)first + count > plan->plan.steps.size()) return DQ_EINVAL;
+  for (uint32_t i = first; i < first + count; ++i) {
+    const dq_status st = run_step(plan, i, (hipStream_t)hip_stream);
+    if (st != DQ_OK) return st;
+  }
+  return DQ_OK;
+}
+
 dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream) {
   if (!plan) return DQ_EINVAL;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -348,22 +374,10 @@ dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream) {
       plan->events.push_back(e);
     }
   }
-  const bool mx = plan->codec != DQ_DYNAMIQ;
   if (step_ms && hipEventRecord(plan->events[0], s) != hipSuccess) return DQ_EHIP;
   for (size_t i = 0; i < ns; ++i) {
-    for (const Launch &L : plan->plan.steps[i].launches) {
-      if (L.jobs.empty()) continue;
-      hipError_t e;
-      const bool has_local = true;
-      if (mx)
-        e = dq::mx_launch_batch(L.kind, plan->codec, L.dtype, has_local,
-                                reinterpret_cast<const dq::MxJob *>(plan->scratch + L.table_off),
-                                (uint32_t)L.jobs.size(), L.max_entries, plan->ctx->n_cu, s);
-      else
-        e = dq::launch_batch(L.kind, L.dtype, has_local, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
-                             (uint32_t)L.jobs.size(), L.max_tiles, plan->ctx->params, plan->ctx->n_cu, s);
-      if (e != hipSuccess) return DQ_EHIP;
-    }
+    const dq_status st = run_step(plan, i, s);
+    if (st != DQ_OK) return st;
     if (step_ms && hipEventRecord(plan->events[i + 1], s) != hipSuccess) return DQ_EHIP;
   }
   if (step_ms) {
