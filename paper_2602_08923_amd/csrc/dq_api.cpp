@@ -132,27 +132,59 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
     const int R = Rs[wi], b = 2 << wi;  // widths 2, 4, 8
     std::vector<float> T, D;
     if (!build_levels(R, gs[wi], T, D)) return DQ_EINVAL;
-    // signed decode table indexed by the whole code: sign << (b-1) | r
-    std::vector<uint32_t> dec((size_t)1 << b);
-    for (int code = 0; code < (1 << b); ++code) {
-      const float t = T[code & R];
-      dec[code] = fbits((code >> (b - 1)) ? -t : t);
-    }
+    while (blob.size() % 4) blob.push_back(0);
+    P.reg_lo[wi] = (uint32_t)blob.size();
+    // decode table indexed by one byte of packed codes: the 8/b signed levels it holds,
+    // lowest bits first; a code is sign << (b-1) | r
+    const int per_byte = 8 / b;
+    std::vector<uint32_t> dec((size_t)256 * per_byte);
+    for (int byte = 0; byte < 256; ++byte)
+      for (int j = 0; j < per_byte; ++j) {
+        const int code = (byte >> (j * b)) & ((1 << b) - 1);
+        const float t = T[code & R];
+        dec[(size_t)byte * per_byte + j] = fbits((code >> (b - 1)) ? -t : t);
+      }
     append_aligned(blob, dec, &P.off_dec[wi]);
-    if (wi == 0) continue;  // levels {0,1}: the kernels need no search
-    int m = 0;
-    std::vector<uint32_t> lut;
-    if (!build_search(T, R, &m, lut)) return DQ_EUNSUPPORTED;
-    append_aligned(blob, lut, &P.off_lut[wi]);
-    std::vector<uint32_t> tab(2 * (size_t)(R + 1));
-    for (int r = 0; r <= R; ++r) {
-      tab[2 * r] = fbits(T[r]);
-      tab[2 * r + 1] = fbits(D[r]);
+    if (wi > 0) {  // levels {0,1} need no search
+      int m = 0;
+      std::vector<uint32_t> lut;
+      if (!build_search(T, R, &m, lut)) return DQ_EUNSUPPORTED;
+      append_aligned(blob, lut, &P.off_lut[wi]);
+      std::vector<uint32_t> tab(2 * (size_t)(R + 1));
+      for (int r = 0; r <= R; ++r) {
+        tab[2 * r] = fbits(T[r]);
+        tab[2 * r + 1] = fbits(D[r]);
+      }
+      append_aligned(blob, tab, &P.off_tab[wi]);
+      P.magic[wi] = (float)ldexp(1.0, 23 - m);
     }
-    append_aligned(blob, tab, &P.off_tab[wi]);
-    P.magic[wi] = (float)ldexp(1.0, 23 - m);
+    if (wi == 1) {  // sign bit of entry k of a word -> bit 4k+3
+      std::vector<uint32_t> sp(256);
+      for (int byte = 0; byte < 256; ++byte) {
+        uint32_t w = 0;
+        for (int k = 0; k < 8; ++k)
+          if ((byte >> k) & 1) w |= 1u << (4 * k + 3);
+        sp[byte] = w;
+      }
+      append_aligned(blob, sp, &P.off_spread4);
+    }
+    while (blob.size() % 4) blob.push_back(0);
+    P.reg_hi[wi] = (uint32_t)blob.size();
   }
-  while (blob.size() % 4) blob.push_back(0);
+  {  // common region: quotients of the 128 bf16 significands by 255 and of 255 by them
+    while (blob.size() % 4) blob.push_back(0);
+    P.reg_lo[3] = (uint32_t)blob.size();
+    std::vector<uint32_t> rec(256);
+    for (int m = 0; m < 128; ++m) {
+      const float sig = 1.0f + (float)m / 128.0f;
+      const float a = sig / 255.0f, b = 255.0f / sig;
+      rec[2 * m] = fbits(a);
+      rec[2 * m + 1] = fbits(b);
+    }
+    append_aligned(blob, rec, &P.off_rec);
+    while (blob.size() % 4) blob.push_back(0);
+    P.reg_hi[3] = (uint32_t)blob.size();
+  }
   if (blob.size() * 4 > 60 * 1024) return DQ_EUNSUPPORTED;
 
   dq_ctx *ctx = new (std::nothrow) dq_ctx;
@@ -177,6 +209,7 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
   P.n_mask = (cfg->n_workers & (cfg->n_workers - 1)) == 0 ? cfg->n_workers - 1 : 0xFFFFFFFFu;
   P.inv_n = 1.0f / (float)cfg->n_workers;
   P.s_n = P.inv_n * (1.0f / 256.0f);
+  P.tiles_per_wave = 0;  // chosen per launch
   ctx->params = P;
   *out = ctx;
   return DQ_OK;

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "dq.h"
 
@@ -25,10 +26,15 @@ struct Job {
 };
 
 // Everything the kernels need besides the job: PRNG key, worker count, table blob.
+// The blob holds one region per width (2, 4, 8 bits), each region = [decode table | search
+// table | level/gap table]; a block copies only the regions of the widths it will meet.
 struct Params {
-  const uint32_t *blob;  // device copy of the table blob, blob_dwords long (multiple of 4)
-  uint32_t blob_dwords;
-  uint32_t off_dec[3];   // dword offsets: signed decode table, 2^b floats
+  const uint32_t *blob;  // device copy of the table blob
+  uint32_t blob_dwords;  // multiple of 4
+  uint32_t reg_lo[4], reg_hi[4];  // dword range of each width's region and of the common one (multiples of 4)
+  uint32_t off_rec;      // common: 128 pairs {bits((1+m/128)/255), bits(255/(1+m/128))}
+  uint32_t off_spread4;  // 4-bit region: byte of 8 sign bits -> those bits at positions 4k+3
+  uint32_t off_dec[3];   // decode table indexed by one code BYTE: 8/b signed levels (+-T[r]) per entry
   uint32_t off_lut[3];   // search table: (2^m + 1) pairs {next level, candidate index}
   uint32_t off_tab[3];   // level/gap pairs {T[r], D[r]}, r = 0..R (D[R] = 0)
   float magic[3];        // 2^(23-m): adding it leaves round(x * 2^m) in the low mantissa bits
@@ -36,6 +42,7 @@ struct Params {
   uint32_t n_workers;
   uint32_t n_mask;       // n-1 if n is a power of two, else 0xFFFFFFFF (meaning: use %)
   float inv_n, s_n;
+  uint32_t tiles_per_wave;  // launch shape only: how many consecutive tiles one wave takes (1..8)
 };
 
 enum Kind { kCompress = 0, kDar = 1, kDecompress = 2 };
@@ -44,7 +51,8 @@ enum Kind { kCompress = 0, kDar = 1, kDecompress = 2 };
 hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t n_cu,
                       hipStream_t stream);
 hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, const Job *jobs_dev, uint32_t n_jobs,
-                        uint32_t max_tiles_per_job, const Params &p, uint32_t n_cu, hipStream_t stream);
+                        uint32_t max_tiles_per_job, uint64_t total_tiles, const Params &p, uint32_t n_cu,
+                        hipStream_t stream);
 
 struct MxJob {
   const uint8_t *in;

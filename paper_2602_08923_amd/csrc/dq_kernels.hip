@@ -4,15 +4,18 @@
 //
 // Mapping.  One lane owns one group of 16 entries; a DPP row of 16 lanes is one super-group
 // (SG), so the group maximum is in-lane and the SG maximum is four row-rotate DPP steps; a
-// wave64 processes 4 SGs per tile.  Codes travel as one 32/64/128-bit access per lane
-// (2/4/8-bit widths), the local slice as 128-bit accesses.  Level tables live in LDS:
-//   dec[code]      signed level  (+-T[r])                                  -> decode
+// wave64 processes 4 SGs per tile and a run of consecutive tiles per launch.  Codes travel as
+// one 32/64/128-bit access per lane (2/4/8-bit widths), the local slice as 128-bit accesses.
+// Level tables live in LDS (a block copies only the widths it meets):
+//   dec[byte]      the 8/b signed levels (+-T[r]) one byte of packed codes holds  -> decode
 //   lut[q]         {T[rc+1], rc} for q = round(x' * 2^m): rc is the level index at the
 //                  lower edge of the bin, and bins are narrower than any gap, so the
 //                  level at or below x' is rc or rc+1 -- one compare settles it
-//   tab[r]         {T[r], D[r]}                                            -> rounding
+//   tab[r]         {T[r], D[r]}                                                    -> rounding
 // The stochastic rounding follows the division-free form  T + u*D < x'  with
 // u = (pi + gamma)/n built from one Philox byte per entry (Section 3.3 "Correlated rounding").
+// The per-SG random numbers (group-scale bytes, shared permutation) of up to 8 tiles are
+// drawn by ONE wave-wide Philox call (each lane a different counter) and parked in LDS.
 //
 // All arithmetic that decides a code is IEEE binary32 with explicit fused multiply-adds
 // only where written (this file is compiled with -ffp-contract=off and correctly rounded
@@ -23,9 +26,22 @@ namespace dq {
 namespace {
 
 struct NoLocal {};
+constexpr int kBatch = 8;  // tiles whose per-SG random numbers one wave-wide draw covers
 
 __device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// LDS accesses by byte address (the tables are addressed with folded constants)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const uint32_t lds_u32;
+typedef __attribute__((address_space(3))) const u32x2 lds_u2;
+typedef __attribute__((address_space(3))) const u32x4 lds_u4;
+typedef __attribute__((address_space(3))) u32x4 lds_w4;
+__device__ __forceinline__ uint32_t lds_ld1(uint32_t a) { return *reinterpret_cast<lds_u32 *>(a); }
+__device__ __forceinline__ u32x2 lds_ld2(uint32_t a) { return *reinterpret_cast<lds_u2 *>(a); }
+__device__ __forceinline__ u32x4 lds_ld4(uint32_t a) { return *reinterpret_cast<lds_u4 *>(a); }
+__device__ __forceinline__ void lds_st4(uint32_t a, u32x4 v) { *reinterpret_cast<lds_w4 *>(a) = v; }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11): counter-based, so every lane draws its numbers
 // from (global group index, round, stream, rank) alone.
@@ -64,200 +80,367 @@ __device__ __forceinline__ float row_max16(float x) {
   return x;
 }
 
+// bit i of a 16-bit value -> bit 2i
+__device__ __forceinline__ uint32_t spread16(uint32_t x) {
+  x = (x | (x << 8)) & 0x00FF00FFu;
+  x = (x | (x << 4)) & 0x0F0F0F0Fu;
+  x = (x | (x << 2)) & 0x33333333u;
+  x = (x | (x << 1)) & 0x55555555u;
+  return x;
+}
+
 template <int B>
 struct Width;
 template <>
-struct Width<2> { static constexpr int wi = 0, words = 1, R = 1; };
+struct Width<2> { static constexpr int wi = 0, words = 1; };
 template <>
-struct Width<4> { static constexpr int wi = 1, words = 2, R = 7; };
+struct Width<4> { static constexpr int wi = 1, words = 2; };
 template <>
-struct Width<8> { static constexpr int wi = 2, words = 4, R = 127; };
+struct Width<8> { static constexpr int wi = 2, words = 4; };
 
-template <typename LT>
-__device__ __forceinline__ void load_local(const void *base, size_t first, float (&loc)[16]) {
+// Where a tile (index t in the job's concatenated 2-, 4-, 8-bit tile sequence) sits.
+struct TilePos {
+  uint32_t seg_first;   // position in the chunk of the first SG of the tile's width
+  uint32_t n_seg;       // SGs of that width in the chunk
+  uint32_t tile_first;  // first SG of the tile inside the segment
+  int wi;
+};
+__device__ __forceinline__ TilePos locate(const Job &job, uint32_t t) {
+  const uint32_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2];
+  const uint32_t t0 = (n0 + kWaveSGs - 1) / kWaveSGs, t1 = (n1 + kWaveSGs - 1) / kWaveSGs;
+  if (t < t0) return TilePos{0, n0, t * kWaveSGs, 0};
+  if (t < t0 + t1) return TilePos{n0, n1, (t - t0) * kWaveSGs, 1};
+  return TilePos{n0 + n1, n2, (t - t0 - t1) * kWaveSGs, 2};
+}
+
+// Wave-uniform addresses of a tile: 64-bit bases once per tile (scalar registers), so that
+// every lane only adds a small 32-bit offset.
+template <int B>
+struct TileBase {
+  size_t code_off, gs_off, sf_off;  // byte offsets inside a packed buffer
+  size_t first_entry;               // first entry of the tile inside the chunk
+  uint32_t last_row;                // rows 0..last_row hold a super-group
+  uint64_t G0;                      // global index of the tile's first super-group
+  __device__ __forceinline__ TileBase(const Job &job, const TilePos pos) {
+    const size_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2];
+    const size_t gs0 = 64 * n0 + 128 * n1 + 256 * n2;
+    const size_t sg0 = (size_t)pos.seg_first + pos.tile_first;  // position in the chunk
+    code_off = (B == 2 ? 0 : (B == 4 ? 64 * n0 : 64 * n0 + 128 * n1)) + (size_t)pos.tile_first * (32 * B);
+    gs_off = gs0 + sg0 * 16;
+    sf_off = gs0 + 16 * (n0 + n1 + n2) + sg0 * 2;
+    first_entry = sg0 * kSG;
+    last_row = min((uint32_t)kWaveSGs - 1, pos.n_seg - 1 - pos.tile_first);
+    G0 = job.first_sg + sg0;
+  }
+};
+
+// sf_SG/255 and 255/sf_SG for a bf16 sf_SG without a division: the quotient of the 8-bit
+// significand comes from a 128-entry table of correctly rounded values and the exponent is
+// added on the bit pattern.  Scaling by a power of two commutes with rounding in the normal
+// range, so these are exactly the IEEE quotients (encoders never store scales below 2^-100).
+__device__ __forceinline__ float sf_over_255(uint32_t sfb, uint32_t rec0) {
+  const uint32_t q = lds_ld1(rec0 + (sfb & 0x7Fu) * 8);
+  return sfb ? u2f(q + (((sfb >> 7) - 127u) << 23)) : 0.0f;
+}
+__device__ __forceinline__ float c255_over_sf(uint32_t sfb, uint32_t rec0) {
+  const uint32_t q = lds_ld1(rec0 + (sfb & 0x7Fu) * 8 + 4);
+  return sfb ? u2f(q - (((sfb >> 7) - 127u) << 23)) : 0.0f;
+}
+
+// One wave tile of compress / DAR: up to 4 super-groups of width B.
+//   lds0     : LDS byte address of the table blob
+//   stage    : LDS byte address of this tile's 8 parked draws (row r: [2r] = permutation
+//              stream, [2r+1] = group-scale stream), 16 bytes each
+template <int B, Kind KIND, typename LT>
+__device__ __forceinline__ void tile(const Job &job, const Params &P, uint32_t lds0, uint32_t stage,
+                                     const TilePos pos) {
+  using W = Width<B>;
+  static_assert(KIND != kDecompress, "decompress has its own tile function");
+  const TileBase<B> tb(job, pos);
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t g = lane & 15u;
+  const uint32_t row = lane >> 4;
+  const bool active = row <= tb.last_row;
+  const uint32_t rowc = min(row, tb.last_row);  // idle rows redo the last SG and store nothing
+  const uint32_t lg = rowc * 16 + g;            // group index inside the tile
+  const uint32_t rec0 = lds0 + P.off_rec * 4;
+
+  // ------------------------------------------------------------------ fetch
+  float v[16];
   if constexpr (sizeof(LT) == 4) {  // fp32: 4 x 128 bit
-    const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + first);
+    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float4 t = p[i];
-      loc[4 * i] = t.x; loc[4 * i + 1] = t.y; loc[4 * i + 2] = t.z; loc[4 * i + 3] = t.w;
+      const uint4 x = p[i];
+      v[4 * i] = u2f(x.x); v[4 * i + 1] = u2f(x.y); v[4 * i + 2] = u2f(x.z); v[4 * i + 3] = u2f(x.w);
     }
   } else {  // bf16: 2 x 128 bit, widened exactly
-    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + first);
+    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const uint4 t = p[i];
-      const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+      const uint4 x = p[i];
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        loc[8 * i + 2 * j] = u2f(w[j] << 16);
-        loc[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
+        v[8 * i + 2 * j] = u2f(w[j] << 16);
+        v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
       }
     }
+  }
+
+  if constexpr (KIND == kDar) {
+    uint32_t cw[W::words];
+    const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
+    if constexpr (B == 2) {
+      cw[0] = *reinterpret_cast<const uint32_t *>(cp);
+    } else if constexpr (B == 4) {
+      const uint2 t = *reinterpret_cast<const uint2 *>(cp);
+      cw[0] = t.x; cw[1] = t.y;
+    } else {
+      const uint4 t = *reinterpret_cast<const uint4 *>(cp);
+      cw[0] = t.x; cw[1] = t.y; cw[2] = t.z; cw[3] = t.w;
+    }
+    const uint32_t rg_in = job.in[tb.gs_off + lg];
+    const uint32_t sf_in = *reinterpret_cast<const uint16_t *>(job.in + tb.sf_off + rowc * 2);
+    // decode: sf_G = r_G * (sf_SG / 255); estimate = +-T[r] * sf_G, accumulated by one fma
+    const float sfg = (float)rg_in * sf_over_255(sf_in, rec0);
+    const uint32_t dec0 = lds0 + P.off_dec[W::wi] * 4;
+#pragma unroll
+    for (int j = 0; j < 2 * B; ++j) {  // one table entry per code byte
+      const uint32_t byte = (cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+      if constexpr (B == 2) {
+        const u32x4 e = lds_ld4(dec0 + byte * 16);
+        v[4 * j] = __builtin_fmaf(u2f(e.x), sfg, v[4 * j]);
+        v[4 * j + 1] = __builtin_fmaf(u2f(e.y), sfg, v[4 * j + 1]);
+        v[4 * j + 2] = __builtin_fmaf(u2f(e.z), sfg, v[4 * j + 2]);
+        v[4 * j + 3] = __builtin_fmaf(u2f(e.w), sfg, v[4 * j + 3]);
+      } else if constexpr (B == 4) {
+        const u32x2 e = lds_ld2(dec0 + byte * 8);
+        v[2 * j] = __builtin_fmaf(u2f(e.x), sfg, v[2 * j]);
+        v[2 * j + 1] = __builtin_fmaf(u2f(e.y), sfg, v[2 * j + 1]);
+      } else {
+        v[j] = __builtin_fmaf(u2f(lds_ld1(dec0 + byte * 4)), sfg, v[j]);
+      }
+    }
+  }
+
+  // ------------------------------------------------------------------ random numbers
+  const uint64_t gi = (tb.G0 + rowc) * 16 + g;  // global group index
+  // stream 0: one byte per entry, private to the worker
+  const U4 gam = philox4x32_10((uint32_t)gi, (uint32_t)(gi >> 32), P.round, job.rank & 0xFFFFu, P.key0, P.key1);
+  // parked per-SG draws: word 0 of the shared stream -> cyclic shift; byte g of the private
+  // stream -> this group's scale dither
+  const uint32_t perm_w0 = lds_ld1(stage + rowc * 32);
+  const uint32_t sc_word = lds_ld1(stage + rowc * 32 + 16 + (g >> 2) * 4);
+  const uint32_t scale_byte = (sc_word >> (8 * (g & 3u))) & 0xFFu;
+  const uint32_t shift = __umulhi(perm_w0, P.n_workers);
+  uint32_t slot = job.rank + shift + g;
+  slot = (P.n_mask != 0xFFFFFFFFu) ? (slot & P.n_mask) : (slot % P.n_workers);
+  const float o_pi = ((float)slot + (1.0f / 512.0f)) * P.inv_n;
+
+  // ------------------------------------------------------------------ scales
+  float m = 0.0f;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) m = fmaxf(m, fabsf(v[k]));
+  const float M = row_max16(m);
+  uint32_t sfb = f2u(M) >> 16;
+  sfb += (f2u(M) & 0xFFFFu) ? 1u : 0u;  // smallest bf16 >= M
+  if (sfb < 0x0D80u) sfb = 0;           // below 2^-100: the SG is encoded as zero
+  const float cs = c255_over_sf(sfb, rec0);
+  const float ts = fminf(m * cs, 255.0f);
+  const float fl = floorf(ts);
+  const float us = ((float)scale_byte + 0.5f) * (1.0f / 256.0f);
+  const uint32_t rg = sfb ? (uint32_t)fl + ((us < ts - fl) ? 1u : 0u) : 0u;
+  // a group whose scale rounds to zero keeps only its signs; its entries are not normalised
+  const float inv = rg ? 1.0f / m : 0.0f;
+
+  // ------------------------------------------------------------------ entries
+  // level indices and sign bits are collected separately: the sign bits by one funnel shift
+  // per entry (entry 0 last, so it lands in bit 0), spread to their code positions at the end
+  uint32_t ow[W::words];
+  uint32_t sbits = 0;
+  const uint32_t gw[4] = {gam.x, gam.y, gam.z, gam.w};
+  if constexpr (B == 2) {
+    // levels {0,1}: T + u*D = u, so the level bit is [u < x']
+    uint32_t rbits = 0;
+#pragma unroll
+    for (int k = 15; k >= 0; --k) {
+      const float x = __builtin_amdgcn_fmed3f(fabsf(v[k]) * inv, 0.0f, 1.0f);
+      const uint32_t byte = (gw[k >> 2] >> (8 * (k & 3))) & 0xFFu;
+      const float u = __builtin_fmaf((float)byte, P.s_n, o_pi);
+      rbits = rbits + rbits + ((u < x) ? 1u : 0u);
+      sbits = __builtin_amdgcn_alignbit(sbits, f2u(v[k]), 31);  // (sbits << 1) | sign
+    }
+    ow[0] = (rg ? spread16(rbits) : 0u) | (spread16(sbits & 0xFFFFu) << 1);
+  } else {
+    const float magic = P.magic[W::wi];
+    // byte address of lut[q] is lut0 + 8*q with q = bits(x + magic) - bits(magic)
+    const uint32_t lut_k = lds0 + P.off_lut[W::wi] * 4 - (f2u(magic) << 3);
+    const uint32_t tab0 = lds0 + P.off_tab[W::wi] * 4;
+    constexpr int per_word = 32 / B;
+#pragma unroll
+    for (int i = 0; i < W::words; ++i) ow[i] = 0;
+#pragma unroll
+    for (int k = 15; k >= 0; --k) {
+      const float x = __builtin_amdgcn_fmed3f(fabsf(v[k]) * inv, 0.0f, 1.0f);
+      const uint32_t byte = (gw[k >> 2] >> (8 * (k & 3))) & 0xFFu;
+      const float u = __builtin_fmaf((float)byte, P.s_n, o_pi);
+      const u32x2 e = lds_ld2((f2u(x + magic) << 3) + lut_k);
+      const uint32_t rlo = e.y + ((x >= u2f(e.x)) ? 1u : 0u);
+      const u32x2 td = lds_ld2(tab0 + rlo * 8);
+      const uint32_t r = rlo + ((__builtin_fmaf(u, u2f(td.y), u2f(td.x)) < x) ? 1u : 0u);
+      ow[k / per_word] |= r << ((k % per_word) * B);
+      sbits = __builtin_amdgcn_alignbit(sbits, f2u(v[k]), 31);
+    }
+    if constexpr (B == 4) {
+      // sign of entry k -> bit 4k+3: a 256-entry table spreads 8 sign bits over a word
+      const uint32_t sp0 = lds0 + P.off_spread4 * 4;
+      const uint32_t s0 = lds_ld1(sp0 + (sbits & 0xFFu) * 4), s1 = lds_ld1(sp0 + ((sbits >> 8) & 0xFFu) * 4);
+      ow[0] = (rg ? ow[0] : 0u) | s0;
+      ow[1] = (rg ? ow[1] : 0u) | s1;
+    } else {
+      // sign of entry k -> bit 8k+7: x * 0x00204081 puts bit i of a nibble at bit 7i (+...), masked to bytes
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t nib = (sbits >> (4 * i)) & 0xFu;
+        const uint32_t sp = ((nib * 0x00204081u) & 0x01010101u) << 7;
+        ow[i] = (rg ? ow[i] : 0u) | sp;
+      }
+    }
+  }
+
+  // ------------------------------------------------------------------ store
+  if (active) {
+    uint8_t *out = static_cast<uint8_t *>(job.out);
+    uint8_t *cp = out + tb.code_off + lg * (2 * B);
+    if constexpr (B == 2) {
+      *reinterpret_cast<uint32_t *>(cp) = ow[0];
+    } else if constexpr (B == 4) {
+      *reinterpret_cast<uint2 *>(cp) = make_uint2(ow[0], ow[1]);
+    } else {
+      *reinterpret_cast<uint4 *>(cp) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    }
+    out[tb.gs_off + lg] = (uint8_t)rg;
+    if (g == 0) *reinterpret_cast<uint16_t *>(out + tb.sf_off + rowc * 2) = (uint16_t)sfb;
   }
 }
 
-// One wave tile: up to 4 super-groups of width B.
-//   seg_first : position in the chunk of the first SG of this width
-//   n_seg     : SGs of this width in the chunk (>= 1)
-//   tile_first: first SG of the tile inside the segment
-//   code_off  : byte offset of this width's code array inside a packed buffer
-template <int B, Kind KIND, typename LT>
-__device__ __forceinline__ void tile(const Job &job, const Params &P, const uint32_t *lds, uint32_t seg_first,
-                                     uint32_t n_seg, uint32_t tile_first, size_t code_off) {
+// One wave tile of decompress(+accumulate).  Here a lane owns 4 consecutive entries of each
+// of the tile's super-groups (one SG per step), so that every load and the fp32 store of a
+// step cover contiguous memory across the wave.
+template <int B, typename LT>
+__device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_t lds0, const TilePos pos) {
   using W = Width<B>;
   constexpr bool kHasLocal = !__is_same(LT, NoLocal);
+  const TileBase<B> tb(job, pos);
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t g = lane & 15u;
-  const uint32_t sgw_raw = tile_first + (lane >> 4);
-  const bool active = sgw_raw < n_seg;
-  const uint32_t sgw = active ? sgw_raw : n_seg - 1;  // idle rows redo the last SG and store nothing
-  const uint32_t sgj = seg_first + sgw;               // position in the chunk
-  const size_t n_all = (size_t)job.n_sg[0] + job.n_sg[1] + job.n_sg[2];
-  const size_t gs_off = 64 * (size_t)job.n_sg[0] + 128 * (size_t)job.n_sg[1] + 256 * (size_t)job.n_sg[2];
-  const size_t sf_off = gs_off + 16 * n_all;
-  const size_t code_at = code_off + ((size_t)sgw * 16 + g) * (2 * B);
-
-  float v[16];
-  // ------------------------------------------------------------------ gather inputs
-  if constexpr (kHasLocal) load_local<LT>(job.local, (size_t)sgj * kSG + g * kGroup, v);
-
-  if constexpr (KIND != kCompress) {
-    uint32_t cw[W::words];
+  const uint32_t rec0 = lds0 + P.off_rec * 4;
+  const uint32_t dec0 = lds0 + P.off_dec[W::wi] * 4;
+  float *outp = static_cast<float *>(job.out) + tb.first_entry;
+#pragma unroll
+  for (uint32_t i = 0; i < (uint32_t)kWaveSGs; ++i) {
+    if (i > tb.last_row) break;
+    // 4 codes = B/2 bytes per lane
+    uint32_t cw;
+    const uint8_t *cp = job.in + tb.code_off + i * (32 * B) + lane * (B / 2);
+    if constexpr (B == 2) cw = *cp;
+    else if constexpr (B == 4) cw = *reinterpret_cast<const uint16_t *>(cp);
+    else cw = *reinterpret_cast<const uint32_t *>(cp);
+    const uint32_t rg_in = job.in[tb.gs_off + i * 16 + (lane >> 2)];
+    const uint32_t sf_in = *reinterpret_cast<const uint16_t *>(job.in + tb.sf_off + i * 2);
+    float loc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (kHasLocal) {
+      if constexpr (sizeof(LT) == 4) {
+        const float4 x = reinterpret_cast<const float4 *>(static_cast<const float *>(job.local) + tb.first_entry + i * kSG)[lane];
+        loc[0] = x.x; loc[1] = x.y; loc[2] = x.z; loc[3] = x.w;
+      } else {
+        const uint2 x = reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry + i * kSG)[lane];
+        loc[0] = u2f(x.x << 16); loc[1] = u2f(x.x & 0xFFFF0000u);
+        loc[2] = u2f(x.y << 16); loc[3] = u2f(x.y & 0xFFFF0000u);
+      }
+    }
+    const float sfg = (float)rg_in * sf_over_255(sf_in, rec0);
+    float t[4];
     if constexpr (B == 2) {
-      cw[0] = *reinterpret_cast<const uint32_t *>(job.in + code_at);
+      const u32x4 e = lds_ld4(dec0 + (cw & 0xFFu) * 16);
+      t[0] = u2f(e.x); t[1] = u2f(e.y); t[2] = u2f(e.z); t[3] = u2f(e.w);
     } else if constexpr (B == 4) {
-      const uint2 t = *reinterpret_cast<const uint2 *>(job.in + code_at);
-      cw[0] = t.x; cw[1] = t.y;
+      const u32x2 e0 = lds_ld2(dec0 + (cw & 0xFFu) * 8), e1 = lds_ld2(dec0 + ((cw >> 8) & 0xFFu) * 8);
+      t[0] = u2f(e0.x); t[1] = u2f(e0.y); t[2] = u2f(e1.x); t[3] = u2f(e1.y);
     } else {
-      const uint4 t = *reinterpret_cast<const uint4 *>(job.in + code_at);
-      cw[0] = t.x; cw[1] = t.y; cw[2] = t.z; cw[3] = t.w;
-    }
-    const uint32_t rg_in = job.in[gs_off + (size_t)sgj * 16 + g];
-    const uint32_t sf_in = *reinterpret_cast<const uint16_t *>(job.in + sf_off + (size_t)sgj * 2);
-    // decode: sf_G = r_G * (sf_SG / 255); estimate = +-T[r] * sf_G, accumulated by one fma
-    const float step = u2f(sf_in << 16) / 255.0f;
-    const float sfg = (float)rg_in * step;
-    const uint32_t *dec = lds + P.off_dec[W::wi];
-    constexpr int per_word = 32 / B;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      const uint32_t code = (cw[k / per_word] >> ((k % per_word) * B)) & ((1u << B) - 1u);
-      const float t = u2f(dec[code]);
-      if constexpr (kHasLocal) v[k] = __builtin_fmaf(t, sfg, v[k]);
-      else v[k] = t * sfg;
+      for (int k = 0; k < 4; ++k) t[k] = u2f(lds_ld1(dec0 + ((cw >> (8 * k)) & 0xFFu) * 4));
     }
-  }
-
-  if constexpr (KIND == kDecompress) {
-    if (active) {
-      float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(job.out) + (size_t)sgj * kSG + g * kGroup);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) o[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+    float4 o;
+    if constexpr (kHasLocal) {
+      o = make_float4(__builtin_fmaf(t[0], sfg, loc[0]), __builtin_fmaf(t[1], sfg, loc[1]),
+                      __builtin_fmaf(t[2], sfg, loc[2]), __builtin_fmaf(t[3], sfg, loc[3]));
+    } else {
+      o = make_float4(t[0] * sfg, t[1] * sfg, t[2] * sfg, t[3] * sfg);
     }
-    return;
-  } else {
-    // ---------------------------------------------------------------- random numbers
-    const uint64_t G = job.first_sg + sgj;  // global super-group index
-    const uint64_t gi = G * 16 + g;         // global group index
-    // stream 0: one byte per entry, private to the worker
-    const U4 gam = philox4x32_10((uint32_t)gi, (uint32_t)(gi >> 32), P.round, job.rank & 0xFFFFu, P.key0, P.key1);
-    // streams 1 (group-scale bytes, private) and 2 (shared cyclic shift) are per SG: lane 0 of
-    // the row draws stream 2, the others draw stream 1, then the row exchanges the words
-    const uint32_t c3 = (g == 0) ? ((2u << 16) | 0xFFFFu) : ((1u << 16) | (job.rank & 0xFFFFu));
-    const U4 sgr = philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), P.round, c3, P.key0, P.key1);
-    const uint32_t row0 = lane & ~15u;
-    const uint32_t perm_w0 = __shfl(sgr.x, row0);
-    // lanes 1..15 all hold the stream-1 words; group g's scale byte sits in word g>>2
-    const uint32_t w_mine = (g >> 2) == 0 ? sgr.x : (g >> 2) == 1 ? sgr.y : (g >> 2) == 2 ? sgr.z : sgr.w;
-    // lane 0 did not draw stream 1: it needs word 0 of a neighbour
-    const uint32_t w_nb = __shfl(sgr.x, row0 + 1);
-    const uint32_t sc_word = (g == 0) ? w_nb : w_mine;
-    const uint32_t scale_byte = (sc_word >> (8 * (g & 3u))) & 0xFFu;
-    const uint32_t shift = __umulhi(perm_w0, P.n_workers);
-    uint32_t slot = job.rank + shift + g;
-    slot = (P.n_mask != 0xFFFFFFFFu) ? (slot & P.n_mask) : (slot % P.n_workers);
-    const float o_pi = ((float)slot + (1.0f / 512.0f)) * P.inv_n;
-
-    // ---------------------------------------------------------------- scales
-    float m = 0.0f;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) m = fmaxf(m, fabsf(v[k]));
-    const float M = row_max16(m);
-    uint32_t sfb = f2u(M) >> 16;
-    sfb += (f2u(M) & 0xFFFFu) ? 1u : 0u;  // smallest bf16 >= M
-    if (sfb < 0x0D80u) sfb = 0;           // below 2^-100: the SG is encoded as zero
-    const float sf = u2f(sfb << 16);
-    const float cs = sfb ? 255.0f / sf : 0.0f;
-    const float t = fminf(m * cs, 255.0f);
-    const float fl = floorf(t);
-    const float us = ((float)scale_byte + 0.5f) * (1.0f / 256.0f);
-    const uint32_t rg = sfb ? (uint32_t)fl + ((us < t - fl) ? 1u : 0u) : 0u;
-    const float inv = 1.0f / m;  // unused (and possibly inf) when rg == 0
-
-    // ---------------------------------------------------------------- entries
-    uint32_t ow[W::words];
-#pragma unroll
-    for (int i = 0; i < W::words; ++i) ow[i] = 0;
-    const uint32_t gw[4] = {gam.x, gam.y, gam.z, gam.w};
-    constexpr int per_word = 32 / B;
-    const float magic = P.magic[W::wi];
-    const uint2 *lut = reinterpret_cast<const uint2 *>(lds + P.off_lut[W::wi]);
-    const uint2 *tab = reinterpret_cast<const uint2 *>(lds + P.off_tab[W::wi]);
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-      const float x = fminf(fabsf(v[k]) * inv, 1.0f);
-      const uint32_t byte = (gw[k >> 2] >> (8 * (k & 3))) & 0xFFu;
-      const float u = __builtin_fmaf((float)byte, P.s_n, o_pi);
-      uint32_t r;
-      if constexpr (B == 2) {
-        r = (u < x) ? 1u : 0u;  // levels {0,1}: T + u*D = u
-      } else {
-        const uint32_t q = f2u(x + magic) - f2u(magic);  // round(x * 2^m)
-        const uint2 e = lut[q];
-        const uint32_t rlo = e.y + ((x >= u2f(e.x)) ? 1u : 0u);
-        const uint2 td = tab[rlo];
-        r = rlo + ((__builtin_fmaf(u, u2f(td.y), u2f(td.x)) < x) ? 1u : 0u);
-      }
-      r = rg ? r : 0u;
-      const uint32_t code = ((f2u(v[k]) >> 31) << (B - 1)) | r;
-      ow[k / per_word] |= code << ((k % per_word) * B);
-    }
-
-    // ---------------------------------------------------------------- store
-    if (active) {
-      uint8_t *out = static_cast<uint8_t *>(job.out);
-      if constexpr (B == 2) {
-        *reinterpret_cast<uint32_t *>(out + code_at) = ow[0];
-      } else if constexpr (B == 4) {
-        *reinterpret_cast<uint2 *>(out + code_at) = make_uint2(ow[0], ow[1]);
-      } else {
-        *reinterpret_cast<uint4 *>(out + code_at) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-      }
-      out[gs_off + (size_t)sgj * 16 + g] = (uint8_t)rg;
-      if (g == 0) *reinterpret_cast<uint16_t *>(out + sf_off + (size_t)sgj * 2) = (uint16_t)sfb;
-    }
+    reinterpret_cast<float4 *>(outp + i * kSG)[lane] = o;
   }
 }
 
 template <Kind KIND, typename LT>
 __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
-  extern __shared__ uint32_t lds[];
-  for (uint32_t i = threadIdx.x * 4; i < P.blob_dwords; i += kBlockThreads * 4)
-    *reinterpret_cast<uint4 *>(&lds[i]) = *reinterpret_cast<const uint4 *>(&P.blob[i]);
-  __syncthreads();
+  extern __shared__ uint4 lds_raw[];
+  uint32_t *lds = reinterpret_cast<uint32_t *>(lds_raw);
   const uint32_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2];
   const uint32_t t0 = (n0 + kWaveSGs - 1) / kWaveSGs, t1 = (n1 + kWaveSGs - 1) / kWaveSGs,
                  t2 = (n2 + kWaveSGs - 1) / kWaveSGs;
   const uint32_t total = t0 + t1 + t2;
+  const uint32_t tpw = P.tiles_per_wave;
+  // this block's tiles: [b_lo, b_hi); wave w of the block takes [b_lo + w*tpw, +tpw)
+  const uint32_t b_lo = blockIdx.x * kBlockWaves * tpw;
+  if (b_lo >= total) return;
+  const uint32_t b_hi = min(b_lo + kBlockWaves * tpw, total);
+  // copy the common tables and the table regions of the widths this block meets
+  const bool need[4] = {b_lo < t0, b_lo < t0 + t1 && b_hi > t0, b_hi > t0 + t1, true};
+#pragma unroll
+  for (int wi = 0; wi < 4; ++wi)
+    if (need[wi])
+      for (uint32_t i = P.reg_lo[wi] + threadIdx.x * 4; i < P.reg_hi[wi]; i += kBlockThreads * 4)
+        *reinterpret_cast<uint4 *>(&lds[i]) = *reinterpret_cast<const uint4 *>(&P.blob[i]);
+  __syncthreads();
+
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t *)lds;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  for (uint32_t t = blockIdx.x * kBlockWaves + wave; t < total; t += gridDim.x * kBlockWaves) {
-    if (t < t0) {
-      tile<2, KIND, LT>(job, P, lds, 0, n0, t * kWaveSGs, 0);
-    } else if (t < t0 + t1) {
-      tile<4, KIND, LT>(job, P, lds, n0, n1, (t - t0) * kWaveSGs, 64 * (size_t)n0);
-    } else {
-      tile<8, KIND, LT>(job, P, lds, n0 + n1, n2, (t - t0 - t1) * kWaveSGs, 64 * (size_t)n0 + 128 * (size_t)n1);
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t w_lo = b_lo + wave * tpw;
+  const uint32_t w_hi = min(w_lo + tpw, total);
+  if constexpr (KIND == kDecompress) {
+    for (uint32_t t = w_lo; t < w_hi; ++t) {
+      const TilePos p = locate(job, t);
+      if (p.wi == 0) tile_da<2, LT>(job, P, lds0, p);
+      else if (p.wi == 1) tile_da<4, LT>(job, P, lds0, p);
+      else tile_da<8, LT>(job, P, lds0, p);
+    }
+  } else {
+    // per-wave parking area for the per-SG draws of up to kBatch tiles: 64 x 16 bytes
+    const uint32_t stage0 = lds0 + P.blob_dwords * 4 + wave * (64 * 16);
+    for (uint32_t tb = w_lo; tb < w_hi; tb += kBatch) {
+      const uint32_t nb = min((uint32_t)kBatch, w_hi - tb);
+      {
+        // lane l draws for tile tb + l/8, row (l%8)/2: even l the shared permutation stream,
+        // odd l the worker's group-scale stream
+        const uint32_t j = min(lane >> 3, nb - 1);
+        const TilePos p = locate(job, tb + j);
+        const uint32_t sgw = min(p.tile_first + ((lane >> 1) & 3u), p.n_seg - 1);
+        const uint64_t G = job.first_sg + p.seg_first + sgw;
+        const uint32_t c3 = (lane & 1u) ? ((1u << 16) | (job.rank & 0xFFFFu)) : ((2u << 16) | 0xFFFFu);
+        const U4 d = philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), P.round, c3, P.key0, P.key1);
+        lds_st4(stage0 + lane * 16, u32x4{d.x, d.y, d.z, d.w});
+        __builtin_amdgcn_wave_barrier();
+      }
+      for (uint32_t j = 0; j < nb; ++j) {
+        const TilePos p = locate(job, tb + j);
+        const uint32_t stage = stage0 + j * 128;
+        if (p.wi == 0) tile<2, KIND, LT>(job, P, lds0, stage, p);
+        else if (p.wi == 1) tile<4, KIND, LT>(job, P, lds0, stage, p);
+        else tile<8, KIND, LT>(job, P, lds0, stage, p);
+      }
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
@@ -277,25 +460,35 @@ uint32_t job_tiles(const Job &j) {
          (j.n_sg[2] + kWaveSGs - 1) / kWaveSGs;
 }
 
+// How many consecutive tiles one wave takes: enough waves to keep every SIMD supplied with
+// fresh blocks when the launch is small, long runs (which share one per-SG draw) when large.
+uint32_t choose_tiles_per_wave(uint64_t total_tiles, uint32_t n_cu) {
+  const char *env = getenv("DQ_TILES_PER_WAVE");  // tuning / test knob
+  if (env && atoi(env) >= 1 && atoi(env) <= kBatch * 4) return (uint32_t)atoi(env);
+  const uint64_t t = total_tiles / ((uint64_t)n_cu * 64);
+  return (uint32_t)(t < 1 ? 1 : (t > kBatch ? kBatch : t));
+}
+
+size_t lds_bytes(const Params &p) { return (size_t)p.blob_dwords * 4 + kBlockWaves * 64 * 16; }
+
 template <Kind KIND, typename LT>
-hipError_t go_one(const Job &job, const Params &p, uint32_t n_cu, hipStream_t s) {
+hipError_t go_one(const Job &job, Params p, uint32_t n_cu, hipStream_t s) {
   const uint32_t tiles = job_tiles(job);
   if (tiles == 0) return hipSuccess;
-  uint32_t blocks = (tiles + kBlockWaves - 1) / kBlockWaves;
-  const uint32_t cap = n_cu * 8;
-  if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL((k_one<KIND, LT>), dim3(blocks), dim3(kBlockThreads), p.blob_dwords * 4, s, job, p);
+  p.tiles_per_wave = choose_tiles_per_wave(tiles, n_cu);
+  const uint32_t per_block = kBlockWaves * p.tiles_per_wave;
+  const uint32_t blocks = (tiles + per_block - 1) / per_block;
+  hipLaunchKernelGGL((k_one<KIND, LT>), dim3(blocks), dim3(kBlockThreads), lds_bytes(p), s, job, p);
   return hipGetLastError();
 }
 template <Kind KIND, typename LT>
-hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, const Params &p, uint32_t n_cu,
-                    hipStream_t s) {
+hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, uint64_t total_tiles, Params p,
+                    uint32_t n_cu, hipStream_t s) {
   if (n_jobs == 0 || max_tiles == 0) return hipSuccess;
-  uint32_t blocks = (max_tiles + kBlockWaves - 1) / kBlockWaves;
-  uint32_t cap = (n_cu * 8 + n_jobs - 1) / n_jobs;
-  if (cap < 1) cap = 1;
-  if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), p.blob_dwords * 4, s, jobs, p);
+  p.tiles_per_wave = choose_tiles_per_wave(total_tiles, n_cu);
+  const uint32_t per_block = kBlockWaves * p.tiles_per_wave;
+  const uint32_t blocks = (max_tiles + per_block - 1) / per_block;
+  hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), lds_bytes(p), s, jobs, p);
   return hipGetLastError();
 }
 
@@ -316,19 +509,19 @@ hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job,
 }
 
 hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, const Job *jobs, uint32_t n_jobs,
-                        uint32_t max_tiles, const Params &p, uint32_t n_cu, hipStream_t s) {
+                        uint32_t max_tiles, uint64_t total_tiles, const Params &p, uint32_t n_cu, hipStream_t s) {
   const bool f32 = dtype == DQ_F32;
   switch (kind) {
     case kCompress:
-      return f32 ? go_batch<kCompress, float>(jobs, n_jobs, max_tiles, p, n_cu, s)
-                 : go_batch<kCompress, uint16_t>(jobs, n_jobs, max_tiles, p, n_cu, s);
+      return f32 ? go_batch<kCompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s)
+                 : go_batch<kCompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
     case kDar:
-      return f32 ? go_batch<kDar, float>(jobs, n_jobs, max_tiles, p, n_cu, s)
-                 : go_batch<kDar, uint16_t>(jobs, n_jobs, max_tiles, p, n_cu, s);
+      return f32 ? go_batch<kDar, float>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s)
+                 : go_batch<kDar, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
     default:
-      if (!has_local) return go_batch<kDecompress, NoLocal>(jobs, n_jobs, max_tiles, p, n_cu, s);
-      return f32 ? go_batch<kDecompress, float>(jobs, n_jobs, max_tiles, p, n_cu, s)
-                 : go_batch<kDecompress, uint16_t>(jobs, n_jobs, max_tiles, p, n_cu, s);
+      if (!has_local) return go_batch<kDecompress, NoLocal>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
+      return f32 ? go_batch<kDecompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s)
+                 : go_batch<kDecompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
   }
 }
 

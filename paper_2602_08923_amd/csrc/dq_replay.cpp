@@ -28,6 +28,7 @@ struct Launch {
   std::vector<HostJob> jobs;
   size_t table_off = 0;  // byte offset of this launch's job table in scratch
   uint32_t max_tiles = 0;
+  uint64_t total_tiles = 0;
   uint64_t max_entries = 0;
   uint64_t entries = 0;
 };
@@ -243,6 +244,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
         const uint32_t tiles = (j.n_sg[0] + 3) / 4 + (j.n_sg[1] + 3) / 4 + (j.n_sg[2] + 3) / 4;
         const uint64_t e = ((uint64_t)j.n_sg[0] + j.n_sg[1] + j.n_sg[2]) * 256;
         if (tiles > L.max_tiles) L.max_tiles = tiles;
+        L.total_tiles += tiles;
         if (e > L.max_entries) L.max_entries = e;
         L.entries += e;
       }
@@ -348,7 +350,7 @@ static dq_status run_step(dq_replay *plan, size_t i, hipStream_t s) {
                               (uint32_t)L.jobs.size(), L.max_entries, plan->ctx->n_cu, s);
     else
       e = dq::launch_batch(L.kind, L.dtype, true, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
-                           (uint32_t)L.jobs.size(), L.max_tiles, plan->ctx->params, plan->ctx->n_cu, s);
+                           (uint32_t)L.jobs.size(), L.max_tiles, L.total_tiles, plan->ctx->params, plan->ctx->n_cu, s);
     if (e != hipSuccess) return DQ_EHIP;
   }
   return DQ_OK;
