@@ -209,7 +209,6 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
   P.n_mask = (cfg->n_workers & (cfg->n_workers - 1)) == 0 ? cfg->n_workers - 1 : 0xFFFFFFFFu;
   P.inv_n = 1.0f / (float)cfg->n_workers;
   P.s_n = P.inv_n * (1.0f / 256.0f);
-  P.tiles_per_wave = 0;  // chosen per launch
   ctx->params = P;
   *out = ctx;
   return DQ_OK;

@@ -42,7 +42,6 @@ struct Params {
   uint32_t n_workers;
   uint32_t n_mask;       // n-1 if n is a power of two, else 0xFFFFFFFF (meaning: use %)
   float inv_n, s_n;
-  uint32_t tiles_per_wave;  // launch shape only: how many consecutive tiles one wave takes (1..8)
 };
 
 enum Kind { kCompress = 0, kDar = 1, kDecompress = 2 };

@@ -43,6 +43,24 @@ __device__ __forceinline__ u32x2 lds_ld2(uint32_t a) { return *reinterpret_cast<
 __device__ __forceinline__ u32x4 lds_ld4(uint32_t a) { return *reinterpret_cast<lds_u4 *>(a); }
 __device__ __forceinline__ void lds_st4(uint32_t a, u32x4 v) { *reinterpret_cast<lds_w4 *>(a) = v; }
 
+// Global-memory accesses through explicit address-space-1 pointers.  The job's pointers reach
+// the kernel inside a struct, where the compiler would otherwise treat them as generic and
+// emit FLAT instructions; those also count on the LDS counter, so every wait for a table
+// lookup would wait for the outstanding global loads and stores as well.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <typename T>
+__device__ __forceinline__ T gld(const void *p) {
+  return *(const __attribute__((address_space(1))) T *)p;
+}
+template <typename T>
+__device__ __forceinline__ void gst(void *p, T v) {
+  *(__attribute__((address_space(1))) T *)p = v;
+}
+__device__ __forceinline__ uint4 gld16(const void *p) {
+  const u32x4 t = gld<u32x4>(p);
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // ---- Philox4x32-10 (Salmon et al., SC'11): counter-based, so every lane draws its numbers
 // from (global group index, round, stream, rank) alone.
 struct U4 {
@@ -147,13 +165,54 @@ __device__ __forceinline__ float c255_over_sf(uint32_t sfb, uint32_t rec0) {
   return sfb ? u2f(q - (((sfb >> 7) - 127u) << 23)) : 0.0f;
 }
 
-// One wave tile of compress / DAR: up to 4 super-groups of width B.
+// What one lane fetches for one tile of compress / DAR: raw words only.
+template <int B, Kind KIND, typename LT>
+struct Fetch {
+  uint4 loc[sizeof(LT) == 4 ? 4 : 2];  // the lane's 16 local entries
+  uint32_t cw[B / 2];                  // DAR: their incoming codes
+  uint32_t rg_in, sf_in;               // DAR: incoming group scale (u8) and SG scale (bf16 pattern)
+};
+
+template <int B, Kind KIND, typename LT>
+__device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePos pos) {
+  const TileBase<B> tb(job, pos);
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t rowc = min(lane >> 4, tb.last_row);  // idle rows redo the last SG and store nothing
+  const uint32_t lg = rowc * 16 + (lane & 15u);       // group index inside the tile
+  Fetch<B, KIND, LT> f;
+  if constexpr (sizeof(LT) == 4) {  // fp32: 4 x 128 bit
+    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f.loc[i] = gld16(p + i);
+  } else {  // bf16: 2 x 128 bit
+    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
+    f.loc[0] = gld16(p);
+    f.loc[1] = gld16(p + 1);
+  }
+  if constexpr (KIND == kDar) {
+    const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
+    if constexpr (B == 2) {
+      f.cw[0] = gld<uint32_t>(cp);
+    } else if constexpr (B == 4) {
+      const u32x2 t = gld<u32x2>(cp);
+      f.cw[0] = t.x; f.cw[1] = t.y;
+    } else {
+      const u32x4 t = gld<u32x4>(cp);
+      f.cw[0] = t.x; f.cw[1] = t.y; f.cw[2] = t.z; f.cw[3] = t.w;
+    }
+    f.rg_in = gld<uint8_t>(job.in + tb.gs_off + lg);
+    f.sf_in = gld<uint16_t>(job.in + tb.sf_off + rowc * 2);
+  }
+  return f;
+}
+
+// One wave tile of compress / DAR after the fetch: up to 4 super-groups of width B.
 //   lds0     : LDS byte address of the table blob
 //   stage    : LDS byte address of this tile's 8 parked draws (row r: [2r] = permutation
 //              stream, [2r+1] = group-scale stream), 16 bytes each
 template <int B, Kind KIND, typename LT>
-__device__ __forceinline__ void tile(const Job &job, const Params &P, uint32_t lds0, uint32_t stage,
-                                     const TilePos pos) {
+__device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_t lds0, uint32_t stage,
+                                        const TilePos pos, const Fetch<B, KIND, LT> &f) {
   using W = Width<B>;
   static_assert(KIND != kDecompress, "decompress has its own tile function");
   const TileBase<B> tb(job, pos);
@@ -161,25 +220,21 @@ __device__ __forceinline__ void tile(const Job &job, const Params &P, uint32_t l
   const uint32_t g = lane & 15u;
   const uint32_t row = lane >> 4;
   const bool active = row <= tb.last_row;
-  const uint32_t rowc = min(row, tb.last_row);  // idle rows redo the last SG and store nothing
-  const uint32_t lg = rowc * 16 + g;            // group index inside the tile
+  const uint32_t rowc = min(row, tb.last_row);
+  const uint32_t lg = rowc * 16 + g;
   const uint32_t rec0 = lds0 + P.off_rec * 4;
 
-  // ------------------------------------------------------------------ fetch
   float v[16];
-  if constexpr (sizeof(LT) == 4) {  // fp32: 4 x 128 bit
-    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
+  if constexpr (sizeof(LT) == 4) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint4 x = p[i];
-      v[4 * i] = u2f(x.x); v[4 * i + 1] = u2f(x.y); v[4 * i + 2] = u2f(x.z); v[4 * i + 3] = u2f(x.w);
+      v[4 * i] = u2f(f.loc[i].x); v[4 * i + 1] = u2f(f.loc[i].y);
+      v[4 * i + 2] = u2f(f.loc[i].z); v[4 * i + 3] = u2f(f.loc[i].w);
     }
-  } else {  // bf16: 2 x 128 bit, widened exactly
-    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
+  } else {  // bf16 widens exactly
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const uint4 x = p[i];
-      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+      const uint32_t w[4] = {f.loc[i].x, f.loc[i].y, f.loc[i].z, f.loc[i].w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         v[8 * i + 2 * j] = u2f(w[j] << 16);
@@ -189,25 +244,12 @@ __device__ __forceinline__ void tile(const Job &job, const Params &P, uint32_t l
   }
 
   if constexpr (KIND == kDar) {
-    uint32_t cw[W::words];
-    const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
-    if constexpr (B == 2) {
-      cw[0] = *reinterpret_cast<const uint32_t *>(cp);
-    } else if constexpr (B == 4) {
-      const uint2 t = *reinterpret_cast<const uint2 *>(cp);
-      cw[0] = t.x; cw[1] = t.y;
-    } else {
-      const uint4 t = *reinterpret_cast<const uint4 *>(cp);
-      cw[0] = t.x; cw[1] = t.y; cw[2] = t.z; cw[3] = t.w;
-    }
-    const uint32_t rg_in = job.in[tb.gs_off + lg];
-    const uint32_t sf_in = *reinterpret_cast<const uint16_t *>(job.in + tb.sf_off + rowc * 2);
     // decode: sf_G = r_G * (sf_SG / 255); estimate = +-T[r] * sf_G, accumulated by one fma
-    const float sfg = (float)rg_in * sf_over_255(sf_in, rec0);
+    const float sfg = (float)f.rg_in * sf_over_255(f.sf_in, rec0);
     const uint32_t dec0 = lds0 + P.off_dec[W::wi] * 4;
 #pragma unroll
     for (int j = 0; j < 2 * B; ++j) {  // one table entry per code byte
-      const uint32_t byte = (cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+      const uint32_t byte = (f.cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
       if constexpr (B == 2) {
         const u32x4 e = lds_ld4(dec0 + byte * 16);
         v[4 * j] = __builtin_fmaf(u2f(e.x), sfg, v[4 * j]);
@@ -314,14 +356,14 @@ __device__ __forceinline__ void tile(const Job &job, const Params &P, uint32_t l
     uint8_t *out = static_cast<uint8_t *>(job.out);
     uint8_t *cp = out + tb.code_off + lg * (2 * B);
     if constexpr (B == 2) {
-      *reinterpret_cast<uint32_t *>(cp) = ow[0];
+      gst<uint32_t>(cp, ow[0]);
     } else if constexpr (B == 4) {
-      *reinterpret_cast<uint2 *>(cp) = make_uint2(ow[0], ow[1]);
+      gst<u32x2>(cp, u32x2{ow[0], ow[1]});
     } else {
-      *reinterpret_cast<uint4 *>(cp) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+      gst<u32x4>(cp, u32x4{ow[0], ow[1], ow[2], ow[3]});
     }
-    out[tb.gs_off + lg] = (uint8_t)rg;
-    if (g == 0) *reinterpret_cast<uint16_t *>(out + tb.sf_off + rowc * 2) = (uint16_t)sfb;
+    gst<uint8_t>(out + tb.gs_off + lg, (uint8_t)rg);
+    if (g == 0) gst<uint16_t>(out + tb.sf_off + rowc * 2, (uint16_t)sfb);
   }
 }
 
@@ -343,18 +385,18 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
     // 4 codes = B/2 bytes per lane
     uint32_t cw;
     const uint8_t *cp = job.in + tb.code_off + i * (32 * B) + lane * (B / 2);
-    if constexpr (B == 2) cw = *cp;
-    else if constexpr (B == 4) cw = *reinterpret_cast<const uint16_t *>(cp);
-    else cw = *reinterpret_cast<const uint32_t *>(cp);
-    const uint32_t rg_in = job.in[tb.gs_off + i * 16 + (lane >> 2)];
-    const uint32_t sf_in = *reinterpret_cast<const uint16_t *>(job.in + tb.sf_off + i * 2);
+    if constexpr (B == 2) cw = gld<uint8_t>(cp);
+    else if constexpr (B == 4) cw = gld<uint16_t>(cp);
+    else cw = gld<uint32_t>(cp);
+    const uint32_t rg_in = gld<uint8_t>(job.in + tb.gs_off + i * 16 + (lane >> 2));
+    const uint32_t sf_in = gld<uint16_t>(job.in + tb.sf_off + i * 2);
     float loc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if constexpr (kHasLocal) {
       if constexpr (sizeof(LT) == 4) {
-        const float4 x = reinterpret_cast<const float4 *>(static_cast<const float *>(job.local) + tb.first_entry + i * kSG)[lane];
+        const f32x4 x = gld<f32x4>(reinterpret_cast<const float4 *>(static_cast<const float *>(job.local) + tb.first_entry + i * kSG) + lane);
         loc[0] = x.x; loc[1] = x.y; loc[2] = x.z; loc[3] = x.w;
       } else {
-        const uint2 x = reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry + i * kSG)[lane];
+        const u32x2 x = gld<u32x2>(reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry + i * kSG) + lane);
         loc[0] = u2f(x.x << 16); loc[1] = u2f(x.x & 0xFFFF0000u);
         loc[2] = u2f(x.y << 16); loc[3] = u2f(x.y & 0xFFFF0000u);
       }
@@ -371,17 +413,33 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
 #pragma unroll
       for (int k = 0; k < 4; ++k) t[k] = u2f(lds_ld1(dec0 + ((cw >> (8 * k)) & 0xFFu) * 4));
     }
-    float4 o;
+    f32x4 o;
     if constexpr (kHasLocal) {
-      o = make_float4(__builtin_fmaf(t[0], sfg, loc[0]), __builtin_fmaf(t[1], sfg, loc[1]),
-                      __builtin_fmaf(t[2], sfg, loc[2]), __builtin_fmaf(t[3], sfg, loc[3]));
+      o = f32x4{__builtin_fmaf(t[0], sfg, loc[0]), __builtin_fmaf(t[1], sfg, loc[1]),
+                __builtin_fmaf(t[2], sfg, loc[2]), __builtin_fmaf(t[3], sfg, loc[3])};
     } else {
-      o = make_float4(t[0] * sfg, t[1] * sfg, t[2] * sfg, t[3] * sfg);
+      o = f32x4{t[0] * sfg, t[1] * sfg, t[2] * sfg, t[3] * sfg};
     }
-    reinterpret_cast<float4 *>(outp + i * kSG)[lane] = o;
+    gst<f32x4>(reinterpret_cast<float4 *>(outp + i * kSG) + lane, o);
   }
 }
 
+// `len` consecutive tiles of width B starting at `pos` (their parked draws 128 bytes apart).
+// Fetch and compute are separate steps, but measurements showed no gain from fetching a tile
+// ahead: the kernel is bound by instruction issue, not by memory latency.
+template <int B, Kind KIND, typename LT>
+__device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint32_t lds0, uint32_t stage, TilePos pos,
+                                          uint32_t len) {
+  for (uint32_t i = 0; i < len; ++i) {
+    const Fetch<B, KIND, LT> f = fetch<B, KIND, LT>(job, pos);
+    compute<B, KIND, LT>(job, P, lds0, stage + i * 128, pos, f);
+    pos.tile_first += kWaveSGs;
+  }
+}
+
+// The job's tiles are split evenly over all waves of the grid row (4 * gridDim.x waves):
+// wave w takes [w*T/W, (w+1)*T/W).  The launcher sizes the grid to what the GPU holds at
+// once, so a wave lives for the whole launch and the table copy is paid once.
 template <Kind KIND, typename LT>
 __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   extern __shared__ uint4 lds_raw[];
@@ -390,25 +448,25 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   const uint32_t t0 = (n0 + kWaveSGs - 1) / kWaveSGs, t1 = (n1 + kWaveSGs - 1) / kWaveSGs,
                  t2 = (n2 + kWaveSGs - 1) / kWaveSGs;
   const uint32_t total = t0 + t1 + t2;
-  const uint32_t tpw = P.tiles_per_wave;
-  // this block's tiles: [b_lo, b_hi); wave w of the block takes [b_lo + w*tpw, +tpw)
-  const uint32_t b_lo = blockIdx.x * kBlockWaves * tpw;
-  if (b_lo >= total) return;
-  const uint32_t b_hi = min(b_lo + kBlockWaves * tpw, total);
+  const uint64_t n_waves = (uint64_t)gridDim.x * kBlockWaves;
+  const uint32_t b_lo = (uint32_t)(((uint64_t)blockIdx.x * kBlockWaves) * total / n_waves);
+  const uint32_t b_hi = (uint32_t)(((uint64_t)(blockIdx.x + 1) * kBlockWaves) * total / n_waves);
+  if (b_lo >= b_hi) return;
   // copy the common tables and the table regions of the widths this block meets
   const bool need[4] = {b_lo < t0, b_lo < t0 + t1 && b_hi > t0, b_hi > t0 + t1, true};
 #pragma unroll
   for (int wi = 0; wi < 4; ++wi)
     if (need[wi])
       for (uint32_t i = P.reg_lo[wi] + threadIdx.x * 4; i < P.reg_hi[wi]; i += kBlockThreads * 4)
-        *reinterpret_cast<uint4 *>(&lds[i]) = *reinterpret_cast<const uint4 *>(&P.blob[i]);
+        *reinterpret_cast<uint4 *>(&lds[i]) = gld16(&P.blob[i]);
   __syncthreads();
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t *)lds;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t w_lo = b_lo + wave * tpw;
-  const uint32_t w_hi = min(w_lo + tpw, total);
+  const uint64_t wv = (uint64_t)blockIdx.x * kBlockWaves + wave;
+  const uint32_t w_lo = (uint32_t)(wv * total / n_waves);
+  const uint32_t w_hi = (uint32_t)((wv + 1) * total / n_waves);
   if constexpr (KIND == kDecompress) {
     for (uint32_t t = w_lo; t < w_hi; ++t) {
       const TilePos p = locate(job, t);
@@ -433,12 +491,15 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
         lds_st4(stage0 + lane * 16, u32x4{d.x, d.y, d.z, d.w});
         __builtin_amdgcn_wave_barrier();
       }
-      for (uint32_t j = 0; j < nb; ++j) {
+      for (uint32_t j = 0; j < nb;) {
         const TilePos p = locate(job, tb + j);
+        const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;  // tiles to the segment's end
+        const uint32_t len = min(nb - j, left);
         const uint32_t stage = stage0 + j * 128;
-        if (p.wi == 0) tile<2, KIND, LT>(job, P, lds0, stage, p);
-        else if (p.wi == 1) tile<4, KIND, LT>(job, P, lds0, stage, p);
-        else tile<8, KIND, LT>(job, P, lds0, stage, p);
+        if (p.wi == 0) run_tiles<2, KIND, LT>(job, P, lds0, stage, p, len);
+        else if (p.wi == 1) run_tiles<4, KIND, LT>(job, P, lds0, stage, p, len);
+        else run_tiles<8, KIND, LT>(job, P, lds0, stage, p, len);
+        j += len;
       }
       __builtin_amdgcn_wave_barrier();
     }
@@ -460,13 +521,16 @@ uint32_t job_tiles(const Job &j) {
          (j.n_sg[2] + kWaveSGs - 1) / kWaveSGs;
 }
 
-// How many consecutive tiles one wave takes: enough waves to keep every SIMD supplied with
-// fresh blocks when the launch is small, long runs (which share one per-SG draw) when large.
-uint32_t choose_tiles_per_wave(uint64_t total_tiles, uint32_t n_cu) {
-  const char *env = getenv("DQ_TILES_PER_WAVE");  // tuning / test knob
-  if (env && atoi(env) >= 1 && atoi(env) <= kBatch * 4) return (uint32_t)atoi(env);
-  const uint64_t t = total_tiles / ((uint64_t)n_cu * 64);
-  return (uint32_t)(t < 1 ? 1 : (t > kBatch ? kBatch : t));
+// Grid shape: as many blocks per job as the GPU holds at once, shared between the jobs of
+// the launch (one block holds 4 waves; a wave then walks its share of the job's tiles).
+uint32_t blocks_per_job(uint32_t max_tiles, uint32_t n_jobs, uint32_t n_cu) {
+  uint32_t per_cu = 6;
+  const char *env = getenv("DQ_BLOCKS_PER_CU");  // tuning / test knob
+  if (env && atoi(env) >= 1 && atoi(env) <= 64) per_cu = (uint32_t)atoi(env);
+  uint32_t blocks = (n_cu * per_cu + n_jobs - 1) / n_jobs;
+  const uint32_t needed = (max_tiles + kBlockWaves - 1) / kBlockWaves;
+  if (blocks > needed) blocks = needed;
+  return blocks < 1 ? 1 : blocks;
 }
 
 size_t lds_bytes(const Params &p) { return (size_t)p.blob_dwords * 4 + kBlockWaves * 64 * 16; }
@@ -475,9 +539,7 @@ template <Kind KIND, typename LT>
 hipError_t go_one(const Job &job, Params p, uint32_t n_cu, hipStream_t s) {
   const uint32_t tiles = job_tiles(job);
   if (tiles == 0) return hipSuccess;
-  p.tiles_per_wave = choose_tiles_per_wave(tiles, n_cu);
-  const uint32_t per_block = kBlockWaves * p.tiles_per_wave;
-  const uint32_t blocks = (tiles + per_block - 1) / per_block;
+  const uint32_t blocks = blocks_per_job(tiles, 1, n_cu);
   hipLaunchKernelGGL((k_one<KIND, LT>), dim3(blocks), dim3(kBlockThreads), lds_bytes(p), s, job, p);
   return hipGetLastError();
 }
@@ -485,9 +547,8 @@ template <Kind KIND, typename LT>
 hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, uint64_t total_tiles, Params p,
                     uint32_t n_cu, hipStream_t s) {
   if (n_jobs == 0 || max_tiles == 0) return hipSuccess;
-  p.tiles_per_wave = choose_tiles_per_wave(total_tiles, n_cu);
-  const uint32_t per_block = kBlockWaves * p.tiles_per_wave;
-  const uint32_t blocks = (max_tiles + per_block - 1) / per_block;
+  (void)total_tiles;
+  const uint32_t blocks = blocks_per_job(max_tiles, n_jobs, n_cu);
   hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), lds_bytes(p), s, jobs, p);
   return hipGetLastError();
 }

@@ -17,6 +17,20 @@ struct NoLocal {};
 __device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
 
+// explicit global (address space 1) accesses: the job's pointers arrive inside a struct and
+// would otherwise be treated as generic, i.e. FLAT instructions
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <typename T>
+__device__ __forceinline__ T gld(const void *p) {
+  return *(const __attribute__((address_space(1))) T *)p;
+}
+template <typename T>
+__device__ __forceinline__ void gst(void *p, T v) {
+  *(__attribute__((address_space(1))) T *)p = v;
+}
+
 template <int FMT>
 struct Fmt;
 template <>
@@ -51,14 +65,14 @@ __device__ __forceinline__ void load_local32(const void *base, size_t first, flo
     const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + first);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float4 t = p[i];
+      const f32x4 t = gld<f32x4>(p + i);
       v[4 * i] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
     }
   } else {
     const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + first);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint4 t = p[i];
+      const u32x4 t = gld<u32x4>(p + i);
       const uint32_t w[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -82,18 +96,17 @@ __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t
     uint32_t w[cw + 1];
     const uint8_t *src = job.in + (size_t)bi * (cw * 4);
     if constexpr (cw == 8) {
-      const uint4 a = *reinterpret_cast<const uint4 *>(src), b = *reinterpret_cast<const uint4 *>(src + 16);
+      const u32x4 a = gld<u32x4>(src), b = gld<u32x4>(src + 16);
       w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
     } else if constexpr (cw == 6) {
-      const uint2 a = *reinterpret_cast<const uint2 *>(src), b = *reinterpret_cast<const uint2 *>(src + 8),
-                  c = *reinterpret_cast<const uint2 *>(src + 16);
+      const u32x2 a = gld<u32x2>(src), b = gld<u32x2>(src + 8), c = gld<u32x2>(src + 16);
       w[0] = a.x; w[1] = a.y; w[2] = b.x; w[3] = b.y; w[4] = c.x; w[5] = c.y;
     } else {
-      const uint4 a = *reinterpret_cast<const uint4 *>(src);
+      const u32x4 a = gld<u32x4>(src);
       w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
     }
     w[cw] = 0;
-    const uint32_t e = job.in[scale_off + bi];
+    const uint32_t e = gld<uint8_t>(job.in + scale_off + bi);
     const float X = e ? u2f(e << 23) : u2f(0x00400000u);  // 2^(e-127); e = 0 is a binary32 subnormal
     const float unbias = u2f((uint32_t)(254 - F::bias) << 23);  // 2^(127-bias)
 #pragma unroll
@@ -112,7 +125,7 @@ __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t
   if constexpr (KIND == kDecompress) {
     float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(job.out) + (size_t)bi * 32);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+    for (int i = 0; i < 8; ++i) gst<f32x4>(o + i, f32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]});
   } else {
     float m = 0.0f;
 #pragma unroll
@@ -134,16 +147,16 @@ __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t
     }
     uint8_t *dst = static_cast<uint8_t *>(job.out) + (size_t)bi * (cw * 4);
     if constexpr (cw == 8) {
-      *reinterpret_cast<uint4 *>(dst) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-      *reinterpret_cast<uint4 *>(dst + 16) = make_uint4(ow[4], ow[5], ow[6], ow[7]);
+      gst<u32x4>(dst, u32x4{ow[0], ow[1], ow[2], ow[3]});
+      gst<u32x4>(dst + 16, u32x4{ow[4], ow[5], ow[6], ow[7]});
     } else if constexpr (cw == 6) {
-      *reinterpret_cast<uint2 *>(dst) = make_uint2(ow[0], ow[1]);
-      *reinterpret_cast<uint2 *>(dst + 8) = make_uint2(ow[2], ow[3]);
-      *reinterpret_cast<uint2 *>(dst + 16) = make_uint2(ow[4], ow[5]);
+      gst<u32x2>(dst, u32x2{ow[0], ow[1]});
+      gst<u32x2>(dst + 8, u32x2{ow[2], ow[3]});
+      gst<u32x2>(dst + 16, u32x2{ow[4], ow[5]});
     } else {
-      *reinterpret_cast<uint4 *>(dst) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+      gst<u32x4>(dst, u32x4{ow[0], ow[1], ow[2], ow[3]});
     }
-    static_cast<uint8_t *>(job.out)[scale_off + bi] = (uint8_t)e;
+    gst<uint8_t>(static_cast<uint8_t *>(job.out) + scale_off + bi, (uint8_t)e);
   }
 }
 

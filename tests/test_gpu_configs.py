@@ -1,0 +1,147 @@
+"""The five BASELINE configurations at FULL size, in the launch configuration bench.py times
+(the hop replay), against the CPU oracle.
+
+Configs 1-3: the oracle replays the whole schedule and every output entry is compared.
+Configs 4-5: the GPU runs everything; the oracle recomputes sampled buckets (config 4) or
+sampled runs of super-groups (config 5) one by one -- valid because a super-group's codes
+depend only on its own data, its width and its global index.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dq_oracle as O
+from paper_2602_08923_amd import binding as B
+from paper_2602_08923_amd import prep, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def test_config2_ring8_bf16_25mb_full(dev):
+    wl = workloads.CONFIGS[2]
+    n = wl.n_workers
+    grads = [workloads.draw(wl, w, 0, device="cpu") for w in range(n)]
+    re, counts, _ = prep.prepare_bucket(grads, wl.budget_bits, n)
+    n_sg = wl.entries // 256
+    assert sum(counts) == n_sg and counts[0] > 0 and counts[1] > 0   # ~4 bits: a mix of 2- and 4-bit SGs
+    seed = 2024
+    want = np.concatenate(O.ring_reduce_scatter(O.Oracle(n, seed=seed), [workloads.to_numpy(g) for g in re], counts))
+    ctx = B.Context(n, seed=seed)
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [g.to(dev) for g in re], n_sg, [counts])
+    assert rp.n_steps == 8 and [rp.step_info(i)[0] for i in range(8)] == [0, 1, 1, 1, 1, 1, 1, 2]
+    rp.run()
+    torch.cuda.synchronize()
+    got = host(rp.out)
+    assert np.array_equal(got, want)
+    true = sum(g.double() for g in re).numpy()
+    assert ((got - true) ** 2).sum() / (true ** 2).sum() < 0.5   # ~4 bits, x100 outliers, 7 re-quantizations
+
+
+@pytest.mark.parametrize("fmt", [B.DQ_MXFP8_E4M3, B.DQ_MXFP6_E3M2, B.DQ_MXFP4_E2M1])
+def test_config3_ring8_mx_full(dev, fmt):
+    wl = workloads.CONFIGS[3]
+    n = wl.n_workers
+    grads = [workloads.draw(wl, w, 0, device="cpu") for w in range(n)]
+    want = np.concatenate(O.mx_ring_reduce_scatter(fmt, [workloads.to_numpy(g) for g in grads]))
+    ctx = B.Context(n)
+    rp = B.Replay(ctx, B.DQ_RING, fmt, [g.to(dev) for g in grads], wl.entries // 256)
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+
+
+def test_config4_butterfly16_1p3b_sampled_buckets(dev):
+    """16-worker butterfly over 100 buckets of 13,107,200 bf16 entries (1.31 B parameters per
+    worker, 42 GB of gradients in HBM), b = 3; the oracle recomputes two whole buckets."""
+    wl = workloads.CONFIGS[4]
+    n, d, nb = wl.n_workers, wl.entries, wl.n_buckets
+    n_sg = d // 256
+    check = (7, 93)
+    worker = [torch.empty(d * nb, dtype=torch.bfloat16, device=dev) for _ in range(n)]
+    counts_all, kept = [], {}
+    for b in range(nb):
+        g = [workloads.draw(wl, w, b, device=dev) for w in range(n)]
+        re, counts, _ = prep.prepare_bucket(g, wl.budget_bits, n)
+        counts_all.append(counts)
+        for w in range(n):
+            worker[w][b * d:(b + 1) * d] = re[w]
+        if b in check:
+            kept[b] = [workloads.to_numpy(x) for x in re]
+        del g, re
+    assert len({tuple(c) for c in counts_all}) > 2      # buckets that straddle two tensors get other allocations
+    assert all(c[0] > 0 for c in counts_all)            # lowest budget: mostly 2-bit
+    seed = 77
+    ctx = B.Context(n, seed=seed)
+    rp = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_DYNAMIQ, worker, n_sg, counts_all, n_buckets=nb)
+    assert rp.n_steps == 5
+    rp.run()
+    torch.cuda.synchronize()
+    orc = O.Oracle(n, seed=seed)
+    for b in check:
+        want = np.concatenate(O.butterfly_reduce_scatter(orc, kept[b], counts_all[b], first_sg=b * n_sg))
+        got = host(rp.out[b * d:(b + 1) * d])
+        assert np.array_equal(got, want), f"bucket {b}"
+    # the unchecked buckets are estimates of their true sums too (at 3 bits per entry on i.i.d.
+    # values the ternary codes are coarse: ask for clear correlation, not for a small error)
+    for b in (0, 50, 99):
+        true = sum(worker[w][b * d:(b + 1) * d].double() for w in range(n))
+        est = rp.out[b * d:(b + 1) * d].double()
+        corr = float((est * true).sum() / torch.sqrt((est * est).sum() * (true * true).sum()))
+        assert corr > 0.5, (b, corr)
+
+
+def test_config5_chain64_125m_sampled_runs(dev):
+    """One chunk of a 64-worker ring: 64 slices of 125,000,192 bf16 entries (16 GB), all 63 hops
+    replayed with the packed partial sums kept in HBM; the oracle recomputes sampled runs."""
+    wl = workloads.CONFIGS[5]
+    n, d = wl.n_workers, wl.entries
+    n_sg = d // 256
+    F = None
+    raw = []
+    for w in range(n):
+        g = workloads.draw(wl, w, 0, device=dev)
+        f = g.to(torch.float64).reshape(-1, 256).pow(2).sum(dim=1)
+        F = f if F is None else F + f
+        raw.append(g)
+    widths = prep.allocate(F, wl.budget_bits)
+    perm, counts = prep.reorder_plan(widths, 1)
+    del F, widths
+    slices = []
+    for w in range(n):
+        slices.append(prep.apply_reorder(raw[w], perm))
+        raw[w] = None
+    assert counts[1] > 0 and counts[2] > 0              # 4.3125 code bits on average: 4- and 8-bit SGs
+    seed = 5
+    ctx = B.Context(n, seed=seed)
+    rp = B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, slices, n_sg, [counts])
+    assert rp.n_steps == 64
+    assert [rp.step_info(i)[0] for i in (0, 1, 62, 63)] == [0, 1, 1, 2]
+    rp.run()
+    torch.cuda.synchronize()
+    # sampled runs: the start, both width boundaries (runs that straddle them), the ragged end
+    edges = np.cumsum([0] + counts)
+    run = 96
+    starts = [0, int(edges[1]) - 40, int(edges[1]) + 1000, int(edges[2]) - 50, (n_sg // 2 // 4) * 4 + 1, n_sg - run]
+    orc = O.Oracle(n, seed=seed)
+    for s in starts:
+        s = max(0, min(s, n_sg - run))
+        cw = [int(max(0, min(s + run, edges[k + 1]) - max(s, edges[k]))) for k in range(3)]
+        ch = O.make_chunk(s, cw)
+        sl = [workloads.to_numpy(x[s * 256:(s + run) * 256]) for x in slices]
+        msg = orc.compress(ch, 0, sl[0])
+        for i in range(1, n - 1):
+            msg = orc.dar_hop(ch, i, msg, sl[i])
+        want = orc.decompress(ch, msg, sl[n - 1])
+        got = host(rp.out[s * 256:(s + run) * 256])
+        assert np.array_equal(got, want), f"run at super-group {s}"

@@ -322,9 +322,9 @@ def test_mx_ring_replay_small(dev):
 # ----------------------------------------------------------------------------- launch shape
 
 def test_result_does_not_depend_on_launch_shape(dev, monkeypatch):
-    """The same chunk through 1, 3 and 8 tiles per wave (and the batch launcher) gives the
-    same bytes: the random streams are keyed by global indices, not by the grid."""
-    n, n_sg = 8, [37, 150, 21]
+    """The same chunk under different grid sizes, and cut in two calls, gives the same bytes:
+    the random streams are keyed by global indices, not by the grid."""
+    n, n_sg = 8, [3700, 15000, 2100]
     rng = np.random.default_rng(99)
     entries = sum(n_sg) * 256
     a, b = make_local(rng, entries, "bf16"), make_local(rng, entries, "bf16")
@@ -333,10 +333,9 @@ def test_result_does_not_depend_on_launch_shape(dev, monkeypatch):
     want1 = orc.compress(och, 2, a)
     want2 = orc.dar_hop(och, 3, want1, b)
     want3 = orc.decompress(och, want2, a)
-    for tpw in ("1", "3", "8", "20"):
-        monkeypatch.setenv("DQ_TILES_PER_WAVE", tpw)
-        # the library reads the variable once per process, so drive the shapes through chunk
-        # sizes as well: the same data as one call and split in two calls at an SG boundary
+    monkeypatch.delenv("DQ_BLOCKS_PER_CU", raising=False)
+    for per_cu in ("1", "2", "7", "64"):   # from ~7 tiles per wave down to one
+        monkeypatch.setenv("DQ_BLOCKS_PER_CU", per_cu)
         ctx = B.Context(n, seed=5)
         g1 = ctx.dq_compress(to_dev(a, dev), gch, 2)
         g2 = ctx.dq_dar_hop(g1, to_dev(b, dev), gch, 3)
@@ -344,7 +343,8 @@ def test_result_does_not_depend_on_launch_shape(dev, monkeypatch):
         assert np.array_equal(host(ctx.dq_decompress(g2, gch, local=to_dev(a, dev))), want3)
     # split the 4-bit run in two chunks: codes of the second part must match the tail of the whole
     ctx = B.Context(n, seed=5)
-    n_a, n_b = [37, 70, 0], [0, 80, 21]
+    monkeypatch.delenv("DQ_BLOCKS_PER_CU", raising=False)
+    n_a, n_b = [3700, 7000, 0], [0, 8000, 2100]
     ea = sum(n_a) * 256
     ga = ctx.dq_compress(to_dev(a[:ea], dev), B.make_chunk(4000, n_a), 2)
     gb = ctx.dq_compress(to_dev(a[ea:], dev), B.make_chunk(4000 + sum(n_a), n_b), 2)
@@ -352,6 +352,6 @@ def test_result_does_not_depend_on_launch_shape(dev, monkeypatch):
     wb = orc.compress(O.make_chunk(4000 + sum(n_a), n_b), 2, a[ea:])
     assert np.array_equal(host(ga), wa) and np.array_equal(host(gb), wb)
     whole = want1
-    assert np.array_equal(wa[:37 * 64], whole[:37 * 64])                       # 2-bit codes
-    assert np.array_equal(wa[37 * 64:37 * 64 + 70 * 128], whole[37 * 64:37 * 64 + 70 * 128])  # first 4-bit codes
-    assert np.array_equal(wb[:80 * 128], whole[37 * 64 + 70 * 128:37 * 64 + 150 * 128])       # remaining 4-bit codes
+    assert np.array_equal(wa[:3700 * 64], whole[:3700 * 64])                       # 2-bit codes
+    assert np.array_equal(wa[3700 * 64:3700 * 64 + 7000 * 128], whole[3700 * 64:3700 * 64 + 7000 * 128])  # first 4-bit codes
+    assert np.array_equal(wb[:8000 * 128], whole[3700 * 64 + 7000 * 128:3700 * 64 + 15000 * 128])         # the other 4-bit codes
