@@ -128,6 +128,23 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
   std::vector<uint32_t> blob;
   dq::Params P;
   memset(&P, 0, sizeof(P));
+  // Blob layout: [common: reciprocals][2-bit: decode][4-bit: decode, sign spread, {T,D}, search]
+  // [8-bit: decode, {T,D}, search]; the fixed-size tables land on the constant offsets that
+  // dq_device.h declares.
+  {
+    std::vector<uint32_t> rec(256);
+    for (int m = 0; m < 128; ++m) {
+      const float sig = 1.0f + (float)m / 128.0f;
+      const float a = sig / 255.0f, b = 255.0f / sig;
+      rec[2 * m] = fbits(a);
+      rec[2 * m + 1] = fbits(b);
+    }
+    uint32_t off;
+    append_aligned(blob, rec, &off);
+    if (off != dq::kOffRec) return DQ_EINVAL;
+    P.reg_lo[3] = off;
+    P.reg_hi[3] = (uint32_t)blob.size();
+  }
   for (int wi = 0; wi < 3; ++wi) {
     const int R = Rs[wi], b = 2 << wi;  // widths 2, 4, 8
     std::vector<float> T, D;
@@ -145,19 +162,6 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
         dec[(size_t)byte * per_byte + j] = fbits((code >> (b - 1)) ? -t : t);
       }
     append_aligned(blob, dec, &P.off_dec[wi]);
-    if (wi > 0) {  // levels {0,1} need no search
-      int m = 0;
-      std::vector<uint32_t> lut;
-      if (!build_search(T, R, &m, lut)) return DQ_EUNSUPPORTED;
-      append_aligned(blob, lut, &P.off_lut[wi]);
-      std::vector<uint32_t> tab(2 * (size_t)(R + 1));
-      for (int r = 0; r <= R; ++r) {
-        tab[2 * r] = fbits(T[r]);
-        tab[2 * r + 1] = fbits(D[r]);
-      }
-      append_aligned(blob, tab, &P.off_tab[wi]);
-      P.magic[wi] = (float)ldexp(1.0, 23 - m);
-    }
     if (wi == 1) {  // sign bit of entry k of a word -> bit 4k+3
       std::vector<uint32_t> sp(256);
       for (int byte = 0; byte < 256; ++byte) {
@@ -166,25 +170,29 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
           if ((byte >> k) & 1) w |= 1u << (4 * k + 3);
         sp[byte] = w;
       }
-      append_aligned(blob, sp, &P.off_spread4);
+      uint32_t off;
+      append_aligned(blob, sp, &off);
+      if (off != dq::kOffSpread4) return DQ_EINVAL;
+    }
+    if (wi > 0) {  // levels {0,1} need no search
+      std::vector<uint32_t> tab(2 * (size_t)(R + 1));
+      for (int r = 0; r <= R; ++r) {
+        tab[2 * r] = fbits(T[r]);
+        tab[2 * r + 1] = fbits(D[r]);
+      }
+      append_aligned(blob, tab, &P.off_tab[wi]);
+      int m = 0;
+      std::vector<uint32_t> lut;
+      if (!build_search(T, R, &m, lut)) return DQ_EUNSUPPORTED;
+      append_aligned(blob, lut, &P.off_lut[wi]);
+      P.magic[wi] = (float)ldexp(1.0, 23 - m);
     }
     while (blob.size() % 4) blob.push_back(0);
     P.reg_hi[wi] = (uint32_t)blob.size();
   }
-  {  // common region: quotients of the 128 bf16 significands by 255 and of 255 by them
-    while (blob.size() % 4) blob.push_back(0);
-    P.reg_lo[3] = (uint32_t)blob.size();
-    std::vector<uint32_t> rec(256);
-    for (int m = 0; m < 128; ++m) {
-      const float sig = 1.0f + (float)m / 128.0f;
-      const float a = sig / 255.0f, b = 255.0f / sig;
-      rec[2 * m] = fbits(a);
-      rec[2 * m + 1] = fbits(b);
-    }
-    append_aligned(blob, rec, &P.off_rec);
-    while (blob.size() % 4) blob.push_back(0);
-    P.reg_hi[3] = (uint32_t)blob.size();
-  }
+  if (P.off_dec[0] != dq::kOffDec2 || P.off_dec[1] != dq::kOffDec4 || P.off_tab[1] != dq::kOffTab4 ||
+      P.off_lut[1] != dq::kOffLut4)
+    return DQ_EINVAL;
   if (blob.size() * 4 > 60 * 1024) return DQ_EUNSUPPORTED;
 
   dq_ctx *ctx = new (std::nothrow) dq_ctx;

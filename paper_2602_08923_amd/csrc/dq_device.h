@@ -25,6 +25,15 @@ struct Job {
   uint32_t rank;       // worker doing the compression (feeds the random streams)
 };
 
+// Fixed part of the table blob (dword offsets).  The tables whose size does not depend on the
+// level sets sit at constant places, so the kernels address them with immediate offsets.
+constexpr uint32_t kOffRec = 0;        // 128 pairs {bits((1+m/128)/255), bits(255/(1+m/128))}
+constexpr uint32_t kOffDec2 = 256;     // 2-bit decode: 256 bytes x 4 levels
+constexpr uint32_t kOffDec4 = 1280;    // 4-bit decode: 256 bytes x 2 levels
+constexpr uint32_t kOffSpread4 = 1792; // 8 sign bits -> bits 4k+3
+constexpr uint32_t kOffTab4 = 2048;    // 8 pairs {T, D}
+constexpr uint32_t kOffLut4 = 2064;    // search table of the 4-bit set (size depends on the set)
+
 // Everything the kernels need besides the job: PRNG key, worker count, table blob.
 // The blob holds one region per width (2, 4, 8 bits), each region = [decode table | search
 // table | level/gap table]; a block copies only the regions of the widths it will meet.
@@ -32,8 +41,6 @@ struct Params {
   const uint32_t *blob;  // device copy of the table blob
   uint32_t blob_dwords;  // multiple of 4
   uint32_t reg_lo[4], reg_hi[4];  // dword range of each width's region and of the common one (multiples of 4)
-  uint32_t off_rec;      // common: 128 pairs {bits((1+m/128)/255), bits(255/(1+m/128))}
-  uint32_t off_spread4;  // 4-bit region: byte of 8 sign bits -> those bits at positions 4k+3
   uint32_t off_dec[3];   // decode table indexed by one code BYTE: 8/b signed levels (+-T[r]) per entry
   uint32_t off_lut[3];   // search table: (2^m + 1) pairs {next level, candidate index}
   uint32_t off_tab[3];   // level/gap pairs {T[r], D[r]}, r = 0..R (D[R] = 0)

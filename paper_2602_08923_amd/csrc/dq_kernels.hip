@@ -42,12 +42,15 @@ __device__ __forceinline__ uint32_t lds_ld1(uint32_t a) { return *reinterpret_ca
 __device__ __forceinline__ u32x2 lds_ld2(uint32_t a) { return *reinterpret_cast<lds_u2 *>(a); }
 __device__ __forceinline__ u32x4 lds_ld4(uint32_t a) { return *reinterpret_cast<lds_u4 *>(a); }
 __device__ __forceinline__ void lds_st4(uint32_t a, u32x4 v) { *reinterpret_cast<lds_w4 *>(a) = v; }
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) f32x4 lds_f4;
+__device__ __forceinline__ void lds_stf4(uint32_t a, f32x4 v) { *reinterpret_cast<lds_f4 *>(a) = v; }
+__device__ __forceinline__ f32x4 lds_ldf4(uint32_t a) { return *reinterpret_cast<const lds_f4 *>(a); }
 
 // Global-memory accesses through explicit address-space-1 pointers.  The job's pointers reach
 // the kernel inside a struct, where the compiler would otherwise treat them as generic and
 // emit FLAT instructions; those also count on the LDS counter, so every wait for a table
 // lookup would wait for the outstanding global loads and stores as well.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 template <typename T>
 __device__ __forceinline__ T gld(const void *p) {
   return *(const __attribute__((address_space(1))) T *)p;
@@ -86,16 +89,18 @@ __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
 }
 
 // ---- max over the 16 lanes of a DPP row, result in every lane of the row
+// (the operands are magnitudes, so the order of their bit patterns is the order of the values)
 template <int CTRL>
-__device__ __forceinline__ float dpp_f(float x) {
-  return u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), CTRL, 0xF, 0xF, false));
+__device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
 }
-__device__ __forceinline__ float row_max16(float x) {
-  x = fmaxf(x, dpp_f<0x128>(x));  // row_ror:8
-  x = fmaxf(x, dpp_f<0x124>(x));  // row_ror:4
-  x = fmaxf(x, dpp_f<0x122>(x));  // row_ror:2
-  x = fmaxf(x, dpp_f<0x121>(x));  // row_ror:1
-  return x;
+__device__ __forceinline__ float row_max16(float m) {
+  uint32_t x = f2u(m);
+  x = max(x, dpp_u<0x128>(x));  // row_ror:8
+  x = max(x, dpp_u<0x124>(x));  // row_ror:4
+  x = max(x, dpp_u<0x122>(x));  // row_ror:2
+  x = max(x, dpp_u<0x121>(x));  // row_ror:1
+  return u2f(x);
 }
 
 // bit i of a 16-bit value -> bit 2i
@@ -110,11 +115,30 @@ __device__ __forceinline__ uint32_t spread16(uint32_t x) {
 template <int B>
 struct Width;
 template <>
-struct Width<2> { static constexpr int wi = 0, words = 1; };
+struct Width<2> { static constexpr int words = 1; };
 template <>
-struct Width<4> { static constexpr int wi = 1, words = 2; };
+struct Width<4> { static constexpr int words = 2; };
 template <>
-struct Width<8> { static constexpr int wi = 2, words = 4; };
+struct Width<8> { static constexpr int words = 4; };
+
+// LDS byte addresses of the tables: constants for the fixed part of the blob (2- and 4-bit
+// sets), kernel parameters for the 8-bit set.
+template <int B>
+__device__ __forceinline__ uint32_t dec_addr(const Params &P, uint32_t lds0) {
+  if constexpr (B == 2) return lds0 + kOffDec2 * 4;
+  else if constexpr (B == 4) return lds0 + kOffDec4 * 4;
+  else return lds0 + P.off_dec[2] * 4;
+}
+template <int B>
+__device__ __forceinline__ uint32_t tab_addr(const Params &P, uint32_t lds0) {
+  if constexpr (B == 4) return lds0 + kOffTab4 * 4;
+  else return lds0 + P.off_tab[2] * 4;
+}
+template <int B>
+__device__ __forceinline__ uint32_t lut_addr(const Params &P, uint32_t lds0) {
+  if constexpr (B == 4) return lds0 + kOffLut4 * 4;
+  else return lds0 + P.off_lut[2] * 4;
+}
 
 // Where a tile (index t in the job's concatenated 2-, 4-, 8-bit tile sequence) sits.
 struct TilePos {
@@ -222,7 +246,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const bool active = row <= tb.last_row;
   const uint32_t rowc = min(row, tb.last_row);
   const uint32_t lg = rowc * 16 + g;
-  const uint32_t rec0 = lds0 + P.off_rec * 4;
+  const uint32_t rec0 = lds0 + kOffRec * 4;
 
   float v[16];
   if constexpr (sizeof(LT) == 4) {
@@ -246,7 +270,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   if constexpr (KIND == kDar) {
     // decode: sf_G = r_G * (sf_SG / 255); estimate = +-T[r] * sf_G, accumulated by one fma
     const float sfg = (float)f.rg_in * sf_over_255(f.sf_in, rec0);
-    const uint32_t dec0 = lds0 + P.off_dec[W::wi] * 4;
+    const uint32_t dec0 = dec_addr<B>(P, lds0);
 #pragma unroll
     for (int j = 0; j < 2 * B; ++j) {  // one table entry per code byte
       const uint32_t byte = (f.cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
@@ -315,10 +339,10 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
     }
     ow[0] = (rg ? spread16(rbits) : 0u) | (spread16(sbits & 0xFFFFu) << 1);
   } else {
-    const float magic = P.magic[W::wi];
+    const float magic = P.magic[B == 4 ? 1 : 2];
     // byte address of lut[q] is lut0 + 8*q with q = bits(x + magic) - bits(magic)
-    const uint32_t lut_k = lds0 + P.off_lut[W::wi] * 4 - (f2u(magic) << 3);
-    const uint32_t tab0 = lds0 + P.off_tab[W::wi] * 4;
+    const uint32_t lut_k = lut_addr<B>(P, lds0) - (f2u(magic) << 3);
+    const uint32_t tab0 = tab_addr<B>(P, lds0);
     constexpr int per_word = 32 / B;
 #pragma unroll
     for (int i = 0; i < W::words; ++i) ow[i] = 0;
@@ -336,7 +360,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
     }
     if constexpr (B == 4) {
       // sign of entry k -> bit 4k+3: a 256-entry table spreads 8 sign bits over a word
-      const uint32_t sp0 = lds0 + P.off_spread4 * 4;
+      const uint32_t sp0 = lds0 + kOffSpread4 * 4;
       const uint32_t s0 = lds_ld1(sp0 + (sbits & 0xFFu) * 4), s1 = lds_ld1(sp0 + ((sbits >> 8) & 0xFFu) * 4);
       ow[0] = (rg ? ow[0] : 0u) | s0;
       ow[1] = (rg ? ow[1] : 0u) | s1;
@@ -367,61 +391,98 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   }
 }
 
-// One wave tile of decompress(+accumulate).  Here a lane owns 4 consecutive entries of each
-// of the tile's super-groups (one SG per step), so that every load and the fp32 store of a
-// step cover contiguous memory across the wave.
+// One wave tile of decompress(+accumulate).  Lanes fetch and decode like the DAR tile (a lane
+// owns a group of 16 entries, few wide loads), then the 4 KB of fp32 results are transposed
+// through a per-wave LDS area so that every store instruction writes 1 KB of contiguous memory.
+//   xpose : LDS byte address of this wave's 4 KB transpose area
 template <int B, typename LT>
-__device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_t lds0, const TilePos pos) {
+__device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_t lds0, uint32_t xpose,
+                                        const TilePos pos) {
   using W = Width<B>;
   constexpr bool kHasLocal = !__is_same(LT, NoLocal);
   const TileBase<B> tb(job, pos);
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t rec0 = lds0 + P.off_rec * 4;
-  const uint32_t dec0 = lds0 + P.off_dec[W::wi] * 4;
-  float *outp = static_cast<float *>(job.out) + tb.first_entry;
+  const uint32_t rowc = min(lane >> 4, tb.last_row);
+  const uint32_t lg = rowc * 16 + (lane & 15u);
+  const uint32_t rec0 = lds0 + kOffRec * 4;
+  const uint32_t dec0 = dec_addr<B>(P, lds0);
+
+  float v[16];
+  if constexpr (kHasLocal) {
+    if constexpr (sizeof(LT) == 4) {
+      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
 #pragma unroll
-  for (uint32_t i = 0; i < (uint32_t)kWaveSGs; ++i) {
-    if (i > tb.last_row) break;
-    // 4 codes = B/2 bytes per lane
-    uint32_t cw;
-    const uint8_t *cp = job.in + tb.code_off + i * (32 * B) + lane * (B / 2);
-    if constexpr (B == 2) cw = gld<uint8_t>(cp);
-    else if constexpr (B == 4) cw = gld<uint16_t>(cp);
-    else cw = gld<uint32_t>(cp);
-    const uint32_t rg_in = gld<uint8_t>(job.in + tb.gs_off + i * 16 + (lane >> 2));
-    const uint32_t sf_in = gld<uint16_t>(job.in + tb.sf_off + i * 2);
-    float loc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if constexpr (kHasLocal) {
-      if constexpr (sizeof(LT) == 4) {
-        const f32x4 x = gld<f32x4>(reinterpret_cast<const float4 *>(static_cast<const float *>(job.local) + tb.first_entry + i * kSG) + lane);
-        loc[0] = x.x; loc[1] = x.y; loc[2] = x.z; loc[3] = x.w;
-      } else {
-        const u32x2 x = gld<u32x2>(reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry + i * kSG) + lane);
-        loc[0] = u2f(x.x << 16); loc[1] = u2f(x.x & 0xFFFF0000u);
-        loc[2] = u2f(x.y << 16); loc[3] = u2f(x.y & 0xFFFF0000u);
+      for (int i = 0; i < 4; ++i) {
+        const uint4 x = gld16(p + i);
+        v[4 * i] = u2f(x.x); v[4 * i + 1] = u2f(x.y); v[4 * i + 2] = u2f(x.z); v[4 * i + 3] = u2f(x.w);
+      }
+    } else {
+      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const uint4 x = gld16(p + i);
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[8 * i + 2 * j] = u2f(w[j] << 16);
+          v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
+        }
       }
     }
-    const float sfg = (float)rg_in * sf_over_255(sf_in, rec0);
+  }
+  uint32_t cw[W::words];
+  const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
+  if constexpr (B == 2) {
+    cw[0] = gld<uint32_t>(cp);
+  } else if constexpr (B == 4) {
+    const u32x2 t = gld<u32x2>(cp);
+    cw[0] = t.x; cw[1] = t.y;
+  } else {
+    const u32x4 t = gld<u32x4>(cp);
+    cw[0] = t.x; cw[1] = t.y; cw[2] = t.z; cw[3] = t.w;
+  }
+  const uint32_t rg_in = gld<uint8_t>(job.in + tb.gs_off + lg);
+  const uint32_t sf_in = gld<uint16_t>(job.in + tb.sf_off + rowc * 2);
+  const float sfg = (float)rg_in * sf_over_255(sf_in, rec0);
+#pragma unroll
+  for (int j = 0; j < 2 * B; ++j) {  // one table entry per code byte
+    const uint32_t byte = (cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
     float t[4];
+    constexpr int per = 8 / B;
     if constexpr (B == 2) {
-      const u32x4 e = lds_ld4(dec0 + (cw & 0xFFu) * 16);
+      const u32x4 e = lds_ld4(dec0 + byte * 16);
       t[0] = u2f(e.x); t[1] = u2f(e.y); t[2] = u2f(e.z); t[3] = u2f(e.w);
     } else if constexpr (B == 4) {
-      const u32x2 e0 = lds_ld2(dec0 + (cw & 0xFFu) * 8), e1 = lds_ld2(dec0 + ((cw >> 8) & 0xFFu) * 8);
-      t[0] = u2f(e0.x); t[1] = u2f(e0.y); t[2] = u2f(e1.x); t[3] = u2f(e1.y);
+      const u32x2 e = lds_ld2(dec0 + byte * 8);
+      t[0] = u2f(e.x); t[1] = u2f(e.y);
     } else {
+      t[0] = u2f(lds_ld1(dec0 + byte * 4));
+    }
 #pragma unroll
-      for (int k = 0; k < 4; ++k) t[k] = u2f(lds_ld1(dec0 + ((cw >> (8 * k)) & 0xFFu) * 4));
+    for (int k = 0; k < per; ++k) {
+      if constexpr (kHasLocal) v[per * j + k] = __builtin_fmaf(t[k], sfg, v[per * j + k]);
+      else v[per * j + k] = t[k] * sfg;
     }
-    f32x4 o;
-    if constexpr (kHasLocal) {
-      o = f32x4{__builtin_fmaf(t[0], sfg, loc[0]), __builtin_fmaf(t[1], sfg, loc[1]),
-                __builtin_fmaf(t[2], sfg, loc[2]), __builtin_fmaf(t[3], sfg, loc[3])};
-    } else {
-      o = f32x4{t[0] * sfg, t[1] * sfg, t[2] * sfg, t[3] * sfg};
-    }
-    gst<f32x4>(reinterpret_cast<float4 *>(outp + i * kSG) + lane, o);
   }
+  // transpose: lane l parks its 4 float4 at slots 4l..4l+3 (chunk index xor-ed with bits 2-3 of
+  // l so that the 16 lanes of a pass hit different banks); store round r then reads slot
+  // r*64 + lane, which is float4 number r*64 + lane of the tile
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (uint32_t i = 0; i < 4; ++i)
+    lds_stf4(xpose + lane * 64 + ((i ^ ((lane >> 2) & 3u)) * 16), f32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]});
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  float *outp = static_cast<float *>(job.out) + tb.first_entry;
+#pragma unroll
+  for (uint32_t r = 0; r < (uint32_t)kWaveSGs; ++r) {
+    if (r > tb.last_row) break;
+    const uint32_t slot = r * 64 + lane, w = slot >> 2, c = slot & 3u;
+    const f32x4 o = lds_ldf4(xpose + w * 64 + ((c ^ ((w >> 2) & 3u)) * 16));
+    gst<f32x4>(reinterpret_cast<float4 *>(outp) + slot, o);
+  }
+  __builtin_amdgcn_wave_barrier();
 }
 
 // `len` consecutive tiles of width B starting at `pos` (their parked draws 128 bytes apart).
@@ -468,11 +529,13 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   const uint32_t w_lo = (uint32_t)(wv * total / n_waves);
   const uint32_t w_hi = (uint32_t)((wv + 1) * total / n_waves);
   if constexpr (KIND == kDecompress) {
+    // per-wave transpose area: 64 lanes x 64 bytes
+    const uint32_t xpose = lds0 + P.blob_dwords * 4 + wave * (64 * 64);
     for (uint32_t t = w_lo; t < w_hi; ++t) {
       const TilePos p = locate(job, t);
-      if (p.wi == 0) tile_da<2, LT>(job, P, lds0, p);
-      else if (p.wi == 1) tile_da<4, LT>(job, P, lds0, p);
-      else tile_da<8, LT>(job, P, lds0, p);
+      if (p.wi == 0) tile_da<2, LT>(job, P, lds0, xpose, p);
+      else if (p.wi == 1) tile_da<4, LT>(job, P, lds0, xpose, p);
+      else tile_da<8, LT>(job, P, lds0, xpose, p);
     }
   } else {
     // per-wave parking area for the per-SG draws of up to kBatch tiles: 64 x 16 bytes
@@ -533,14 +596,17 @@ uint32_t blocks_per_job(uint32_t max_tiles, uint32_t n_jobs, uint32_t n_cu) {
   return blocks < 1 ? 1 : blocks;
 }
 
-size_t lds_bytes(const Params &p) { return (size_t)p.blob_dwords * 4 + kBlockWaves * 64 * 16; }
+// blob + per-wave area: 1 KB of parked draws (compress, DAR) or 4 KB for the transpose (decompress)
+size_t lds_bytes(const Params &p, Kind kind) {
+  return (size_t)p.blob_dwords * 4 + kBlockWaves * 64 * (kind == kDecompress ? 64 : 16);
+}
 
 template <Kind KIND, typename LT>
 hipError_t go_one(const Job &job, Params p, uint32_t n_cu, hipStream_t s) {
   const uint32_t tiles = job_tiles(job);
   if (tiles == 0) return hipSuccess;
   const uint32_t blocks = blocks_per_job(tiles, 1, n_cu);
-  hipLaunchKernelGGL((k_one<KIND, LT>), dim3(blocks), dim3(kBlockThreads), lds_bytes(p), s, job, p);
+  hipLaunchKernelGGL((k_one<KIND, LT>), dim3(blocks), dim3(kBlockThreads), lds_bytes(p, KIND), s, job, p);
   return hipGetLastError();
 }
 template <Kind KIND, typename LT>
@@ -549,7 +615,7 @@ hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, uint64
   if (n_jobs == 0 || max_tiles == 0) return hipSuccess;
   (void)total_tiles;
   const uint32_t blocks = blocks_per_job(max_tiles, n_jobs, n_cu);
-  hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), lds_bytes(p), s, jobs, p);
+  hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), lds_bytes(p, KIND), s, jobs, p);
   return hipGetLastError();
 }
 
