@@ -22,6 +22,13 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per DAR launch from two `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then
+# WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads for a plain copy of
+# 2^30 bytes on the same box: FETCH_SIZE counts half the bytes read (x2.0), WRITE_SIZE all of
+# them (x1.0).  Key: (workload, codec).  The summary with the commands sits in profiles/.
+MEASURED_TRAFFIC_BYTES = {
+    (2, 0): int((16179.8 * 2.0 + 6249.8 * 1.0) * 1024),
+}
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E published peak
 
 
@@ -140,7 +147,8 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "dq_dar_hop" if codec == 0 else "dq_mx_dar_hop",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, codec)),
         "algorithmic_bytes_per_entry": bpe, "entries_per_launch": dar_entries,
         "avg_launch_us": round(dar_ms * 1e3, 2),
         "gradient_GBps_per_dar_hop": round(dar_entries * dtype_bytes / (dar_ms * 1e-3) / 1e9, 1) if dar_steps else None,
