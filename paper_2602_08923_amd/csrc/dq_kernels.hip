@@ -501,6 +501,37 @@ __device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint3
 // The job's tiles are split evenly over all waves of the grid row (4 * gridDim.x waves):
 // wave w takes [w*T/W, (w+1)*T/W).  The launcher sizes the grid to what the GPU holds at
 // once, so a wave lives for the whole launch and the table copy is paid once.
+// Per-SG draws of `nb` <= 8 consecutive tiles starting at tile `t_first`, made by one wave-wide
+// Philox call and parked at `area` (128 bytes per tile: row r at [32r] the shared permutation
+// stream, at [32r+16] the worker's group-scale stream).  Lane l draws for tile l/8, row (l%8)/2.
+__device__ __forceinline__ void park_draws(const Job &job, const Params &P, uint32_t t_first, uint32_t nb,
+                                           uint32_t area) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t j = min(lane >> 3, nb - 1);
+  const TilePos p = locate(job, t_first + j);
+  const uint32_t sgw = min(p.tile_first + ((lane >> 1) & 3u), p.n_seg - 1);
+  const uint64_t G = job.first_sg + p.seg_first + sgw;
+  const uint32_t c3 = (lane & 1u) ? ((1u << 16) | (job.rank & 0xFFFFu)) : ((2u << 16) | 0xFFFFu);
+  const U4 d = philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), P.round, c3, P.key0, P.key1);
+  lds_st4(area + lane * 16, u32x4{d.x, d.y, d.z, d.w});
+}
+
+// Tiles [t_first, t_first + nb) of the job, whose draws are parked from `area` on.
+template <Kind KIND, typename LT>
+__device__ __forceinline__ void run_range(const Job &job, const Params &P, uint32_t lds0, uint32_t area,
+                                          uint32_t t_first, uint32_t nb) {
+  for (uint32_t j = 0; j < nb;) {
+    const TilePos p = locate(job, t_first + j);
+    const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;  // tiles to the segment's end
+    const uint32_t len = min(nb - j, left);
+    const uint32_t stage = area + j * 128;
+    if (p.wi == 0) run_tiles<2, KIND, LT>(job, P, lds0, stage, p, len);
+    else if (p.wi == 1) run_tiles<4, KIND, LT>(job, P, lds0, stage, p, len);
+    else run_tiles<8, KIND, LT>(job, P, lds0, stage, p, len);
+    j += len;
+  }
+}
+
 template <Kind KIND, typename LT>
 __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   extern __shared__ uint4 lds_raw[];
@@ -509,61 +540,68 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   const uint32_t t0 = (n0 + kWaveSGs - 1) / kWaveSGs, t1 = (n1 + kWaveSGs - 1) / kWaveSGs,
                  t2 = (n2 + kWaveSGs - 1) / kWaveSGs;
   const uint32_t total = t0 + t1 + t2;
-  const uint64_t n_waves = (uint64_t)gridDim.x * kBlockWaves;
-  const uint32_t b_lo = (uint32_t)(((uint64_t)blockIdx.x * kBlockWaves) * total / n_waves);
-  const uint32_t b_hi = (uint32_t)(((uint64_t)(blockIdx.x + 1) * kBlockWaves) * total / n_waves);
+  // even split of the tiles over the grid's waves in 32-bit arithmetic: wave v takes q tiles
+  // from v*q + min(v, r), one more if v < r (q, r = quotient and remainder of tiles by waves)
+  const uint32_t n_waves = gridDim.x * kBlockWaves;
+  const uint32_t q = total / n_waves, r = total - q * n_waves;
+  const uint32_t bw = blockIdx.x * kBlockWaves;
+  const uint32_t b_lo = bw * q + min(bw, r);
+  const uint32_t b_hi = (bw + kBlockWaves) * q + min(bw + kBlockWaves, r);
   if (b_lo >= b_hi) return;
-  // copy the common tables and the table regions of the widths this block meets
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t *)lds;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t wv = bw + wave;
+  const uint32_t w_lo = wv * q + min(wv, r);
+  const uint32_t w_hi = w_lo + q + (wv < r ? 1u : 0u);
+  // parking area for per-SG draws: 1 KB (8 tiles) per wave, the four areas contiguous
+  const uint32_t park0 = lds0 + P.blob_dwords * 4;
+  // a block with at most 32 tiles makes all its draws up front, 8 tiles per wave-wide call,
+  // instead of one call per wave (waves of a small job hold only a tile or two each)
+  const bool block_draws = KIND != kDecompress && (b_hi - b_lo) <= 8u * kBlockWaves;
+
+  // copy the common tables and the table regions of the widths this block meets; the first
+  // 16 bytes per thread of every region are requested together (one round trip, not four)
   const bool need[4] = {b_lo < t0, b_lo < t0 + t1 && b_hi > t0, b_hi > t0 + t1, true};
+  uint4 first[4];
+  bool has[4];
+#pragma unroll
+  for (int wi = 0; wi < 4; ++wi) {
+    const uint32_t i = P.reg_lo[wi] + threadIdx.x * 4;
+    has[wi] = need[wi] && i < P.reg_hi[wi];
+    if (has[wi]) first[wi] = gld16(&P.blob[i]);
+  }
+  if constexpr (KIND != kDecompress) {
+    if (block_draws && 8u * wave < b_hi - b_lo)
+      park_draws(job, P, b_lo + 8u * wave, min(8u, b_hi - b_lo - 8u * wave), park0 + wave * 1024);
+  }
+#pragma unroll
+  for (int wi = 0; wi < 4; ++wi)
+    if (has[wi]) *reinterpret_cast<uint4 *>(&lds[P.reg_lo[wi] + threadIdx.x * 4]) = first[wi];
 #pragma unroll
   for (int wi = 0; wi < 4; ++wi)
     if (need[wi])
-      for (uint32_t i = P.reg_lo[wi] + threadIdx.x * 4; i < P.reg_hi[wi]; i += kBlockThreads * 4)
+      for (uint32_t i = P.reg_lo[wi] + (kBlockThreads + threadIdx.x) * 4; i < P.reg_hi[wi]; i += kBlockThreads * 4)
         *reinterpret_cast<uint4 *>(&lds[i]) = gld16(&P.blob[i]);
   __syncthreads();
 
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t *)lds;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t lane = threadIdx.x & 63u;
-  const uint64_t wv = (uint64_t)blockIdx.x * kBlockWaves + wave;
-  const uint32_t w_lo = (uint32_t)(wv * total / n_waves);
-  const uint32_t w_hi = (uint32_t)((wv + 1) * total / n_waves);
   if constexpr (KIND == kDecompress) {
     // per-wave transpose area: 64 lanes x 64 bytes
-    const uint32_t xpose = lds0 + P.blob_dwords * 4 + wave * (64 * 64);
+    const uint32_t xpose = park0 + wave * (64 * 64);
     for (uint32_t t = w_lo; t < w_hi; ++t) {
       const TilePos p = locate(job, t);
       if (p.wi == 0) tile_da<2, LT>(job, P, lds0, xpose, p);
       else if (p.wi == 1) tile_da<4, LT>(job, P, lds0, xpose, p);
       else tile_da<8, LT>(job, P, lds0, xpose, p);
     }
+  } else if (block_draws) {
+    run_range<KIND, LT>(job, P, lds0, park0 + (w_lo - b_lo) * 128, w_lo, w_hi - w_lo);
   } else {
-    // per-wave parking area for the per-SG draws of up to kBatch tiles: 64 x 16 bytes
-    const uint32_t stage0 = lds0 + P.blob_dwords * 4 + wave * (64 * 16);
+    const uint32_t area = park0 + wave * 1024;
     for (uint32_t tb = w_lo; tb < w_hi; tb += kBatch) {
       const uint32_t nb = min((uint32_t)kBatch, w_hi - tb);
-      {
-        // lane l draws for tile tb + l/8, row (l%8)/2: even l the shared permutation stream,
-        // odd l the worker's group-scale stream
-        const uint32_t j = min(lane >> 3, nb - 1);
-        const TilePos p = locate(job, tb + j);
-        const uint32_t sgw = min(p.tile_first + ((lane >> 1) & 3u), p.n_seg - 1);
-        const uint64_t G = job.first_sg + p.seg_first + sgw;
-        const uint32_t c3 = (lane & 1u) ? ((1u << 16) | (job.rank & 0xFFFFu)) : ((2u << 16) | 0xFFFFu);
-        const U4 d = philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), P.round, c3, P.key0, P.key1);
-        lds_st4(stage0 + lane * 16, u32x4{d.x, d.y, d.z, d.w});
-        __builtin_amdgcn_wave_barrier();
-      }
-      for (uint32_t j = 0; j < nb;) {
-        const TilePos p = locate(job, tb + j);
-        const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;  // tiles to the segment's end
-        const uint32_t len = min(nb - j, left);
-        const uint32_t stage = stage0 + j * 128;
-        if (p.wi == 0) run_tiles<2, KIND, LT>(job, P, lds0, stage, p, len);
-        else if (p.wi == 1) run_tiles<4, KIND, LT>(job, P, lds0, stage, p, len);
-        else run_tiles<8, KIND, LT>(job, P, lds0, stage, p, len);
-        j += len;
-      }
+      park_draws(job, P, tb, nb, area);
+      __builtin_amdgcn_wave_barrier();
+      run_range<KIND, LT>(job, P, lds0, area, tb, nb);
       __builtin_amdgcn_wave_barrier();
     }
   }
