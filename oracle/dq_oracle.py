@@ -1,4 +1,4 @@
-"""ctypes front end of the CPU oracle (dq_oracle.c, mx_oracle.c).
+"""ctypes front end of the CPU oracle (dq_oracle.c, mx_oracle.c; pp_oracle.c is wrapped by pp_oracle.py).
 
 TEST INFRASTRUCTURE, NOT PRODUCT CODE: only tests, the smoke check and the
 benchmark's cpu_baseline leg may import this module.  It never imports the GPU
@@ -19,7 +19,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liboracle_dq.so")
-_SOURCES = ["dq_oracle.c", "mx_oracle.c"]
+_SOURCES = ["dq_oracle.c", "mx_oracle.c", "pp_oracle.c"]
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC", "-Wall"]
 
 
