@@ -141,6 +141,51 @@ dq_status dq_replay_step_info(const dq_replay *plan, uint32_t step, uint32_t *ki
                               uint64_t *entries_other);
 void dq_replay_destroy(dq_replay *plan);
 
+/* ---------------------------------------------------------------------------------------
+ * Steps before and after the main stage.  Same conventions as above (device pointers, the
+ * calls enqueue and return); float and index arrays need 4-byte alignment only, gradient
+ * tensors 16.  A "bucket" is a run of n_sg_per_bucket super-groups allocated and reordered
+ * on its own; buckets lie back to back in every array.
+ */
+
+/* Section 3.1: per super-group j of ONE worker's tensor x (n_sg * 256 entries of dtype),
+ * mu_out[j] = mean of its entries and F_out[j] = sum of their squares, accumulated in fp32
+ * (16 entries left to right per lane, then a 16-lane butterfly). */
+dq_status dq_sg_stats(const void *x, dq_dtype dtype, uint64_t n_sg, float *mu_out, float *F_out, void *hip_stream);
+
+/* Section 3.1 / 3.5: what the statistics all-reduce returns.  mu_all and F_all hold the n
+ * workers' statistics row-major [n_workers][n_sg]; every contribution is rounded to bf16
+ * (nearest even: each worker sends two BF16 numbers per super-group), summed in rank order in
+ * fp32; mu[j] = sum / n (one division), F[j] = sum. */
+dq_status dq_stats_combine(const float *mu_all, const float *F_all, uint32_t n_workers, uint64_t n_sg, float *mu,
+                           float *F, void *hip_stream);
+
+/* Section 3.2 + Appendix A: widths in {2,4,8} from the summed squared norms F (>= 0) of each
+ * bucket.  A super-group gets 8 bits if F >= T48, else 4 bits if F >= T24 = T48 * 17/512 (one
+ * fp32 product), else 2 bits; T48 is the smallest positive fp32 value or +infinity for which
+ * sum_j width_j <= max_code_bits (per bucket), found by bisection on the bit pattern.
+ * DQ_EINVAL if max_code_bits < 2 * n_sg_per_bucket.  Outputs per bucket:
+ *   widths[j]  the width of super-group j
+ *   pos[j]     its index inside the reordered bucket: all 2-bit super-groups first, then the
+ *              4-bit, then the 8-bit ones, each class in original order (Section 3.5)
+ *   counts[4b .. 4b+3] = {#2-bit, #4-bit, #8-bit, bit pattern of T48} of bucket b
+ * One thread block per bucket. */
+dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
+                      uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream);
+
+/* Sections 3.1 and 3.5: out[super-group pos[j] of the bucket] = x[super-group j] - mu[j], the
+ * subtraction in fp32, the result stored in x's dtype (bf16: nearest even).  mu_or_null NULL:
+ * a plain permutation.  out must not overlap x.  At most 2^24 super-groups per bucket and
+ * 65535 buckets (DQ_EUNSUPPORTED beyond). */
+dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, const float *mu_or_null,
+                     uint32_t n_sg_per_bucket, uint32_t n_buckets, void *out, void *hip_stream);
+
+/* Section 3.4, last paragraph: out[super-group j] = sum[super-group pos[j]] + n_workers * mu[j]
+ * (fp32; `sum` is the main stage's result in reordered order, a sum over the workers of
+ * mean-subtracted entries).  mu_or_null NULL: only the permutation is undone. */
+dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_or_null, uint32_t n_workers,
+                     uint32_t n_sg_per_bucket, uint32_t n_buckets, float *out, void *hip_stream);
+
 const char *dq_status_str(dq_status s);
 /* Last HIP error string seen by this library on the calling thread (for DQ_EHIP). */
 const char *dq_last_hip_error(void);

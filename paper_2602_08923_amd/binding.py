@@ -23,6 +23,7 @@ EXPORTS = [
     "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_run_steps",
     "dq_replay_step_info",
     "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
+    "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_reorder", "dq_restore",
 ]
 
 
@@ -83,6 +84,11 @@ def lib():
         L.dq_replay_step_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u64)]
         L.dq_replay_destroy.argtypes = [vp]
         L.dq_replay_destroy.restype = None
+        L.dq_sg_stats.argtypes = [vp, i, u64, vp, vp, vp]
+        L.dq_stats_combine.argtypes = [vp, vp, u32, u64, vp, vp, vp]
+        L.dq_allocate.argtypes = [vp, u32, u32, u64, vp, vp, vp, vp]
+        L.dq_reorder.argtypes = [vp, i, vp, vp, u32, u32, vp, vp]
+        L.dq_restore.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp]
         _lib = L
     return _lib
 
@@ -273,3 +279,65 @@ class Replay:
             self.h = None
 
     __del__ = close
+
+
+# ------------------------------------------------------------------ before and after the main stage
+def dq_sg_stats(x, mu_out=None, F_out=None):
+    """Per-super-group mean and sum of squares of one worker's tensor -> (mu, F) float32."""
+    n_sg = x.numel() // 256
+    if x.numel() % 256:
+        raise DqError("tensor length must be a multiple of 256")
+    if mu_out is None:
+        mu_out = torch.empty(n_sg, dtype=torch.float32, device=x.device)
+    if F_out is None:
+        F_out = torch.empty(n_sg, dtype=torch.float32, device=x.device)
+    _check(lib().dq_sg_stats(_ptr(x), _dtype(x), n_sg, _ptr(mu_out), _ptr(F_out), _stream()))
+    return mu_out, F_out
+
+
+def dq_stats_combine(mu_all, F_all):
+    """mu_all, F_all: float32 [n_workers, n_sg] -> (mu, F) float32 [n_sg]."""
+    n, J = mu_all.shape
+    if F_all.shape != mu_all.shape or mu_all.dtype != torch.float32 or F_all.dtype != torch.float32:
+        raise DqError("statistics are two float32 tensors of the same [n_workers, n_sg] shape")
+    mu = torch.empty(J, dtype=torch.float32, device=mu_all.device)
+    F = torch.empty(J, dtype=torch.float32, device=mu_all.device)
+    _check(lib().dq_stats_combine(_ptr(mu_all), _ptr(F_all), n, J, _ptr(mu), _ptr(F), _stream()))
+    return mu, F
+
+
+def dq_allocate(F, n_sg_per_bucket, max_code_bits):
+    """F: float32 [n_buckets * n_sg_per_bucket] -> (widths uint8, pos int32 (holds uint32), counts int32 [n_buckets, 4])."""
+    if F.dtype != torch.float32 or F.numel() % n_sg_per_bucket:
+        raise DqError("F is float32 with a whole number of buckets")
+    nb = F.numel() // n_sg_per_bucket
+    widths = torch.empty(F.numel(), dtype=torch.uint8, device=F.device)
+    pos = torch.empty(F.numel(), dtype=torch.int32, device=F.device)
+    counts = torch.empty((nb, 4), dtype=torch.int32, device=F.device)
+    _check(lib().dq_allocate(_ptr(F), n_sg_per_bucket, nb, int(max_code_bits), _ptr(widths), _ptr(pos), _ptr(counts),
+                             _stream()))
+    return widths, pos, counts
+
+
+def dq_reorder(x, pos, n_sg_per_bucket, mu=None, out=None):
+    nb = pos.numel() // n_sg_per_bucket
+    if x.numel() != pos.numel() * 256 or pos.numel() % n_sg_per_bucket or pos.dtype != torch.int32:
+        raise DqError("x holds 256 entries per position; positions are int32, a whole number of buckets")
+    if mu is not None and (mu.dtype != torch.float32 or mu.numel() != pos.numel()):
+        raise DqError("mu is float32, one per super-group")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().dq_reorder(_ptr(x), _dtype(x), _ptr(pos), _ptr(mu), n_sg_per_bucket, nb, _ptr(out), _stream()))
+    return out
+
+
+def dq_restore(total, pos, n_sg_per_bucket, n_workers, mu=None, out=None):
+    nb = pos.numel() // n_sg_per_bucket
+    if total.dtype != torch.float32 or total.numel() != pos.numel() * 256 or pos.dtype != torch.int32:
+        raise DqError("the main stage's result is float32, 256 entries per position")
+    if mu is not None and (mu.dtype != torch.float32 or mu.numel() != pos.numel()):
+        raise DqError("mu is float32, one per super-group")
+    if out is None:
+        out = torch.empty_like(total)
+    _check(lib().dq_restore(_ptr(total), _ptr(pos), _ptr(mu), n_workers, n_sg_per_bucket, nb, _ptr(out), _stream()))
+    return out

@@ -1,0 +1,227 @@
+"""HIP path of the steps before and after the main stage against the CPU oracle
+(oracle/pp_oracle.c), through the C ABI.  Each stage gets the oracle's output of the stage
+before it (never the other way round): statistics within the tolerance of fp32 accumulation
+against the float64 definition, everything that is an integer decision or a single rounded
+operation bit-exactly."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pp_oracle as P
+from paper_2602_08923_amd import binding as B
+from paper_2602_08923_amd import prep, workloads
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def draw(cfg, worker, entries, bucket=0):
+    return workloads.draw(workloads.CONFIGS[cfg], worker, bucket, device="cpu", entries=entries)
+
+
+def as_np(t):
+    return workloads.to_numpy(t)
+
+
+def lognormal_F(seed, J, zeros=0, ties=0):
+    rng = np.random.default_rng(seed)
+    F = np.exp(rng.normal(-14, 2.5, J)).astype(f32)
+    if zeros:
+        F[rng.integers(0, J, zeros)] = 0
+    if ties:
+        F[rng.integers(0, J, ties)] = F[0]
+    return F
+
+
+# ---------------------------------------------------------------- statistics
+@pytest.mark.parametrize("cfg,n_sg", [(1, 1), (1, 5), (2, 1027), (4, 4096), (5, 2049)])
+def test_sg_stats(dev, cfg, n_sg):
+    x = draw(cfg, 3, n_sg * 256)
+    mu64, F64 = P.sg_stats(as_np(x))
+    mu, F = B.dq_sg_stats(x.to(dev))
+    mu, F = host(mu).astype(np.float64), host(F).astype(np.float64)
+    # 16 sequential + 4 tree additions in fp32: relative error below 20 * 2^-24 of the sum of magnitudes
+    tol = 20 * 2.0 ** -24
+    assert np.all(np.abs(F - F64) <= tol * F64 + 1e-45)
+    mean_abs = np.abs(x.double().numpy().reshape(n_sg, 256)).sum(axis=1) / 256
+    assert np.all(np.abs(mu - mu64) <= tol * mean_abs + 1e-45)
+    assert np.all(F64 > 0)
+
+
+def test_sg_stats_exact_cases(dev):
+    c = 0.375
+    x = np.concatenate([np.full(256, c), np.tile([0.5, -0.5], 128), np.arange(256) * 2.0 ** -10, np.zeros(256)]).astype(f32)
+    for t in (torch.from_numpy(x), torch.from_numpy(x).to(torch.bfloat16)):      # all values are bf16-exact
+        mu, F = B.dq_sg_stats(t.to(dev))
+        assert host(mu).tolist() == [c, 0.0, 127.5 * 2.0 ** -10, 0.0]
+        assert host(F).tolist() == [256 * c * c, 64.0, 5559680 * 2.0 ** -20, 0.0]
+    mu, F = B.dq_sg_stats(torch.empty(0, dtype=torch.float32, device=dev))       # empty input
+    assert mu.numel() == 0 and F.numel() == 0
+
+
+def test_stats_combine(dev):
+    n, J = 8, 3001
+    xs = [draw(2, w, J * 256) for w in range(n)]
+    st = [P.sg_stats(as_np(x)) for x in xs]
+    mu_all = np.array([s[0] for s in st], f32)
+    F_all = np.array([s[1] for s in st], f32)
+    want_mu, want_F = P.stats_combine(mu_all, F_all)
+    mu, F = B.dq_stats_combine(torch.from_numpy(mu_all).to(dev), torch.from_numpy(F_all).to(dev))
+    assert np.array_equal(host(mu).view(np.uint32), want_mu.view(np.uint32))
+    assert np.array_equal(host(F).view(np.uint32), want_F.view(np.uint32))
+    # n = 1 and a worker count that is not a power of two (the division is rounded, not a shift)
+    for k in (1, 3):
+        want_mu, want_F = P.stats_combine(mu_all[:k], F_all[:k])
+        mu, F = B.dq_stats_combine(torch.from_numpy(mu_all[:k].copy()).to(dev), torch.from_numpy(F_all[:k].copy()).to(dev))
+        assert np.array_equal(host(mu).view(np.uint32), want_mu.view(np.uint32))
+        assert np.array_equal(host(F).view(np.uint32), want_F.view(np.uint32))
+
+
+# ---------------------------------------------------------------- allocation
+def check_allocate(dev, F, J, budget):
+    nb = F.size // J
+    widths, pos, counts = B.dq_allocate(torch.from_numpy(F).to(dev), J, budget)
+    widths, pos, counts = host(widths), host(pos).view(np.uint32), host(counts).view(np.uint32)
+    for b in range(nb):
+        w, tbits = P.allocate(F[b * J:(b + 1) * J], budget)
+        p, c = P.positions(w)
+        assert np.array_equal(widths[b * J:(b + 1) * J], w), f"bucket {b}"
+        assert np.array_equal(pos[b * J:(b + 1) * J], p), f"bucket {b}"
+        assert counts[b].tolist() == c + [tbits], f"bucket {b}"
+    return counts
+
+
+@pytest.mark.parametrize("J", [1, 7, 64, 1000, 1024, 1025, 51200, 65536])
+@pytest.mark.parametrize("bits", [3.0, 5.0])
+def test_allocate_sizes(dev, J, bits):
+    F = lognormal_F(J, J, zeros=min(J // 10, 50), ties=min(J // 7, 40))
+    check_allocate(dev, F, J, int(math.floor(prep.code_bits(bits) * J)))
+
+
+def test_allocate_many_buckets_full_size(dev):
+    """config 4's shape: 100 buckets of 51,200 super-groups, one block per bucket."""
+    J, nb = 51200, 100
+    rng = np.random.default_rng(4)
+    F = np.concatenate([np.exp(rng.normal(rng.uniform(-20, -8), rng.uniform(0.5, 3.0), J)) for _ in range(nb)]).astype(f32)
+    counts = check_allocate(dev, F, J, int(math.floor(prep.code_bits(3.0) * J)))
+    assert len({tuple(c[:3]) for c in counts.tolist()}) > 50
+
+
+def test_allocate_beyond_register_capacity(dev):
+    J = 65536 + 4321                                   # runs no longer fit 64 registers per thread
+    F = lognormal_F(99, 2 * J, zeros=100, ties=100)
+    check_allocate(dev, F, J, int(math.floor(prep.code_bits(4.0) * J)))
+
+
+def test_allocate_budget_edges(dev):
+    F = lognormal_F(5, 2000)
+    c = check_allocate(dev, F, 2000, 2 * 2000)                       # exactly 2 bits each
+    assert c[0][:3].tolist() == [2000, 0, 0]
+    c = check_allocate(dev, F, 2000, 8 * 2000 + 5)                   # everything fits
+    assert c[0][:3].tolist() == [0, 0, 2000] and c[0][3] == 1
+    c = check_allocate(dev, np.zeros(512, f32), 512, 3 * 512)        # an all-zero bucket
+    assert c[0][:3].tolist() == [512, 0, 0]
+    with pytest.raises(B.DqError):
+        B.dq_allocate(torch.from_numpy(F).to(dev), 2000, 3999)       # below 2 bits per coordinate
+
+
+# ---------------------------------------------------------------- reorder / restore
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("J,nb", [(1, 1), (37, 3), (1030, 2)])
+def test_reorder_and_restore(dev, dtype, J, nb):
+    n_sg = J * nb
+    x = draw(2 if dtype == "bf16" else 1, 1, n_sg * 256)
+    rng = np.random.default_rng(J)
+    widths = rng.choice(np.array([2, 4, 8], np.uint8), n_sg, p=[0.4, 0.4, 0.2])
+    pos = np.concatenate([P.positions(widths[b * J:(b + 1) * J])[0] for b in range(nb)])
+    mu = (rng.standard_normal(n_sg) * 1e-4).astype(f32)
+    xn = as_np(x)
+    pos_t = torch.from_numpy(pos.view(np.int32)).to(dev)
+    mu_t = torch.from_numpy(mu).to(dev)
+    for m, m_t in ((mu, mu_t), (None, None)):
+        want = np.concatenate([P.reorder(xn[b * J * 256:(b + 1) * J * 256], pos[b * J:(b + 1) * J],
+                                         None if m is None else m[b * J:(b + 1) * J]) for b in range(nb)])
+        got = B.dq_reorder(x.to(dev), pos_t, J, mu=m_t)
+        assert np.array_equal(as_np(got.cpu()), want)
+    total = (rng.standard_normal(n_sg * 256) * 1e-2).astype(f32)
+    for m, m_t in ((mu, mu_t), (None, None)):
+        want = np.concatenate([P.restore(total[b * J * 256:(b + 1) * J * 256], pos[b * J:(b + 1) * J],
+                                         None if m is None else m[b * J:(b + 1) * J], 8) for b in range(nb)])
+        got = B.dq_restore(torch.from_numpy(total).to(dev), pos_t, J, 8, mu=m_t)
+        assert np.array_equal(host(got).view(np.uint32), want.view(np.uint32))
+
+
+def test_reorder_full_bucket(dev):
+    """One worker's whole config-2 bucket (13,107,200 bf16 entries), allocation from the oracle."""
+    wl = workloads.CONFIGS[2]
+    J = wl.entries // 256
+    x = workloads.draw(wl, 0, 0, device="cpu")
+    mu64, F64 = P.sg_stats(as_np(x))
+    mu, F = P.stats_combine(mu64.astype(f32)[None], (8 * F64).astype(f32)[None])
+    w, _ = P.allocate(F, int(math.floor(prep.code_bits(wl.budget_bits) * J)))
+    pos, counts = P.positions(w)
+    assert counts[0] > 0 and counts[1] > 0
+    got = B.dq_reorder(x.to(dev), torch.from_numpy(pos.view(np.int32)).to(dev), J, mu=torch.from_numpy(mu).to(dev))
+    assert np.array_equal(as_np(got.cpu()), P.reorder(as_np(x), pos, mu))
+    total = got.float()
+    back = B.dq_restore(total, torch.from_numpy(pos.view(np.int32)).to(dev), J, 1, mu=torch.from_numpy(mu).to(dev))
+    assert np.array_equal(host(back).view(np.uint32), P.restore(host(total), pos, mu, 1).view(np.uint32))
+    # restoring what was reordered returns the gradient up to the bf16 rounding of x - mu
+    err = (back.cpu().double() - x.double()).abs().max().item()
+    assert err <= 2.0 ** -8 * x.double().abs().max().item()
+
+
+def test_rejects_bad_arguments(dev):
+    x = torch.zeros(512, dtype=torch.float32, device=dev)
+    pos = torch.zeros(2, dtype=torch.int32, device=dev)
+    L = B.lib()
+    st = L.dq_reorder(B._ptr(x), 0, B._ptr(pos), None, 2, 1, B._ptr(x), None)         # in place
+    assert st == B.DQ_EINVAL
+    st = L.dq_reorder(x.data_ptr() + 4, 0, B._ptr(pos), None, 2, 1, B._ptr(torch.empty_like(x)), None)
+    assert st == B.DQ_EALIGN
+    st = L.dq_restore(B._ptr(x), B._ptr(pos), None, 0, 2, 1, B._ptr(torch.empty_like(x)), None)   # n = 0
+    assert st == B.DQ_EINVAL
+    st = L.dq_sg_stats(B._ptr(x), 7, 2, B._ptr(x), B._ptr(x), None)                  # unknown dtype
+    assert st == B.DQ_EINVAL
+
+
+def test_whole_pipeline_is_consistent(dev):
+    """statistics -> combine -> allocate -> reorder -> ring reduce-scatter -> restore, all on the GPU:
+    the allocation meets its budget with larger norms never getting fewer bits, and the restored
+    result estimates the true sum."""
+    wl = workloads.CONFIGS[2]
+    n, J = 8, 4096
+    xs = [workloads.draw(wl, w, 0, device=dev, entries=J * 256) for w in range(n)]
+    xs[3][:256] += 0.5                                                   # a super-group with a large mean
+    st = [B.dq_sg_stats(x) for x in xs]
+    mu, F = B.dq_stats_combine(torch.stack([s[0] for s in st]), torch.stack([s[1] for s in st]))
+    budget = int(math.floor(prep.code_bits(5.0) * J))
+    widths, pos, counts = B.dq_allocate(F, J, budget)
+    c = counts.cpu().numpy()[0]
+    w = host(widths).astype(int)
+    assert sum(c[:3]) == J and budget - 6 < int(w.sum()) <= budget
+    order = np.argsort(host(F), kind="stable")
+    assert np.all(np.diff(w[order]) >= 0)
+    re = [B.dq_reorder(x, pos, J, mu=mu) for x in xs]
+    ctx = B.Context(n, seed=11)
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, re, J, [[int(v) for v in c[:3]]])
+    rp.run()
+    out = B.dq_restore(rp.out, pos, J, n, mu=mu)
+    true = sum(x.double() for x in xs)
+    est = out.double()
+    assert float(((est - true) ** 2).sum() / (true ** 2).sum()) < 0.05
+    # the shifted super-group: without the mean handling its 0.5 offset would dominate the error
+    assert float((est[:256] - true[:256]).abs().max()) < 0.02
