@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--mx-format", type=int, default=1, choices=[1, 2, 3], help="config 3 only: 1 FP8, 2 FP6, 3 FP4")
     ap.add_argument("--entries", type=int, default=None, help="override entries per worker (multiple of 256*workers)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")
+    ap.add_argument("--no-prepost", action="store_true",
+                    help="skip the context timings of the steps before and after the main stage")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, as the known-size reference row for HBM counters")
     args = ap.parse_args()
@@ -156,6 +158,60 @@ def main():
         "timing": "HIP events on the launch stream bracketing the consecutive DAR launches of each replay, inside the timed region",
     }
 
+    # ---- context only: the steps before and after the main stage on this workload's shape
+    # (statistics of every worker, their combination, allocation, mean-subtracting reorder of
+    # every worker, restore of the result), each timed with events over `reps` runs
+    prepost = None
+    if codec == 0 and not args.no_prepost and wl.topology != "chain":
+        import math
+        raw = [workloads.draw(wl, w, 0, device=dev, entries=entries) for w in range(n)]
+        mu_all = torch.empty((n, n_sg), dtype=torch.float32, device=dev)
+        F_all = torch.empty((n, n_sg), dtype=torch.float32, device=dev)
+        budget = int(math.floor(prep.code_bits(wl.budget_bits) * n_sg))
+        re_out = torch.empty_like(raw[0])
+        final = torch.empty(entries, dtype=torch.float32, device=dev)
+        state = {}
+
+        def f_stats():
+            for w in range(n):
+                B.dq_sg_stats(raw[w], mu_all[w], F_all[w])
+
+        def f_combine():
+            state["mu"], state["F"] = B.dq_stats_combine(mu_all, F_all)
+
+        def f_alloc():
+            state["w"], state["pos"], state["counts"] = B.dq_allocate(state["F"], n_sg, budget)
+
+        def f_reorder():
+            for w in range(n):
+                B.dq_reorder(raw[w], state["pos"], n_sg, mu=state["mu"], out=re_out)
+
+        def f_restore():
+            B.dq_restore(rp.out, state["pos"], n_sg, n, mu=state["mu"], out=final)
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            b.synchronize()
+            return a.elapsed_time(b) * 1e3 / reps
+
+        t_stats, t_comb, t_alloc, t_reo, t_res = timed(f_stats), timed(f_combine), timed(f_alloc), timed(f_reorder), timed(f_restore)
+        c = state["counts"].cpu().numpy()[0]
+        prepost = {
+            "stats_us": round(t_stats, 1), "stats_GBps": round(n * entries * dtype_bytes / t_stats / 1e3, 1),
+            "combine_us": round(t_comb, 1), "allocate_us": round(t_alloc, 1),
+            "reorder_us": round(t_reo, 1), "reorder_GBps": round(n * entries * 2 * dtype_bytes / t_reo / 1e3, 1),
+            "restore_us": round(t_res, 1), "restore_GBps": round(entries * 8 / t_res / 1e3, 1),
+            "sg_by_width_2_4_8_gpu_allocation": [int(c[0]), int(c[1]), int(c[2])],
+            "note": "all workers per figure (stats and reorder: one launch per worker); GB/s = bytes read + written",
+        }
+        del raw, re_out, final
+
     if args.calibrate_copy:  # 2^30 bytes read + 2^30 bytes written by one copy kernel
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -213,6 +269,7 @@ def main():
                    "budget_bits": wl.budget_bits if codec == 0 else None, "sg_by_width_2_4_8": counts if codec == 0 else None,
                    "hop_steps_per_replay": n_steps, "entries_all_hops": hop_entries},
         "roofline": roofline,
+        "prepost": prepost,
         "cpu_baseline": cpu,
         "step_ms_by_kind": {k: round(float(np.mean(v)), 5) for k, v in per_kind.items()},
     }

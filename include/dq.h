@@ -160,8 +160,8 @@ dq_status dq_sg_stats(const void *x, dq_dtype dtype, uint64_t n_sg, float *mu_ou
 dq_status dq_stats_combine(const float *mu_all, const float *F_all, uint32_t n_workers, uint64_t n_sg, float *mu,
                            float *F, void *hip_stream);
 
-/* Section 3.2 + Appendix A: widths in {2,4,8} from the summed squared norms F (>= 0) of each
- * bucket.  A super-group gets 8 bits if F >= T48, else 4 bits if F >= T24 = T48 * 17/512 (one
+/* Section 3.2 + Appendix A: widths in {2,4,8} from the summed squared norms F of each bucket
+ * (F >= 0; negative values and NaN are unspecified input).  A super-group gets 8 bits if F >= T48, else 4 bits if F >= T24 = T48 * 17/512 (one
  * fp32 product), else 2 bits; T48 is the smallest positive fp32 value or +infinity for which
  * sum_j width_j <= max_code_bits (per bucket), found by bisection on the bit pattern.
  * DQ_EINVAL if max_code_bits < 2 * n_sg_per_bucket.  Outputs per bucket:

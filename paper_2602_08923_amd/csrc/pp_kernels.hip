@@ -102,141 +102,203 @@ __global__ void __launch_bounds__(kThreads) k_combine(const float *mu_all, const
 }
 
 // ---------------------------------------------------------------------------------------
-// Allocation: one block of 1024 threads per bucket.  Thread t owns the run of `per`
-// consecutive super-groups starting at t*per (in registers when per <= kRegs), so that the
-// positions of the stable reorder follow from one block-wide exclusive scan.
+// Allocation: one block of 1024 threads per bucket.  Super-group j = 1024*k + t sits in slot k
+// of thread t (a register when the bucket has at most 64 rows of 1024), so every global access
+// is coalesced.  Values are handled as int32 bit patterns: non-negative floats order like their
+// patterns, and the difference of two patterns below 2^31 has the sign of the comparison,
+// F >= theta  <=>  bits(F) - bits(theta) >= 0.  Negative values and NaN count as +0; slots past
+// the bucket's end hold -1, which is below every threshold.
 constexpr int kAllocThreads = 1024;
+constexpr int kAllocWaves = kAllocThreads / 64;
 constexpr int kRegs = 64;
 
-__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *lds) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d, 64);
-  const uint32_t wave = threadIdx.x >> 6;
-  __syncthreads();  // the previous round's readers are done
-  if ((threadIdx.x & 63u) == 0) lds[wave] = v;
-  __syncthreads();
-  uint32_t tot = 0;
-#pragma unroll
-  for (int w = 0; w < kAllocThreads / 64; ++w) tot += lds[w];
-  return tot;
-}
+__device__ __forceinline__ int32_t pattern_of(float f) { return f > 0.0f ? (int32_t)f2u(f) : 0; }
 
-// widths follow Section 3.2's tied thresholds: T_{2,4} = 17/512 * T_{4,8}
-__device__ __forceinline__ uint32_t width_of(float F, float theta, float t24) {
-  return F >= theta ? 8u : (F >= t24 ? 4u : 2u);
+// class 0, 1, 2 = 2, 4, 8 bits; 3 = no super-group.  Section 3.2's tied thresholds:
+// p8 = pattern of T_{4,8}, p4 = pattern of T_{2,4} = T_{4,8} * 17/512.
+__device__ __forceinline__ uint32_t class_of(int32_t v, int32_t p4, int32_t p8) {
+  return v < 0 ? 3u : (v >= p8 ? 2u : (v >= p4 ? 1u : 0u));
 }
 
 template <bool IN_REGS>
 __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, uint32_t J, uint64_t max_code_bits,
                                                             uint8_t *widths_all, uint32_t *pos_all, uint32_t *counts_all) {
-  __shared__ uint32_t red[kAllocThreads / 64];
-  __shared__ uint32_t scan[3][kAllocThreads / 64];
+  __shared__ uint32_t red[2][2][kAllocWaves];
+  __shared__ uint32_t tot[kRegs * kAllocWaves][3];  // per (row, wave): class counts, then their exclusive scan
+  __shared__ uint32_t wsum[kAllocWaves][3];
   const float *F = F_all + (uint64_t)blockIdx.x * J;
   uint8_t *widths = widths_all + (uint64_t)blockIdx.x * J;
   uint32_t *pos = pos_all + (uint64_t)blockIdx.x * J;
-  const uint32_t per = (J + kAllocThreads - 1) / kAllocThreads;
-  const uint32_t j0 = min(threadIdx.x * per, J), j1 = min(j0 + per, J);
-  float fr[IN_REGS ? kRegs : 1];
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t rows = (J + kAllocThreads - 1) / kAllocThreads;
+  int32_t fr[IN_REGS ? kRegs : 1];
   if constexpr (IN_REGS) {
 #pragma unroll
-    for (int k = 0; k < kRegs; ++k) fr[k] = (j0 + k < j1) ? gld<float>(F + j0 + k) : -1.0f;  // -1: below any threshold
+    for (int k = 0; k < kRegs; ++k) {
+      const uint32_t j = k * kAllocThreads + tid;
+      fr[k] = j < J ? pattern_of(gld<float>(F + j)) : -1;
+    }
   }
-  auto count = [&](float theta, uint32_t &c4, uint32_t &c8) {
-    const float t24 = theta * (17.0f / 512.0f);
-    c4 = 0; c8 = 0;
+  // Counts over the wave of super-groups at or above T_{2,4} and T_{4,8}.  In registers a funnel
+  // shift collects the sign bits of 32 differences in a word and one population count per word
+  // turns them into the number below the threshold.
+  auto count = [&](int32_t p4, int32_t p8, uint32_t &c4, uint32_t &c8) {
+    uint32_t a4 = 0, a8 = 0;
     if constexpr (IN_REGS) {
+      uint32_t below4 = 0, below8 = 0;
 #pragma unroll
-      for (int k = 0; k < kRegs; ++k) {
-        c4 += fr[k] >= t24 ? 1u : 0u;
-        c8 += fr[k] >= theta ? 1u : 0u;
+      for (int h = 0; h < kRegs / 32; ++h) {
+        uint32_t m4 = 0, m8 = 0;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+          m4 = __builtin_amdgcn_alignbit(m4, (uint32_t)(fr[32 * h + k] - p4), 31);
+          m8 = __builtin_amdgcn_alignbit(m8, (uint32_t)(fr[32 * h + k] - p8), 31);
+        }
+        below4 += __builtin_popcount(m4);
+        below8 += __builtin_popcount(m8);
       }
+      a4 = kRegs - below4;
+      a8 = kRegs - below8;
     } else {
-      for (uint32_t j = j0; j < j1; ++j) {
-        const float f = gld<float>(F + j);
-        c4 += f >= t24 ? 1u : 0u;
-        c8 += f >= theta ? 1u : 0u;
+      for (uint32_t j = tid; j < J; j += kAllocThreads) {
+        const int32_t v = pattern_of(gld<float>(F + j));
+        a4 += v >= p4 ? 1u : 0u;
+        a8 += v >= p8 ? 1u : 0u;
       }
     }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      a4 += __shfl_xor(a4, d, 64);
+      a8 += __shfl_xor(a8, d, 64);
+    }
+    c4 = a4; c8 = a8;
+  };
+  // The waves' counts meet in LDS, in one of two buffers by turns, so that one barrier per round
+  // is enough: a wave can only be one round ahead of the slowest reader.
+  uint32_t turn = 0;
+  auto block_counts = [&](uint32_t pattern, uint32_t &s4, uint32_t &s8) {
+    uint32_t c4, c8;
+    count((int32_t)f2u(u2f(pattern) * (17.0f / 512.0f)), (int32_t)pattern, c4, c8);
+    if (lane == 0) {
+      red[turn][0][wave] = c4;
+      red[turn][1][wave] = c8;
+    }
+    __syncthreads();
+    s4 = 0; s8 = 0;
+#pragma unroll
+    for (int w = 0; w < kAllocWaves; ++w) {
+      s4 += red[turn][0][w];
+      s8 += red[turn][1][w];
+    }
+    turn ^= 1u;
   };
   // smallest fp32 pattern in [1, +inf] whose allocation fits; the host has checked 2J <= budget.
   // An SG at or above T_{4,8} is also at or above T_{2,4}: cost = 2J + 2*c4 + 4*c8.
   uint32_t lo = 0, hi = 0x7F800000u;
   while (hi - lo > 1) {
     const uint32_t mid = lo + (hi - lo) / 2;
-    uint32_t c4, c8;
-    count(u2f(mid), c4, c8);
-    const uint32_t s4 = block_sum(c4, red);
-    const uint32_t s8 = block_sum(c8, red);
+    uint32_t s4, s8;
+    block_counts(mid, s4, s8);
     const uint64_t cost = 2ull * J + 2ull * s4 + 4ull * s8;
     if (cost <= max_code_bits) hi = mid; else lo = mid;
   }
-  const float theta = u2f(hi), t24 = theta * (17.0f / 512.0f);
-  // class counts of the thread's run, then exclusive scans over the block
-  uint32_t n[3] = {0, 0, 0};
-  if constexpr (IN_REGS) {
+  uint32_t s4, s8;
+  block_counts(hi, s4, s8);
+  const int32_t p8 = (int32_t)hi, p4 = (int32_t)f2u(u2f(hi) * (17.0f / 512.0f));
+  const uint32_t n_class[3] = {J - s4, s4 - s8, s8};
+  // first position of each class in the reordered bucket, advanced chunk by chunk
+  uint32_t next[3] = {0, n_class[0], n_class[0] + n_class[1]};
+
+  // Positions of the stable reorder, 64 rows of 1024 super-groups at a time: the rank of a
+  // super-group inside its class is (members in earlier rows and waves) + (members in lower lanes).
+  for (uint32_t r0 = 0; r0 < rows; r0 += kRegs) {
+    const uint32_t nr = min((uint32_t)kRegs, rows - r0);
+    auto slot = [&](uint32_t k) -> int32_t {  // buckets too large for registers: read again
+      const uint32_t j = (r0 + k) * kAllocThreads + tid;
+      return j < J ? pattern_of(gld<float>(F + j)) : -1;
+    };
+    // pass 1: class counts of every (row, wave)
+    if constexpr (IN_REGS) {
 #pragma unroll
-    for (int k = 0; k < kRegs; ++k)
-      if (j0 + k < j1) {
-        const uint32_t w = width_of(fr[k], theta, t24);
-        n[w == 2 ? 0 : w == 4 ? 1 : 2] += 1;
+      for (int k = 0; k < kRegs; ++k) {
+        if ((uint32_t)k < nr) {
+          const uint32_t c = class_of(fr[k], p4, p8);
+          const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2);
+          if (lane == 0) {
+            tot[k * kAllocWaves + wave][0] = (uint32_t)__builtin_popcountll(b0);
+            tot[k * kAllocWaves + wave][1] = (uint32_t)__builtin_popcountll(b1);
+            tot[k * kAllocWaves + wave][2] = (uint32_t)__builtin_popcountll(b2);
+          }
+        }
       }
-  } else {
-    for (uint32_t j = j0; j < j1; ++j) {
-      const uint32_t w = width_of(gld<float>(F + j), theta, t24);
-      n[w == 2 ? 0 : w == 4 ? 1 : 2] += 1;
-    }
-  }
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  uint32_t excl[3], total[3];
-#pragma unroll
-  for (int c = 0; c < 3; ++c) {
-    uint32_t inc = n[c];
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t up = __shfl_up(inc, d, 64);
-      if (lane >= (uint32_t)d) inc += up;
-    }
-    if (lane == 63) scan[c][wave] = inc;
-    excl[c] = inc - n[c];
-  }
-  __syncthreads();
-#pragma unroll
-  for (int c = 0; c < 3; ++c) {
-    uint32_t before = 0, all = 0;
-#pragma unroll
-    for (int w = 0; w < kAllocThreads / 64; ++w) {
-      const uint32_t s = scan[c][w];
-      before += (uint32_t)w < wave ? s : 0u;
-      all += s;
-    }
-    excl[c] += before;
-    total[c] = all;
-  }
-  uint32_t next[3] = {excl[0], total[0] + excl[1], total[0] + total[1] + excl[2]};
-  if constexpr (IN_REGS) {
-#pragma unroll
-    for (int k = 0; k < kRegs; ++k)
-      if (j0 + k < j1) {
-        const uint32_t w = width_of(fr[k], theta, t24);
-        const int c = w == 2 ? 0 : w == 4 ? 1 : 2;
-        gst<uint8_t>(widths + j0 + k, (uint8_t)w);
-        gst<uint32_t>(pos + j0 + k, next[c]);
-        next[c] += 1;
+    } else {
+      for (uint32_t k = 0; k < nr; ++k) {
+        const uint32_t c = class_of(slot(k), p4, p8);
+        const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2);
+        if (lane == 0) {
+          tot[k * kAllocWaves + wave][0] = (uint32_t)__builtin_popcountll(b0);
+          tot[k * kAllocWaves + wave][1] = (uint32_t)__builtin_popcountll(b1);
+          tot[k * kAllocWaves + wave][2] = (uint32_t)__builtin_popcountll(b2);
+        }
       }
-  } else {
-    for (uint32_t j = j0; j < j1; ++j) {
-      const uint32_t w = width_of(gld<float>(F + j), theta, t24);
-      const int c = w == 2 ? 0 : w == 4 ? 1 : 2;
-      gst<uint8_t>(widths + j, (uint8_t)w);
-      gst<uint32_t>(pos + j, next[c]);
-      next[c] += 1;
     }
+    __syncthreads();
+    // pass 2: exclusive scan of the counts in (row, wave) order; thread e owns entry e
+    uint32_t x[3], inc[3];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+      x[c] = tid < nr * kAllocWaves ? tot[tid][c] : 0u;
+      inc[c] = x[c];
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(inc[c], d, 64);
+        if (lane >= (uint32_t)d) inc[c] += up;
+      }
+      if (lane == 63) wsum[wave][c] = inc[c];
+    }
+    __syncthreads();
+    uint32_t chunk_total[3];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+      uint32_t before = 0, all = 0;
+#pragma unroll
+      for (int w = 0; w < kAllocWaves; ++w) {
+        const uint32_t t = wsum[w][c];
+        before += (uint32_t)w < wave ? t : 0u;
+        all += t;
+      }
+      chunk_total[c] = all;
+      if (tid < nr * kAllocWaves) tot[tid][c] = next[c] + before + inc[c] - x[c];
+    }
+    __syncthreads();
+    // pass 3: widths and positions, coalesced
+    auto emit = [&](uint32_t k, int32_t v) {
+      const uint32_t j = (r0 + k) * kAllocThreads + tid;
+      const uint32_t c = class_of(v, p4, p8);
+      const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2);
+      const uint64_t mine = c == 0 ? b0 : (c == 1 ? b1 : b2);
+      const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mine >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mine, 0u));
+      if (c < 3) {
+        gst<uint8_t>(widths + j, (uint8_t)(2u << c));
+        gst<uint32_t>(pos + j, tot[k * kAllocWaves + wave][c] + rank);
+      }
+    };
+    if constexpr (IN_REGS) {
+#pragma unroll
+      for (int k = 0; k < kRegs; ++k)
+        if ((uint32_t)k < nr) emit(k, fr[k]);
+    } else {
+      for (uint32_t k = 0; k < nr; ++k) emit(k, slot(k));
+    }
+#pragma unroll
+    for (int c = 0; c < 3; ++c) next[c] += chunk_total[c];
+    __syncthreads();  // tot and wsum are reused by the next chunk
   }
-  if (threadIdx.x == 0) {
+  if (tid == 0) {
     uint32_t *cnt = counts_all + 4ull * blockIdx.x;
-    gst<uint32_t>(cnt, total[0]);
-    gst<uint32_t>(cnt + 1, total[1]);
-    gst<uint32_t>(cnt + 2, total[2]);
+    gst<uint32_t>(cnt, n_class[0]);
+    gst<uint32_t>(cnt + 1, n_class[1]);
+    gst<uint32_t>(cnt + 2, n_class[2]);
     gst<uint32_t>(cnt + 3, hi);
   }
 }
