@@ -111,6 +111,8 @@ __global__ void __launch_bounds__(kThreads) k_combine(const float *mu_all, const
 constexpr int kAllocThreads = 1024;
 constexpr int kAllocWaves = kAllocThreads / 64;
 constexpr int kRegs = 64;
+constexpr uint32_t kBins = 2048;  // 2 per thread
+constexpr uint32_t kCap = 4096;   // candidates kept per threshold
 
 __device__ __forceinline__ int32_t pattern_of(float f) { return f > 0.0f ? (int32_t)f2u(f) : 0; }
 
@@ -126,6 +128,9 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
   __shared__ uint32_t red[2][2][kAllocWaves];
   __shared__ uint32_t tot[kRegs * kAllocWaves][3];  // per (row, wave): class counts, then their exclusive scan
   __shared__ uint32_t wsum[kAllocWaves][3];
+  __shared__ uint32_t hist[kBins + 2];   // top-11-bit histogram, then suffix counts (register path)
+  __shared__ int32_t cand[2][kCap];      // patterns that can still change c8 / c4
+  __shared__ uint32_t ncand[2];
   const float *F = F_all + (uint64_t)blockIdx.x * J;
   uint8_t *widths = widths_all + (uint64_t)blockIdx.x * J;
   uint32_t *pos = pos_all + (uint64_t)blockIdx.x * J;
@@ -135,8 +140,9 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
   if constexpr (IN_REGS) {
 #pragma unroll
     for (int k = 0; k < kRegs; ++k) {
-      const uint32_t j = k * kAllocThreads + tid;
-      fr[k] = j < J ? pattern_of(gld<float>(F + j)) : -1;
+      const uint32_t j = k * kAllocThreads + tid;  // all loads in flight at once: clamp, then mask
+      const int32_t v = pattern_of(gld<float>(F + min(j, J - 1)));
+      fr[k] = j < J ? v : -1;
     }
   }
   // Counts over the wave of super-groups at or above T_{2,4} and T_{4,8}.  In registers a funnel
@@ -192,15 +198,142 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
     }
     turn ^= 1u;
   };
-  // smallest fp32 pattern in [1, +inf] whose allocation fits; the host has checked 2J <= budget.
-  // An SG at or above T_{4,8} is also at or above T_{2,4}: cost = 2J + 2*c4 + 4*c8.
+  // Wanted: the smallest fp32 pattern in [1, +inf] whose allocation fits (the host has checked
+  // 2J <= budget).  An SG at or above T_{4,8} is also at or above T_{2,4}, so
+  // cost = 2J + 2*c4 + 4*c8, which never increases with the threshold: bisection from any
+  // bracket (lo does not fit or is 0, hi fits) ends at the same pattern.
+  auto p4_of = [](uint32_t pattern) { return f2u(u2f(pattern) * (17.0f / 512.0f)); };
   uint32_t lo = 0, hi = 0x7F800000u;
-  while (hi - lo > 1) {
-    const uint32_t mid = lo + (hi - lo) / 2;
-    uint32_t s4, s8;
-    block_counts(mid, s4, s8);
-    const uint64_t cost = 2ull * J + 2ull * s4 + 4ull * s8;
-    if (cost <= max_code_bits) hi = mid; else lo = mid;
+  bool narrowed = false;
+  uint32_t base4 = 0, base8 = 0;
+  if constexpr (IN_REGS) {
+    // (1) Histogram of the patterns' top 11 bits (bin b = patterns [b << 20, (b+1) << 20);
+    //     2040 << 20 is +infinity), turned into suffix counts S[b] = #{v : bin(v) >= b}.
+    for (uint32_t b = tid; b < kBins + 2; b += kAllocThreads) hist[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kRegs; ++k)
+      if (fr[k] >= 0) atomicAdd(&hist[(uint32_t)fr[k] >> 20], 1u);
+    __syncthreads();
+    {
+      // thread t owns bins 2t and 2t+1; suffix scan = total - exclusive prefix
+      const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+      uint32_t inc = h0 + h1;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(inc, d, 64);
+        if (lane >= (uint32_t)d) inc += up;
+      }
+      if (lane == 63) wsum[wave][0] = inc;
+      __syncthreads();
+      uint32_t before = 0, all = 0;
+#pragma unroll
+      for (int w = 0; w < kAllocWaves; ++w) {
+        const uint32_t t = wsum[w][0];
+        before += (uint32_t)w < wave ? t : 0u;
+        all += t;
+      }
+      const uint32_t excl = before + inc - (h0 + h1);  // patterns in bins below 2t
+      hist[2 * tid] = all - excl;
+      hist[2 * tid + 1] = all - excl - h0;
+      if (tid == 0) hist[kBins] = hist[kBins + 1] = 0;
+      __syncthreads();
+    }
+    // (2) Bracket in whole bins, by every thread alike (LDS reads only).  For a threshold on a
+    //     bin boundary c8 = S[b] is exact and c4 lies in [S[bin4 + 1], S[bin4]], bin4 the bin of
+    //     T_{2,4}: an upper and a lower bound of the cost, both monotone.
+    auto cost_bounds = [&](uint32_t b, uint64_t &c_min, uint64_t &c_max) {
+      const uint32_t bin4 = p4_of(b << 20) >> 20;
+      const uint64_t fixed = 2ull * J + 4ull * hist[b];
+      c_min = fixed + 2ull * hist[bin4 + 1];
+      c_max = fixed + 2ull * hist[bin4];
+    };
+    uint32_t b_no = 0, b_fit = kBins - 8;  // 2040: +infinity, everything at 2 bits
+    while (b_fit - b_no > 1) {             // smallest bin boundary that surely fits
+      const uint32_t mid = b_no + (b_fit - b_no) / 2;
+      uint64_t c_min, c_max;
+      cost_bounds(mid, c_min, c_max);
+      if (c_max <= max_code_bits) b_fit = mid; else b_no = mid;
+    }
+    uint32_t b_open = b_fit;
+    b_no = 0;                              // pattern 0 is no threshold: "does not fit"
+    while (b_open - b_no > 1) {            // largest bin boundary that surely does not fit
+      const uint32_t mid = b_no + (b_open - b_no) / 2;
+      uint64_t c_min, c_max;
+      cost_bounds(mid, c_min, c_max);
+      if (c_min > max_code_bits) b_no = mid; else b_open = mid;
+    }
+    lo = b_no << 20;
+    hi = b_fit << 20;
+    // (3) Only patterns strictly inside (lo, hi) can change c8 while the threshold moves in
+    //     (lo, hi], and only patterns in [p4(lo), p4(hi)) can change c4: collect them in LDS.
+    const int32_t lo8 = (int32_t)lo, hi8 = (int32_t)hi, lo4 = (int32_t)p4_of(lo), hi4 = (int32_t)p4_of(hi);
+    if (tid < 2) ncand[tid] = 0;
+    __syncthreads();
+    uint32_t always4 = 0;
+#pragma unroll
+    for (int k = 0; k < kRegs; ++k) {
+      const int32_t v = fr[k];
+      const bool in8 = v > lo8 && v < hi8, in4 = v >= lo4 && v < hi4;
+      always4 += v >= hi4 ? 1u : 0u;
+      const uint64_t m8 = __ballot(in8), m4 = __ballot(in4);
+      if (m8) {
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&ncand[0], (uint32_t)__builtin_popcountll(m8));
+        at = __shfl(at, 0, 64) + __builtin_amdgcn_mbcnt_hi((uint32_t)(m8 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m8, 0u));
+        if (in8 && at < kCap) cand[0][at] = v;
+      }
+      if (m4) {
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&ncand[1], (uint32_t)__builtin_popcountll(m4));
+        at = __shfl(at, 0, 64) + __builtin_amdgcn_mbcnt_hi((uint32_t)(m4 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m4, 0u));
+        if (in4 && at < kCap) cand[1][at] = v;
+      }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) always4 += __shfl_xor(always4, d, 64);
+    if (lane == 0) red[0][0][wave] = always4;
+    __syncthreads();
+    const uint32_t n8 = ncand[0], n4 = ncand[1];
+    base8 = hist[b_fit];  // patterns at or above hi: exact, hi is a bin boundary
+#pragma unroll
+    for (int w = 0; w < kAllocWaves; ++w) base4 += red[0][0][w];
+    narrowed = n8 <= kCap && n4 <= kCap;  // otherwise (masses of equal values) count everything again
+    __syncthreads();                      // red is reused below
+    if (narrowed) {
+      // (4) bisection over the candidates
+      while (hi - lo > 1) {
+        const uint32_t mid = lo + (hi - lo) / 2;
+        const int32_t m8 = (int32_t)mid, m4 = (int32_t)p4_of(mid);
+        uint32_t a4 = 0, a8 = 0;
+        for (uint32_t i = tid; i < n8; i += kAllocThreads) a8 += cand[0][i] >= m8 ? 1u : 0u;
+        for (uint32_t i = tid; i < n4; i += kAllocThreads) a4 += cand[1][i] >= m4 ? 1u : 0u;
+        uint32_t both = a4 | (a8 << 16);  // at most kCap / 1024 each per lane
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) both += __shfl_xor(both, d, 64);
+        if (lane == 0) red[turn][0][wave] = both;
+        __syncthreads();
+        uint32_t s4 = base4, s8 = base8;
+#pragma unroll
+        for (int w = 0; w < kAllocWaves; ++w) {
+          const uint32_t t = red[turn][0][w];
+          s4 += t & 0xFFFFu;
+          s8 += t >> 16;
+        }
+        turn ^= 1u;
+        const uint64_t cost = 2ull * J + 2ull * s4 + 4ull * s8;
+        if (cost <= max_code_bits) hi = mid; else lo = mid;
+      }
+    }
+  }
+  if (!narrowed) {
+    while (hi - lo > 1) {
+      const uint32_t mid = lo + (hi - lo) / 2;
+      uint32_t s4, s8;
+      block_counts(mid, s4, s8);
+      const uint64_t cost = 2ull * J + 2ull * s4 + 4ull * s8;
+      if (cost <= max_code_bits) hi = mid; else lo = mid;
+    }
   }
   uint32_t s4, s8;
   block_counts(hi, s4, s8);

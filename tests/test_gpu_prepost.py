@@ -126,6 +126,18 @@ def test_allocate_beyond_register_capacity(dev):
     check_allocate(dev, F, J, int(math.floor(prep.code_bits(4.0) * J)))
 
 
+@pytest.mark.parametrize("bits", [2.8, 4.0, 6.0, 8.5])
+def test_allocate_masses_of_equal_values(dev, bits):
+    """More equal norms than the kernel keeps as candidates of its narrowed search: it must fall
+    back to counting everything and still agree."""
+    J = 51200
+    F = lognormal_F(21, J)
+    F[5000:35000] = F[7]                      # 30,000 equal values
+    F[40000:46000] = np.float32(F[7] * np.float32(17.0 / 512.0))   # and 6,000 at the tied lower threshold
+    check_allocate(dev, F, J, int(math.floor(prep.code_bits(bits) * J)))
+    check_allocate(dev, np.full(J, 3.25e-7, f32), J, int(math.floor(prep.code_bits(bits) * J)))
+
+
 def test_allocate_budget_edges(dev):
     F = lognormal_F(5, 2000)
     c = check_allocate(dev, F, 2000, 2 * 2000)                       # exactly 2 bits each
