@@ -5,8 +5,7 @@
 // elements rounded to nearest-even and clamped to the largest normal.
 //
 // Mapping: one lane owns one block of 32 entries (its maximum is in-lane); a wave64 covers
-// 2048 entries per tile.  Element conversion is pure integer/exponent arithmetic on the
-// binary32 pattern, so it is exact and identical for every launch shape.
+// 2048 entries per tile.
 #include "dq_device.h"
 
 namespace dq {
@@ -34,30 +33,11 @@ __device__ __forceinline__ void gst(void *p, T v) {
 template <int FMT>
 struct Fmt;
 template <>
-struct Fmt<DQ_MXFP8_E4M3> { static constexpr int ebits = 4, mbits = 3, bias = 7, emax = 8, cb = 8; };
+struct Fmt<DQ_MXFP8_E4M3> { static constexpr int emax = 8, cb = 8; };  // largest exponent, code bits
 template <>
-struct Fmt<DQ_MXFP6_E3M2> { static constexpr int ebits = 3, mbits = 2, bias = 3, emax = 4, cb = 6; };
+struct Fmt<DQ_MXFP6_E3M2> { static constexpr int emax = 4, cb = 6; };
 template <>
-struct Fmt<DQ_MXFP4_E2M1> { static constexpr int ebits = 2, mbits = 1, bias = 1, emax = 2, cb = 4; };
-
-// magnitude code (exponent field | mantissa) of a >= 0 in element format F, RNE, saturating
-template <typename F>
-__device__ __forceinline__ uint32_t quantize_mag(float a) {
-  constexpr int drop = 23 - F::mbits;
-  constexpr int emin = 1 - F::bias;
-  // largest normal: exponent field all ones (E4M3 keeps mantissa 111 for NaN), mantissa all ones
-  constexpr uint32_t max_code = F::ebits == 4 ? 0x7Eu : ((1u << (F::ebits + F::mbits)) - 1u);
-  // below 2^emin the quantum is fixed at 2^(emin-mbits): adding 2^(23+emin-mbits) leaves the
-  // count of quanta (rounded to nearest even) in the low mantissa bits
-  const float c_sub = u2f((uint32_t)(127 + 23 + emin - F::mbits) << 23);
-  const uint32_t sub = f2u(a + c_sub) - f2u(c_sub);
-  // at or above 2^emin: round the mantissa to mbits bits, ties to even, on the bit pattern
-  const uint32_t b = f2u(a);
-  const uint32_t rounded = (b + ((b >> drop) & 1u) + ((1u << (drop - 1)) - 1u)) >> drop;
-  const uint32_t nrm = rounded - ((uint32_t)(127 - F::bias) << F::mbits);
-  const uint32_t code = (a < u2f((uint32_t)(127 + emin) << 23)) ? sub : nrm;
-  return code < max_code ? code : max_code;
-}
+struct Fmt<DQ_MXFP4_E2M1> { static constexpr int emax = 2, cb = 4; };
 
 template <typename LT>
 __device__ __forceinline__ void load_local32(const void *base, size_t first, float (&v)[32]) {
@@ -83,17 +63,34 @@ __device__ __forceinline__ void load_local32(const void *base, size_t first, flo
   }
 }
 
+// One block of 32 entries per lane, converted by gfx950's scaled conversion instructions
+// (V_CVT_SCALEF32_*): packed elements <-> fp32 with the block scale applied in the same
+// instruction, round to nearest even.  What measurement against the CPU oracle showed about them:
+//   - the scale operand is a binary32 whose exponent FIELD is taken as the E8M0 byte (so the
+//     pattern e << 23 is passed, also for e = 0);
+//   - the E4M3 narrowing turns overflow into NaN (0x7F) where MX saturates: values are clamped
+//     to +-448 * 2^(e-127) first (same result as round-then-saturate); E3M2 and E2M1 saturate;
+//   - the instruction set's "fp6" is E2M3; OCP's MXFP6 E3M2 is its "bf6";
+//   - the 32-wide 6-bit narrowing interleaves its two 16-entry inputs (a0 b0 a1 b1 ...), the
+//     widening returns entries in order.
+// Decoded element * scale is exact in binary32 for every code and scale byte, so adding the
+// local entry afterwards is the single-rounding fma the conversion rule asks for.
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x32 __attribute__((ext_vector_type(32)));
+
 template <int FMT, Kind KIND, typename LT>
 __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t n_blocks) {
   using F = Fmt<FMT>;
   constexpr bool kHasLocal = !__is_same(LT, NoLocal);
-  constexpr int cw = F::cb;  // dwords of codes per block (cb*32/32)
+  constexpr int cw = F::cb;
   const size_t scale_off = (size_t)n_blocks * (cw * 4);
   float v[32];
   if constexpr (kHasLocal) load_local32<LT>(job.local, (size_t)bi * 32, v);
-
   if constexpr (KIND != kCompress) {
-    uint32_t w[cw + 1];
+    uint32_t w[cw];
     const uint8_t *src = job.in + (size_t)bi * (cw * 4);
     if constexpr (cw == 8) {
       const u32x4 a = gld<u32x4>(src), b = gld<u32x4>(src + 16);
@@ -105,23 +102,34 @@ __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t
       const u32x4 a = gld<u32x4>(src);
       w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
     }
-    w[cw] = 0;
     const uint32_t e = gld<uint8_t>(job.in + scale_off + bi);
-    const float X = e ? u2f(e << 23) : u2f(0x00400000u);  // 2^(e-127); e = 0 is a binary32 subnormal
-    const float unbias = u2f((uint32_t)(254 - F::bias) << 23);  // 2^(127-bias)
+    const float X = u2f(e << 23);  // the instruction reads the exponent field as the E8M0 scale
+    float d[32];
+    if constexpr (cw == 8) {
 #pragma unroll
-    for (int k = 0; k < 32; ++k) {
-      const int bit = k * F::cb;
-      const uint64_t pair = (uint64_t)w[bit >> 5] | ((uint64_t)w[(bit >> 5) + 1] << 32);
-      const uint32_t code = (uint32_t)(pair >> (bit & 31)) & ((1u << F::cb) - 1u);
-      const uint32_t mag = code & ((1u << (F::cb - 1)) - 1u);
-      // the magnitude bits read as a binary32 pattern are the element value / 2^(127-bias)
-      const float el = u2f((mag << (23 - F::mbits)) | ((code >> (F::cb - 1)) << 31)) * unbias;
-      if constexpr (kHasLocal) v[k] = __builtin_fmaf(el, X, v[k]);
-      else v[k] = el * X;
+      for (int i = 0; i < 8; ++i) {
+        const f32x2 lo = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(w[i], X, false);
+        const f32x2 hi = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(w[i], X, true);
+        d[4 * i] = lo.x; d[4 * i + 1] = lo.y; d[4 * i + 2] = hi.x; d[4 * i + 3] = hi.y;
+      }
+    } else if constexpr (cw == 4) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const f32x2 b0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], X, 0);
+        const f32x2 b1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], X, 1);
+        const f32x2 b2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], X, 2);
+        const f32x2 b3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], X, 3);
+        d[8 * i] = b0.x; d[8 * i + 1] = b0.y; d[8 * i + 2] = b1.x; d[8 * i + 3] = b1.y;
+        d[8 * i + 4] = b2.x; d[8 * i + 5] = b2.y; d[8 * i + 6] = b3.x; d[8 * i + 7] = b3.y;
+      }
+    } else {
+      const f32x32 all = __builtin_amdgcn_cvt_scalef32_pk32_f32_bf6(u32x6{w[0], w[1], w[2], w[3], w[4], w[5]}, X);
+#pragma unroll
+      for (int k = 0; k < 32; ++k) d[k] = all[k];
     }
+#pragma unroll
+    for (int k = 0; k < 32; ++k) v[k] = kHasLocal ? d[k] + v[k] : d[k];
   }
-
   if constexpr (KIND == kDecompress) {
     float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(job.out) + (size_t)bi * 32);
 #pragma unroll
@@ -130,20 +138,39 @@ __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t
     float m = 0.0f;
 #pragma unroll
     for (int k = 0; k < 32; ++k) m = fmaxf(m, fabsf(v[k]));
-    // E8M0 byte: floor(log2 m) - emax + 127, clamped to [0, 254]; the biased exponent field of
-    // m is floor(log2 m) + 127 for normal m and 0 for zero / subnormal m (which clamp to 0 anyway)
     int e = (int)(f2u(m) >> 23) - F::emax;
     e = e < 0 ? 0 : (e > 254 ? 254 : e);
+    const float X = u2f((uint32_t)e << 23);
     uint32_t ow[cw];
+    if constexpr (cw == 8) {
+      // the E4M3 conversion turns overflow into NaN; MX saturates: clamp to the largest normal first
+      const float top = 448.0f * X;
 #pragma unroll
-    for (int i = 0; i < cw; ++i) ow[i] = 0;
+      for (int k = 0; k < 32; ++k) v[k] = __builtin_amdgcn_fmed3f(v[k], -top, top);
 #pragma unroll
-    for (int k = 0; k < 32; ++k) {
-      const float a = ldexpf(fabsf(v[k]), 127 - e);
-      const uint32_t code = quantize_mag<F>(a) | ((f2u(v[k]) >> 31) << (F::cb - 1));
-      const int bit = k * F::cb;
-      ow[bit >> 5] |= code << (bit & 31);
-      if ((bit & 31) + F::cb > 32) ow[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+      for (int i = 0; i < 8; ++i) {
+        s16x2 r = {0, 0};
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, v[4 * i], v[4 * i + 1], X, false);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, v[4 * i + 2], v[4 * i + 3], X, true);
+        ow[i] = __builtin_bit_cast(uint32_t, r);
+      }
+    } else if constexpr (cw == 4) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        uint32_t r = 0;
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * i], v[8 * i + 1], X, 0);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * i + 2], v[8 * i + 3], X, 1);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * i + 4], v[8 * i + 5], X, 2);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * i + 6], v[8 * i + 7], X, 3);
+        ow[i] = r;
+      }
+    } else {
+      f32x16 a, b;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) { a[k] = v[2 * k]; b[k] = v[2 * k + 1]; }  // the two inputs interleave
+      const u32x6 r = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(a, b, X);
+#pragma unroll
+      for (int i = 0; i < 6; ++i) ow[i] = r[i];
     }
     uint8_t *dst = static_cast<uint8_t *>(job.out) + (size_t)bi * (cw * 4);
     if constexpr (cw == 8) {
