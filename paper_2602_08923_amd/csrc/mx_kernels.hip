@@ -30,6 +30,10 @@ __device__ __forceinline__ void gst(void *p, T v) {
   *(__attribute__((address_space(1))) T *)p = v;
 }
 
+typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
+__device__ __forceinline__ void lds_put(uint32_t a, f32x4 v) { *reinterpret_cast<lds_f32x4 *>(a) = v; }
+__device__ __forceinline__ f32x4 lds_get(uint32_t a) { return *reinterpret_cast<const lds_f32x4 *>(a); }
+
 template <int FMT>
 struct Fmt;
 template <>
@@ -82,16 +86,17 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x32 __attribute__((ext_vector_type(32)));
 
 template <int FMT, Kind KIND, typename LT>
-__device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t n_blocks) {
+__device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t n_blocks, bool active, uint32_t xpose) {
   using F = Fmt<FMT>;
   constexpr bool kHasLocal = !__is_same(LT, NoLocal);
   constexpr int cw = F::cb;
   const size_t scale_off = (size_t)n_blocks * (cw * 4);
+  const uint64_t bl = active ? bi : n_blocks - 1;  // block whose inputs this lane reads
   float v[32];
-  if constexpr (kHasLocal) load_local32<LT>(job.local, (size_t)bi * 32, v);
+  if constexpr (kHasLocal) load_local32<LT>(job.local, (size_t)bl * 32, v);
   if constexpr (KIND != kCompress) {
     uint32_t w[cw];
-    const uint8_t *src = job.in + (size_t)bi * (cw * 4);
+    const uint8_t *src = job.in + (size_t)bl * (cw * 4);
     if constexpr (cw == 8) {
       const u32x4 a = gld<u32x4>(src), b = gld<u32x4>(src + 16);
       w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
@@ -102,7 +107,7 @@ __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t
       const u32x4 a = gld<u32x4>(src);
       w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
     }
-    const uint32_t e = gld<uint8_t>(job.in + scale_off + bi);
+    const uint32_t e = gld<uint8_t>(job.in + scale_off + bl);
     const float X = u2f(e << 23);  // the instruction reads the exponent field as the E8M0 scale
     float d[32];
     if constexpr (cw == 8) {
@@ -131,9 +136,26 @@ __device__ __forceinline__ void mx_block(const MxJob &job, uint64_t bi, uint64_t
     for (int k = 0; k < 32; ++k) v[k] = kHasLocal ? d[k] + v[k] : d[k];
   }
   if constexpr (KIND == kDecompress) {
-    float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(job.out) + (size_t)bi * 32);
+    // The wave's 64 blocks are 8 KB of consecutive output.  Lane l parks its 8 float4 in the
+    // wave's LDS area (slot index xor-ed with l % 8 against bank conflicts); round r then
+    // stores float4 number 64 r + l of the tile, 1 KB of consecutive memory per instruction.
+    const uint32_t lane = threadIdx.x & 63u;
+    if (active) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) gst<f32x4>(o + i, f32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]});
+      for (uint32_t c = 0; c < 8; ++c)
+        lds_put(xpose + lane * 128 + ((c ^ (lane & 7u)) * 16), f32x4{v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]});
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint64_t tile_first = bi - lane;  // first block of the wave's tile
+    float4 *o = reinterpret_cast<float4 *>(static_cast<float *>(job.out) + (size_t)tile_first * 32);
+#pragma unroll
+    for (uint32_t r = 0; r < 8; ++r) {
+      const uint32_t L = r * 64 + lane, w = L >> 3, c = L & 7u;
+      if (tile_first + w < n_blocks) gst<f32x4>(o + L, lds_get(xpose + w * 128 + ((c ^ (w & 7u)) * 16)));
+    }
+    __builtin_amdgcn_wave_barrier();  // the area is reused by the wave's next tile
   } else {
     float m = 0.0f;
 #pragma unroll
@@ -191,8 +213,20 @@ template <int FMT, Kind KIND, typename LT>
 __device__ __forceinline__ void mx_run(const MxJob &job) {
   const uint64_t n_blocks = job.n_entries / 32;
   const uint64_t stride = (uint64_t)gridDim.x * kBlockThreads;
-  for (uint64_t bi = (uint64_t)blockIdx.x * kBlockThreads + threadIdx.x; bi < n_blocks; bi += stride)
-    mx_block<FMT, KIND, LT>(job, bi, n_blocks);
+  if constexpr (KIND == kDecompress) {
+    // whole waves walk the tiles of 64 blocks together (the stores are a wave-wide transpose);
+    // lanes past the end of a ragged last tile redo the last block and store nothing
+    __shared__ float4 park[kBlockWaves * 512];  // 8 KB per wave
+    const uint32_t xpose = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float4 *)park + (threadIdx.x >> 6) * 8192;
+    const uint64_t first = (uint64_t)blockIdx.x * kBlockThreads + (threadIdx.x & ~63u);
+    for (uint64_t t0 = first; t0 < n_blocks; t0 += stride) {
+      const uint64_t bi = t0 + (threadIdx.x & 63u);
+      mx_block<FMT, KIND, LT>(job, bi, n_blocks, bi < n_blocks, xpose);
+    }
+  } else {
+    for (uint64_t bi = (uint64_t)blockIdx.x * kBlockThreads + threadIdx.x; bi < n_blocks; bi += stride)
+      mx_block<FMT, KIND, LT>(job, bi, n_blocks, true, 0u);
+  }
 }
 
 template <int FMT, Kind KIND, typename LT>
