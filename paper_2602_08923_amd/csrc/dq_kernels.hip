@@ -70,14 +70,19 @@ struct U4 {
   uint32_t x, y, z, w;
 };
 
+// a ^ b ^ c in one instruction (three-input bitwise operation, truth table 0x96)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
                                             uint32_t k1) {
 #pragma unroll
   for (int i = 0; i < 10; ++i) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
     const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t a = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t b = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t a = xor3((uint32_t)(p1 >> 32), c1, k0);
+    const uint32_t b = xor3((uint32_t)(p0 >> 32), c3, k1);
     c1 = (uint32_t)p1;
     c3 = (uint32_t)p0;
     c0 = a;
