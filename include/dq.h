@@ -109,7 +109,13 @@ dq_status dq_mx_decompress(dq_codec fmt, const void *packed_in, const void *loca
  * same order as the inputs).  DQ_CHAIN: the path of one ring chunk: worker_grads[i] is
  * worker i's slice of that chunk (n_buckets = 1, n_sg_bucket = the chunk's SG count); worker
  * 0 compresses, workers 1..n-2 run DAR, worker n-1 decompresses and adds.
- * codec: DQ_DYNAMIQ or an MX format (then n_sg_by_width is ignored). */
+ * codec: DQ_DYNAMIQ or an MX format (then n_sg_by_width is ignored).
+ * all_gather = 1 appends Section 3.4's "All-gather": one step in which the sink of every chunk
+ * (ring: worker c-1 mod n of chunk c; butterfly: worker c; chain: worker n-1) compresses its fp32
+ * sum with its own rank, and one step that decompresses every chunk back into `out`, so that
+ * `out` ends as what EVERY worker holds after the all-reduce, the sink included (all workers must
+ * end with the same bytes).  The decompression is run once per chunk, not once per receiving
+ * worker: the n copies would be identical. */
 typedef struct {
   dq_topology topology;
   dq_codec codec;
@@ -118,6 +124,7 @@ typedef struct {
   uint64_t n_sg_bucket;
   const uint32_t *n_sg_by_width; /* host, [n_buckets][3] */
   uint64_t first_sg;
+  uint32_t all_gather; /* 0: reduce-scatter only; 1: append the all-gather phase (see below) */
 } dq_replay_desc;
 
 /* Device scratch the replay needs (job tables, packed messages, fp32 keep-buffers). */

@@ -319,6 +319,24 @@ def butterfly_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None):
     return out
 
 
+
+def all_gather(orc, sums, n_sg_by_width, topology, first_sg=0):
+    """All-gather phase (Section 3.4): the sink of chunk c compresses its fp32 sum and
+    broadcasts it; whoever receives it decompresses it.  Every worker, the sink included,
+    keeps the decompressed message, so all workers end with the same bytes.  The sink is
+    worker c-1 mod n on a ring (where the reduce-scatter of chunk c ended) and worker c after
+    recursive halving; it compresses with its own rank, for super-groups it has compressed
+    nothing of before.  sums: the reduce-scatter's result per chunk."""
+    n = orc.n_workers
+    chunks = split_bucket(n_sg_by_width, n, first_sg)
+    out = []
+    for c in range(n):
+        sink = (c + n - 1) % n if topology == "ring" else c
+        msg = orc.compress(chunks[c], sink, np.ascontiguousarray(sums[c], dtype=np.float32))
+        out.append(orc.decompress(chunks[c], msg))
+    return out
+
+
 # ------------------------------------------------------------------ MX comparison codec
 
 MXFP8, MXFP6, MXFP4 = 1, 2, 3
@@ -378,3 +396,8 @@ def mx_ring_reduce_scatter(fmt, grads, trace=None):
                 trace[(t, c)] = msg
         out.append(mx_decompress(fmt, msg, m, np.ascontiguousarray(grads[(c + n - 1) % n][sl])))
     return out
+
+
+def mx_all_gather(fmt, sums):
+    """All-gather phase with the MX codec: compress each chunk's fp32 sum, decompress it."""
+    return [mx_decompress(fmt, mx_compress(fmt, np.ascontiguousarray(x, dtype=np.float32)), len(x)) for x in sums]

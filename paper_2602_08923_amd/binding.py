@@ -42,7 +42,8 @@ class Chunk(C.Structure):
 
 class ReplayDesc(C.Structure):
     _fields_ = [("topology", C.c_int), ("codec", C.c_int), ("dtype", C.c_int), ("n_buckets", C.c_uint32),
-                ("n_sg_bucket", C.c_uint64), ("n_sg_by_width", C.POINTER(C.c_uint32)), ("first_sg", C.c_uint64)]
+                ("n_sg_bucket", C.c_uint64), ("n_sg_by_width", C.POINTER(C.c_uint32)), ("first_sg", C.c_uint64),
+                ("all_gather", C.c_uint32)]
 
 
 _lib = None
@@ -229,7 +230,8 @@ def dq_mx_decompress(fmt, packed_in, n_entries, local=None, out=None):
 class Replay:
     """dq_replay: a prepared ring / butterfly / chain schedule over N simulated workers."""
 
-    def __init__(self, ctx, topology, codec, worker_grads, n_sg_bucket, n_sg_by_width=None, n_buckets=1, first_sg=0):
+    def __init__(self, ctx, topology, codec, worker_grads, n_sg_bucket, n_sg_by_width=None, n_buckets=1, first_sg=0,
+                 all_gather=False):
         self.ctx = ctx
         self.grads = list(worker_grads)
         dev = self.grads[0].device
@@ -240,7 +242,8 @@ class Replay:
                 for k in range(3):
                     flat[3 * b + k] = int(n_sg_by_width[b][k])
         self._widths = flat
-        desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg)
+        desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg,
+                          1 if all_gather else 0)
         self.desc = desc
         entries = n_sg_bucket * 256 * n_buckets
         for g in self.grads:

@@ -25,6 +25,7 @@ struct HostJob {
 struct Launch {
   dq::Kind kind;
   dq_dtype dtype;  // dtype of `local`
+  bool has_local = true;  // false: decompress without accumulation
   std::vector<HostJob> jobs;
   size_t table_off = 0;  // byte offset of this launch's job table in scratch
   uint32_t max_tiles = 0;
@@ -234,6 +235,39 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
     plan->steps.push_back(std::move(st));
   }
 
+  if (d->all_gather) {
+    // All-gather phase: the sink of each chunk compresses its fp32 sum (with its own rank: it has
+    // compressed nothing of this chunk before, so these random numbers are fresh), and every
+    // worker, the sink included, ends with the decompressed message.
+    std::vector<size_t> slot(ci.size());
+    off = align_up(off, 256);
+    size_t region = 0;
+    for (size_t i = 0; i < ci.size(); ++i) {
+      slot[i] = region;
+      region += align_up(ci[i].bytes, 256);
+    }
+    uint8_t *ag = base + off;
+    off += region;
+    Step sc, sd;
+    Launch comp, dec;
+    comp.kind = dq::kCompress;
+    comp.dtype = DQ_F32;
+    dec.kind = dq::kDecompress;
+    dec.dtype = DQ_F32;
+    dec.has_local = false;
+    for (uint32_t b = 0; b < d->n_buckets; ++b)
+      for (uint32_t c = 0; c < n_chunks; ++c) {
+        const size_t i = (size_t)b * n_chunks + c;
+        const uint32_t sink = d->topology == DQ_CHAIN ? n - 1 : (d->topology == DQ_RING ? (c + n - 1) % n : c);
+        comp.jobs.push_back(mk(ci[i], nullptr, out_ptr(b, c), ag + slot[i], sink));
+        dec.jobs.push_back(mk(ci[i], ag + slot[i], nullptr, out_ptr(b, c), sink));
+      }
+    sc.launches.push_back(std::move(comp));
+    sd.launches.push_back(std::move(dec));
+    plan->steps.push_back(std::move(sc));
+    plan->steps.push_back(std::move(sd));
+  }
+
   // job tables
   for (Step &st : plan->steps)
     for (Launch &L : st.launches) {
@@ -345,11 +379,11 @@ static dq_status run_step(dq_replay *plan, size_t i, hipStream_t s) {
     if (L.jobs.empty()) continue;
     hipError_t e;
     if (mx)
-      e = dq::mx_launch_batch(L.kind, plan->codec, L.dtype, true,
+      e = dq::mx_launch_batch(L.kind, plan->codec, L.dtype, L.has_local,
                               reinterpret_cast<const dq::MxJob *>(plan->scratch + L.table_off),
                               (uint32_t)L.jobs.size(), L.max_entries, plan->ctx->n_cu, s);
     else
-      e = dq::launch_batch(L.kind, L.dtype, true, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
+      e = dq::launch_batch(L.kind, L.dtype, L.has_local, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
                            (uint32_t)L.jobs.size(), L.max_tiles, L.total_tiles, plan->ctx->params, plan->ctx->n_cu, s);
     if (e != hipSuccess) return DQ_EHIP;
   }

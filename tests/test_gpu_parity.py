@@ -355,3 +355,55 @@ def test_result_does_not_depend_on_launch_shape(dev, monkeypatch):
     assert np.array_equal(wa[:3700 * 64], whole[:3700 * 64])                       # 2-bit codes
     assert np.array_equal(wa[3700 * 64:3700 * 64 + 7000 * 128], whole[3700 * 64:3700 * 64 + 7000 * 128])  # first 4-bit codes
     assert np.array_equal(wb[:8000 * 128], whole[3700 * 64 + 7000 * 128:3700 * 64 + 15000 * 128])         # the other 4-bit codes
+
+
+# ----------------------------------------------------------------------------- all-gather phase
+
+@pytest.mark.parametrize("topology", ["ring", "butterfly"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_all_gather_phase(dev, topology, dtype):
+    """Reduce-scatter followed by the all-gather: every worker ends with decompress(compress(sum))."""
+    n, n_sg = 8, 8 * 9
+    rng = np.random.default_rng(31)
+    grads = [make_local(rng, n_sg * 256, dtype) for _ in range(n)]
+    counts = [20, 41, 11]
+    orc = O.Oracle(n, seed=5)
+    rs = (O.ring_reduce_scatter if topology == "ring" else O.butterfly_reduce_scatter)(orc, grads, counts, first_sg=1000)
+    want = np.concatenate(O.all_gather(orc, rs, counts, topology, first_sg=1000))
+    ctx = B.Context(n, seed=5)
+    topo = B.DQ_RING if topology == "ring" else B.DQ_BUTTERFLY
+    rp = B.Replay(ctx, topo, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], n_sg, [counts], first_sg=1000, all_gather=True)
+    base = B.Replay(ctx, topo, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], n_sg, [counts], first_sg=1000)
+    assert rp.n_steps == base.n_steps + 2
+    assert [rp.step_info(i)[0] for i in (rp.n_steps - 2, rp.n_steps - 1)] == [0, 2]
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+    # the result is not the reduce-scatter's: one more quantization happened
+    assert not np.array_equal(want, np.concatenate(rs))
+
+
+def test_all_gather_phase_mx_and_chain(dev):
+    n, n_sg = 4, 4 * 6
+    rng = np.random.default_rng(32)
+    grads = [make_local(rng, n_sg * 256, "bf16") for _ in range(n)]
+    rs = O.mx_ring_reduce_scatter(B.DQ_MXFP6_E3M2, grads)
+    want = np.concatenate(O.mx_all_gather(B.DQ_MXFP6_E3M2, rs))
+    ctx = B.Context(n)
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_MXFP6_E3M2, [to_dev(g, dev) for g in grads], n_sg, all_gather=True)
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+    # chain: one chunk, the last worker is the sink
+    counts = [5, 12, 7]
+    orc = O.Oracle(n, seed=9)
+    ch = O.make_chunk(0, counts)
+    msg = orc.compress(ch, 0, grads[0])
+    for i in range(1, n - 1):
+        msg = orc.dar_hop(ch, i, msg, grads[i])
+    total = orc.decompress(ch, msg, grads[n - 1])
+    want = orc.decompress(ch, orc.compress(ch, n - 1, total))
+    rc = B.Replay(B.Context(n, seed=9), B.DQ_CHAIN, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], n_sg, [counts], all_gather=True)
+    rc.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rc.out), want)

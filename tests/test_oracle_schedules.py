@@ -119,3 +119,46 @@ def test_single_worker_passthrough():
     gs = grads(1, 2, 6)
     out = O.ring_reduce_scatter(orc, gs, [0, 2, 0])
     assert np.array_equal(out[0], gs[0])
+
+
+# ----------------------------------------------------------------- all-gather phase (Section 3.4)
+
+def test_all_gather_is_compress_then_decompress_by_the_sink():
+    """Chunk c's sum is compressed by the worker where its reduce-scatter ended (ring: c-1 mod n,
+    recursive halving: c) and everyone keeps the decompressed message."""
+    n = 4
+    orc = O.Oracle(n, seed=3)
+    counts = [4, 8, 4]
+    rng = np.random.default_rng(1)
+    sums = [(rng.standard_normal(4 * 256) * 1e-2).astype(np.float32) for _ in range(n)]
+    chunks = O.split_bucket(counts, n, first_sg=40)
+    for topo, sink_of in (("ring", lambda c: (c - 1) % n), ("butterfly", lambda c: c)):
+        got = O.all_gather(orc, sums, counts, topo, first_sg=40)
+        for c in range(n):
+            want = orc.decompress(chunks[c], orc.compress(chunks[c], sink_of(c), sums[c]))
+            assert np.array_equal(got[c], want)
+            other = orc.decompress(chunks[c], orc.compress(chunks[c], (sink_of(c) + 1) % n, sums[c]))
+            assert not np.array_equal(got[c], other)          # the rank feeds the rounding
+
+
+def test_all_gather_keeps_lattice_values_and_estimates_the_rest():
+    n = 4
+    orc = O.Oracle(n, seed=8)
+    T = orc.T(1)
+    rng = np.random.default_rng(2)
+    r = rng.integers(0, 8, 4 * 256)
+    r[::16] = 7
+    lattice = (np.where(rng.integers(0, 2, r.size) == 1, -1.0, 1.0) * T[r].astype(np.float64) * 0.5).astype(np.float32)
+    counts = [0, 4, 0]                                         # four 4-bit super-groups, one per chunk
+    sums = [lattice[c * 256:(c + 1) * 256] for c in range(n)]
+    out = O.all_gather(orc, sums, counts, "ring")
+    for c in range(n):
+        nz = sums[c] != 0
+        assert np.array_equal(out[c][nz], sums[c][nz])         # values on the codec's lattice survive
+    # off the lattice: every entry lands within one level gap of its group's scale
+    rough = [(rng.standard_normal(256) * 1e-3).astype(np.float32) for _ in range(n)]
+    out = O.all_gather(orc, rough, counts, "butterfly")
+    for c in range(n):
+        g = np.abs(rough[c]).reshape(16, 16).max(axis=1)
+        bound = np.repeat(g, 16) * (float(T[7] - T[6]) + 1.0 / 255 + 2.0 ** -7)
+        assert np.all(np.abs(out[c] - rough[c]) <= bound)
