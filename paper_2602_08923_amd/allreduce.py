@@ -1,0 +1,59 @@
+"""The whole simulated all-reduce of one bucket set on one GPU, as a sequence of boundary calls:
+statistics -> their combination -> bit allocation -> mean-subtracting reorder -> hop replay
+(reduce-scatter, optionally the all-gather) -> restore (Sections 3.1-3.4).  Host glue only:
+every step runs in the library's kernels.  Also the error measure the paper reports."""
+import math
+
+import torch
+
+from . import binding as B
+from . import prep
+
+
+def vnmse(estimate, truth):
+    """||estimate - truth||^2 / ||truth||^2 in float64 (the paper's vNMSE, Section 5)."""
+    e = estimate.double() - truth.double()
+    return float((e * e).sum() / (truth.double() ** 2).sum())
+
+
+def true_sum(worker_grads):
+    acc = torch.zeros(worker_grads[0].numel(), dtype=torch.float64, device=worker_grads[0].device)
+    for g in worker_grads:
+        acc += g.double()
+    return acc
+
+
+def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.DQ_DYNAMIQ, seed=0, round=0,
+                        all_gather=True, subtract_mean=True, n_sg_bucket=None, g4=1.3, g8=1.02):
+    """Returns (sum estimate in the original order, float32; info dict).
+    worker_grads: one tensor per simulated worker (same length, float32 or bfloat16, a whole
+    number of buckets of n_sg_bucket super-groups; default: one bucket).  MX codecs skip the
+    statistics, allocation and reorder (they have none) and ignore budget_bits."""
+    n = len(worker_grads)
+    entries = worker_grads[0].numel()
+    n_sg = entries // 256
+    J = n_sg_bucket or n_sg
+    if entries % 256 or n_sg % J or J % n:
+        raise B.DqError("buckets must hold a multiple of n_workers super-groups of 256 entries")
+    nb = n_sg // J
+    ctx = B.Context(n, seed=seed, round=round, g4=g4, g8=g8)
+    if codec != B.DQ_DYNAMIQ:
+        rp = B.Replay(ctx, topology, codec, worker_grads, J, n_buckets=nb, all_gather=all_gather)
+        rp.run()
+        return rp.out, {"replay_steps": rp.n_steps}
+    dev = worker_grads[0].device
+    mu_all = torch.empty((n, n_sg), dtype=torch.float32, device=dev)
+    F_all = torch.empty((n, n_sg), dtype=torch.float32, device=dev)
+    for w, g in enumerate(worker_grads):
+        B.dq_sg_stats(g, mu_all[w], F_all[w])
+    mu, F = B.dq_stats_combine(mu_all, F_all)
+    if not subtract_mean:
+        mu = None
+    budget = int(math.floor(prep.code_bits(budget_bits) * J))
+    widths, pos, counts = B.dq_allocate(F, J, budget)
+    by_width = [[int(v) for v in row[:3]] for row in counts.cpu().tolist()]
+    reordered = [B.dq_reorder(g, pos, J, mu=mu) for g in worker_grads]
+    rp = B.Replay(ctx, topology, B.DQ_DYNAMIQ, reordered, J, by_width, n_buckets=nb, all_gather=all_gather)
+    rp.run()
+    out = B.dq_restore(rp.out, pos, J, n, mu=mu)
+    return out, {"sg_by_width": by_width, "replay_steps": rp.n_steps}

@@ -99,6 +99,38 @@ def draw(wl: Workload, worker: int, bucket: int = 0, device="cpu", entries=None)
     return x if wl.dtype == "f32" else x.to(torch.bfloat16)
 
 
+# Section 6.2 / Appendix "Synthesizing data": the magnitude M of a super-group follows a mixture
+# of two LogNormal laws fitted to measured per-super-group norms (weights, mu, sigma of ln M as
+# printed with the paper's fit for K = 2); every coordinate of every worker is N(0, M^2 / 256).
+MIXTURE = ((0.79, -3.99, 1.22), (0.21, -16.41, 4.63))
+
+
+def mixture_magnitudes(n_sg, seed=0, device="cpu"):
+    """One magnitude per super-group, shared by all workers (float32 tensor)."""
+    g = _gen(device, 7_000_000 + seed)
+    pick = torch.rand(n_sg, generator=g, device=device)
+    z = torch.randn(n_sg, generator=g, device=device)
+    first = pick < MIXTURE[0][0]
+    mu = torch.where(first, torch.tensor(MIXTURE[0][1], device=device), torch.tensor(MIXTURE[1][1], device=device))
+    sd = torch.where(first, torch.tensor(MIXTURE[0][2], device=device), torch.tensor(MIXTURE[1][2], device=device))
+    return torch.exp(mu + sd * z).to(torch.float32)
+
+
+def draw_mixture(magnitudes, worker, seed=0, dtype=torch.bfloat16, out=None):
+    """Worker `worker`'s gradient for the given super-group magnitudes: i.i.d. N(0, M^2/256)
+    inside each super-group, rounded to `dtype`.  `out` (same dtype) is filled in place if given."""
+    device = magnitudes.device
+    n_sg = magnitudes.numel()
+    g = _gen(device, 7_100_000 + 100_000 * seed + worker)
+    x = torch.randn(n_sg, S, generator=g, device=device, dtype=torch.float32)
+    x *= (magnitudes / 16.0).unsqueeze(1)
+    x = x.reshape(-1)
+    if out is not None:
+        out.copy_(x)
+        return out
+    return x.to(dtype)
+
+
 def to_numpy(t: torch.Tensor):
     """Host copy as numpy: float32 stays float32, bfloat16 becomes its uint16 bit patterns."""
     t = t.detach().cpu().contiguous()

@@ -1,0 +1,72 @@
+"""Compression error of the whole simulated all-reduce on the paper's synthetic workload
+(Section 6.2: super-group magnitudes from a mixture of two LogNormal laws).  No oracle can
+replay these sizes; what is checked are the orderings the paper reports -- error grows with the
+number of workers, recursive halving beats the ring, DynamiQ beats MXFP8 at the same budget,
+more bits help -- and that the pipeline returns an estimate of the true sum at all."""
+import pytest
+import torch
+
+from paper_2602_08923_amd import allreduce as A
+from paper_2602_08923_amd import binding as B
+from paper_2602_08923_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def run(dev, n, J, bits, topology, codec=B.DQ_DYNAMIQ, seed=1):
+    M = workloads.mixture_magnitudes(J, seed=3, device=dev)
+    grads = [workloads.draw_mixture(M, w, seed=3) for w in range(n)]
+    est, info = A.simulated_allreduce(grads, bits, topology=topology, codec=codec, seed=seed)
+    torch.cuda.synchronize()
+    return A.vnmse(est, A.true_sum(grads)), info
+
+
+def test_error_orderings(dev):
+    J = 4096
+    ring8, i8 = run(dev, 8, J, 5.0, B.DQ_RING)
+    ring64, i64 = run(dev, 64, J, 5.0, B.DQ_RING)
+    bfly64, _ = run(dev, 64, J, 5.0, B.DQ_BUTTERFLY)
+    ring64_hi, _ = run(dev, 64, J, 8.5, B.DQ_RING)
+    mx64, _ = run(dev, 64, J, 8.5, B.DQ_RING, codec=B.DQ_MXFP8_E4M3)
+    print(f"\nvNMSE  ring n=8 b=5: {ring8:.3e}   ring n=64 b=5: {ring64:.3e}   butterfly n=64 b=5: {bfly64:.3e}"
+          f"   ring n=64 b=8.5: {ring64_hi:.3e}   MXFP8 ring n=64: {mx64:.3e}")
+    assert sum(i8["sg_by_width"][0]) == J and i64["replay_steps"] == 64 + 2
+    assert 0 < ring8 < ring64 < 1.0            # the error accumulates over the hops (Section 6.1)
+    assert bfly64 < ring64                     # log2(n) re-quantizations instead of n-1 (Section 5.4)
+    assert ring64_hi < ring64                  # more bits help
+    assert ring64_hi < mx64                    # DynamiQ beats MXFP8 at the same budget (Section 6.2)
+
+
+def test_reduce_scatter_only_is_more_accurate_than_with_all_gather(dev):
+    J, n = 2048, 16
+    M = workloads.mixture_magnitudes(J, seed=5, device=dev)
+    grads = [workloads.draw_mixture(M, w, seed=5) for w in range(n)]
+    truth = A.true_sum(grads)
+    rs, _ = A.simulated_allreduce(grads, 5.0, all_gather=False, seed=2)
+    ar, _ = A.simulated_allreduce(grads, 5.0, all_gather=True, seed=2)
+    assert A.vnmse(rs, truth) < A.vnmse(ar, truth) < 0.5      # one more quantization
+
+
+def test_rounds_draw_fresh_randomness_and_average_out(dev):
+    """Unbiasedness at scale: averaging the estimates of R rounds shrinks the error about 1/R."""
+    J, n, R = 1024, 8, 16
+    M = workloads.mixture_magnitudes(J, seed=6, device=dev)
+    grads = [workloads.draw_mixture(M, w, seed=6) for w in range(n)]
+    truth = A.true_sum(grads)
+    acc = torch.zeros_like(truth)
+    single = []
+    for r in range(R):
+        est, _ = A.simulated_allreduce(grads, 4.0, seed=9, round=r)
+        single.append(A.vnmse(est, truth))
+        acc += est.double()
+    avg = A.vnmse(acc / R, truth)
+    mean_single = sum(single) / R
+    assert avg < 2.0 * mean_single / R, (avg, mean_single)
+    assert len({round(s, 12) for s in single}) == R           # every round differs
