@@ -102,6 +102,8 @@ dq_status check_chunk(const dq_ctx *ctx, const dq_chunk *ch, uint32_t rank) {
 
 }  // namespace
 
+dq_status dq::hip_status(hipError_t e) { return hip_ok(e) ? DQ_OK : DQ_EHIP; }
+
 extern "C" {
 
 const char *dq_status_str(dq_status s) {
@@ -208,6 +210,10 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
     return DQ_EHIP;
   }
   ctx->n_cu = (uint32_t)prop.multiProcessorCount;
+  uint32_t per_cu = 6;
+  const char *env = getenv("DQ_BLOCKS_PER_CU");  // tuning / test knob, read once per context
+  if (env && atoi(env) >= 1 && atoi(env) <= 64) per_cu = (uint32_t)atoi(env);
+  ctx->grid_blocks = ctx->n_cu * per_cu;
   P.blob = ctx->blob_dev;
   P.blob_dwords = (uint32_t)blob.size();
   P.key0 = (uint32_t)cfg->seed;
@@ -250,7 +256,7 @@ dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const dq_c
   if (!local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
   if (!aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
   dq::Job j{nullptr, local, packed_out, chunk->first_sg, {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, rank};
-  return hip_ok(dq::launch_one(dq::kCompress, dtype, true, j, ctx->params, ctx->n_cu, (hipStream_t)hip_stream))
+  return hip_ok(dq::launch_one(dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream))
              ? DQ_OK
              : DQ_EHIP;
 }
@@ -264,7 +270,7 @@ dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_d
   if (!aligned16(packed_in) || !aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
   dq::Job j{(const uint8_t *)packed_in, local, packed_out, chunk->first_sg,
             {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, rank};
-  return hip_ok(dq::launch_one(dq::kDar, dtype, true, j, ctx->params, ctx->n_cu, (hipStream_t)hip_stream)) ? DQ_OK
+  return hip_ok(dq::launch_one(dq::kDar, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream)) ? DQ_OK
                                                                                                           : DQ_EHIP;
 }
 
@@ -278,7 +284,7 @@ dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or
   if (!aligned16(packed_in) || !aligned16(out) || !aligned16(local_or_null)) return DQ_EALIGN;
   dq::Job j{(const uint8_t *)packed_in, local_or_null, out, chunk->first_sg,
             {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, 0};
-  return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->n_cu,
+  return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->grid_blocks,
                                (hipStream_t)hip_stream))
              ? DQ_OK
              : DQ_EHIP;

@@ -53,12 +53,15 @@ struct Params {
 
 enum Kind { kCompress = 0, kDar = 1, kDecompress = 2 };
 
-// kernel launchers (dq_kernels.hip); grid_x = 0 lets the launcher choose
-hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t n_cu,
+// kernel launchers (dq_kernels.hip); grid_blocks = thread blocks the GPU keeps resident at once
+hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t grid_blocks,
                       hipStream_t stream);
 hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, const Job *jobs_dev, uint32_t n_jobs,
-                        uint32_t max_tiles_per_job, uint64_t total_tiles, const Params &p, uint32_t n_cu,
+                        uint32_t max_tiles_per_job, uint64_t total_tiles, const Params &p, uint32_t grid_blocks,
                         hipStream_t stream);
+
+// DQ_OK, or DQ_EHIP after recording the error's text for dq_last_hip_error (dq_api.cpp)
+dq_status hip_status(hipError_t e);
 
 struct MxJob {
   const uint8_t *in;
@@ -79,5 +82,6 @@ struct dq_ctx {
   dq::Params params;
   uint32_t *blob_dev;
   uint32_t n_cu;
+  uint32_t grid_blocks;  // n_cu x blocks per CU (6, or the DQ_BLOCKS_PER_CU environment variable at dq_create)
   int device;
 };

@@ -627,13 +627,11 @@ uint32_t job_tiles(const Job &j) {
          (j.n_sg[2] + kWaveSGs - 1) / kWaveSGs;
 }
 
-// Grid shape: as many blocks per job as the GPU holds at once, shared between the jobs of
-// the launch (one block holds 4 waves; a wave then walks its share of the job's tiles).
-uint32_t blocks_per_job(uint32_t max_tiles, uint32_t n_jobs, uint32_t n_cu) {
-  uint32_t per_cu = 6;
-  const char *env = getenv("DQ_BLOCKS_PER_CU");  // tuning / test knob
-  if (env && atoi(env) >= 1 && atoi(env) <= 64) per_cu = (uint32_t)atoi(env);
-  uint32_t blocks = (n_cu * per_cu + n_jobs - 1) / n_jobs;
+// Grid shape: `grid_blocks` (what the GPU holds at once: CUs x blocks per CU, fixed when the
+// context is made) shared between the jobs of the launch (one block holds 4 waves; a wave
+// then walks its share of the job's tiles).
+uint32_t blocks_per_job(uint32_t max_tiles, uint32_t n_jobs, uint32_t grid_blocks) {
+  uint32_t blocks = (grid_blocks + n_jobs - 1) / n_jobs;
   const uint32_t needed = (max_tiles + kBlockWaves - 1) / kBlockWaves;
   if (blocks > needed) blocks = needed;
   return blocks < 1 ? 1 : blocks;
@@ -645,53 +643,53 @@ size_t lds_bytes(const Params &p, Kind kind) {
 }
 
 template <Kind KIND, typename LT>
-hipError_t go_one(const Job &job, Params p, uint32_t n_cu, hipStream_t s) {
+hipError_t go_one(const Job &job, Params p, uint32_t grid_blocks, hipStream_t s) {
   const uint32_t tiles = job_tiles(job);
   if (tiles == 0) return hipSuccess;
-  const uint32_t blocks = blocks_per_job(tiles, 1, n_cu);
+  const uint32_t blocks = blocks_per_job(tiles, 1, grid_blocks);
   hipLaunchKernelGGL((k_one<KIND, LT>), dim3(blocks), dim3(kBlockThreads), lds_bytes(p, KIND), s, job, p);
   return hipGetLastError();
 }
 template <Kind KIND, typename LT>
 hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, uint64_t total_tiles, Params p,
-                    uint32_t n_cu, hipStream_t s) {
+                    uint32_t grid_blocks, hipStream_t s) {
   if (n_jobs == 0 || max_tiles == 0) return hipSuccess;
   (void)total_tiles;
-  const uint32_t blocks = blocks_per_job(max_tiles, n_jobs, n_cu);
+  const uint32_t blocks = blocks_per_job(max_tiles, n_jobs, grid_blocks);
   hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), lds_bytes(p, KIND), s, jobs, p);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t n_cu,
+hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t grid_blocks,
                       hipStream_t s) {
   const bool f32 = dtype == DQ_F32;
   switch (kind) {
     case kCompress:
-      return f32 ? go_one<kCompress, float>(job, p, n_cu, s) : go_one<kCompress, uint16_t>(job, p, n_cu, s);
+      return f32 ? go_one<kCompress, float>(job, p, grid_blocks, s) : go_one<kCompress, uint16_t>(job, p, grid_blocks, s);
     case kDar:
-      return f32 ? go_one<kDar, float>(job, p, n_cu, s) : go_one<kDar, uint16_t>(job, p, n_cu, s);
+      return f32 ? go_one<kDar, float>(job, p, grid_blocks, s) : go_one<kDar, uint16_t>(job, p, grid_blocks, s);
     default:
-      if (!has_local) return go_one<kDecompress, NoLocal>(job, p, n_cu, s);
-      return f32 ? go_one<kDecompress, float>(job, p, n_cu, s) : go_one<kDecompress, uint16_t>(job, p, n_cu, s);
+      if (!has_local) return go_one<kDecompress, NoLocal>(job, p, grid_blocks, s);
+      return f32 ? go_one<kDecompress, float>(job, p, grid_blocks, s) : go_one<kDecompress, uint16_t>(job, p, grid_blocks, s);
   }
 }
 
 hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, const Job *jobs, uint32_t n_jobs,
-                        uint32_t max_tiles, uint64_t total_tiles, const Params &p, uint32_t n_cu, hipStream_t s) {
+                        uint32_t max_tiles, uint64_t total_tiles, const Params &p, uint32_t grid_blocks, hipStream_t s) {
   const bool f32 = dtype == DQ_F32;
   switch (kind) {
     case kCompress:
-      return f32 ? go_batch<kCompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s)
-                 : go_batch<kCompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
+      return f32 ? go_batch<kCompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s)
+                 : go_batch<kCompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
     case kDar:
-      return f32 ? go_batch<kDar, float>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s)
-                 : go_batch<kDar, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
+      return f32 ? go_batch<kDar, float>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s)
+                 : go_batch<kDar, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
     default:
-      if (!has_local) return go_batch<kDecompress, NoLocal>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
-      return f32 ? go_batch<kDecompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s)
-                 : go_batch<kDecompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, n_cu, s);
+      if (!has_local) return go_batch<kDecompress, NoLocal>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
+      return f32 ? go_batch<kDecompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s)
+                 : go_batch<kDecompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
   }
 }
 

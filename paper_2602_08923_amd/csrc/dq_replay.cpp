@@ -26,7 +26,8 @@ struct Launch {
   dq::Kind kind;
   dq_dtype dtype;  // dtype of `local`
   bool has_local = true;  // false: decompress without accumulation
-  std::vector<HostJob> jobs;
+  std::vector<HostJob> jobs;  // freed once the table is on the device
+  uint32_t n_jobs = 0;
   size_t table_off = 0;  // byte offset of this launch's job table in scratch
   uint32_t max_tiles = 0;
   uint64_t total_tiles = 0;
@@ -273,6 +274,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
     for (Launch &L : st.launches) {
       off = align_up(off, 256);
       L.table_off = off;
+      L.n_jobs = (uint32_t)L.jobs.size();
       off += L.jobs.size() * (mx ? sizeof(dq::MxJob) : sizeof(dq::Job));
       for (const HostJob &j : L.jobs) {
         const uint32_t tiles = (j.n_sg[0] + 3) / 4 + (j.n_sg[1] + 3) / 4 + (j.n_sg[2] + 3) / 4;
@@ -347,8 +349,9 @@ dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *
       }
       if (e != hipSuccess) {
         delete r;
-        return DQ_EHIP;
+        return dq::hip_status(e);
       }
+      std::vector<HostJob>().swap(L.jobs);
     }
   *plan_out = r;
   return DQ_OK;
@@ -376,16 +379,16 @@ dq_status dq_replay_step_info(const dq_replay *plan, uint32_t step, uint32_t *ki
 static dq_status run_step(dq_replay *plan, size_t i, hipStream_t s) {
   const bool mx = plan->codec != DQ_DYNAMIQ;
   for (const Launch &L : plan->plan.steps[i].launches) {
-    if (L.jobs.empty()) continue;
+    if (L.n_jobs == 0) continue;
     hipError_t e;
     if (mx)
       e = dq::mx_launch_batch(L.kind, plan->codec, L.dtype, L.has_local,
                               reinterpret_cast<const dq::MxJob *>(plan->scratch + L.table_off),
-                              (uint32_t)L.jobs.size(), L.max_entries, plan->ctx->n_cu, s);
+                              L.n_jobs, L.max_entries, plan->ctx->n_cu, s);
     else
       e = dq::launch_batch(L.kind, L.dtype, L.has_local, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
-                           (uint32_t)L.jobs.size(), L.max_tiles, L.total_tiles, plan->ctx->params, plan->ctx->n_cu, s);
-    if (e != hipSuccess) return DQ_EHIP;
+                           L.n_jobs, L.max_tiles, L.total_tiles, plan->ctx->params, plan->ctx->grid_blocks, s);
+    if (e != hipSuccess) return dq::hip_status(e);
   }
   return DQ_OK;
 }
@@ -403,25 +406,22 @@ dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream) {
   if (!plan) return DQ_EINVAL;
   hipStream_t s = (hipStream_t)hip_stream;
   const size_t ns = plan->plan.steps.size();
-  if (step_ms && plan->events.size() < ns + 1) {
-    while (plan->events.size() < ns + 1) {
-      hipEvent_t e;
-      if (hipEventCreate(&e) != hipSuccess) return DQ_EHIP;
-      plan->events.push_back(e);
-    }
+  hipError_t he = hipSuccess;
+  while (step_ms && he == hipSuccess && plan->events.size() < ns + 1) {
+    hipEvent_t e;
+    he = hipEventCreate(&e);
+    if (he == hipSuccess) plan->events.push_back(e);
   }
-  if (step_ms && hipEventRecord(plan->events[0], s) != hipSuccess) return DQ_EHIP;
-  for (size_t i = 0; i < ns; ++i) {
+  if (step_ms && he == hipSuccess) he = hipEventRecord(plan->events[0], s);
+  for (size_t i = 0; i < ns && he == hipSuccess; ++i) {
     const dq_status st = run_step(plan, i, s);
     if (st != DQ_OK) return st;
-    if (step_ms && hipEventRecord(plan->events[i + 1], s) != hipSuccess) return DQ_EHIP;
+    if (step_ms) he = hipEventRecord(plan->events[i + 1], s);
   }
-  if (step_ms) {
-    if (hipEventSynchronize(plan->events[ns]) != hipSuccess) return DQ_EHIP;
-    for (size_t i = 0; i < ns; ++i)
-      if (hipEventElapsedTime(&step_ms[i], plan->events[i], plan->events[i + 1]) != hipSuccess) return DQ_EHIP;
-  }
-  return DQ_OK;
+  if (step_ms && he == hipSuccess) he = hipEventSynchronize(plan->events[ns]);
+  for (size_t i = 0; step_ms && i < ns && he == hipSuccess; ++i)
+    he = hipEventElapsedTime(&step_ms[i], plan->events[i], plan->events[i + 1]);
+  return dq::hip_status(he);
 }
 
 void dq_replay_destroy(dq_replay *plan) {

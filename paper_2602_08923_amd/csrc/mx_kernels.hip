@@ -326,9 +326,7 @@ dq_status dq_mx_compress(dq_codec fmt, const void *local, dq_dtype dtype, uint64
     return DQ_EINVAL;
   if (!al16(local) || !al16(packed_out)) return DQ_EALIGN;
   dq::MxJob j{nullptr, local, packed_out, n_entries};
-  return dq::mx_launch_one(dq::kCompress, fmt, dtype, true, j, device_cus(), (hipStream_t)hip_stream) == hipSuccess
-             ? DQ_OK
-             : DQ_EHIP;
+  return dq::hip_status(dq::mx_launch_one(dq::kCompress, fmt, dtype, true, j, device_cus(), (hipStream_t)hip_stream));
 }
 
 dq_status dq_mx_dar_hop(dq_codec fmt, const void *packed_in, const void *local, dq_dtype dtype, uint64_t n_entries,
@@ -338,9 +336,7 @@ dq_status dq_mx_dar_hop(dq_codec fmt, const void *packed_in, const void *local, 
     return DQ_EINVAL;
   if (!al16(packed_in) || !al16(local) || !al16(packed_out)) return DQ_EALIGN;
   dq::MxJob j{(const uint8_t *)packed_in, local, packed_out, n_entries};
-  return dq::mx_launch_one(dq::kDar, fmt, dtype, true, j, device_cus(), (hipStream_t)hip_stream) == hipSuccess
-             ? DQ_OK
-             : DQ_EHIP;
+  return dq::hip_status(dq::mx_launch_one(dq::kDar, fmt, dtype, true, j, device_cus(), (hipStream_t)hip_stream));
 }
 
 dq_status dq_mx_decompress(dq_codec fmt, const void *packed_in, const void *local_or_null, dq_dtype dtype,
@@ -349,10 +345,8 @@ dq_status dq_mx_decompress(dq_codec fmt, const void *packed_in, const void *loca
   if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
   if (!al16(packed_in) || !al16(out) || !al16(local_or_null)) return DQ_EALIGN;
   dq::MxJob j{(const uint8_t *)packed_in, local_or_null, out, n_entries};
-  return dq::mx_launch_one(dq::kDecompress, fmt, dtype, local_or_null != nullptr, j, device_cus(),
-                           (hipStream_t)hip_stream) == hipSuccess
-             ? DQ_OK
-             : DQ_EHIP;
+  return dq::hip_status(dq::mx_launch_one(dq::kDecompress, fmt, dtype, local_or_null != nullptr, j, device_cus(),
+                           (hipStream_t)hip_stream));
 }
 
 }  // extern "C"

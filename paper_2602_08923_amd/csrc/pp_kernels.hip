@@ -7,7 +7,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "dq.h"
+#include "dq_device.h"
 
 namespace {
 
@@ -537,7 +537,7 @@ uint32_t stream_blocks(uint64_t units_per_block_round, uint64_t units, uint32_t 
   return (uint32_t)(need < 1 ? 1 : (need < cap ? need : cap));
 }
 
-dq_status launched() { return hipGetLastError() == hipSuccess ? DQ_OK : DQ_EHIP; }
+dq_status launched() { return dq::hip_status(hipGetLastError()); }
 
 }  // namespace
 
