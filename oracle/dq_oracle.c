@@ -269,29 +269,34 @@ void dqo_decode_sg_core(const dqo_ctx *c, int wi, const uint8_t code[DQO_SG], co
 /* ---------------------------------------------------------------- wire format */
 
 /* A chunk is a run of super-groups with global indices first_sg, first_sg+1, ...;
- * the first n_sg[0] use 2 bits, the next n_sg[1] 4 bits, the last n_sg[2] 8 bits
- * (super-groups are reordered by increasing width, Section 3.5).  Packed buffer,
+ * the first n_sg[0] use 2 bits, the next n_sg[1] 4 bits, then n_sg[2] at 8 bits and
+ * the last n_sg[3] at 16 bits (super-groups are reordered by increasing width,
+ * Section 3.5; "16 bits corresponds to uncompressed values", Section 3.2: such a
+ * super-group travels as 256 raw bf16 numbers, without scales).  Packed buffer,
  * structure of arrays, every array 16-byte aligned, each in super-group order:
  *   [2-bit codes: 64 B per SG][4-bit codes: 128 B per SG][8-bit codes: 256 B per SG]
- *   [group scales: 16 u8 per SG][super-group scales: one u16 (bf16 pattern) per SG]
- * Entry k of a super-group sits at bit offset k*b of its code block, little-endian.
+ *   [16-bit values: 512 B per SG]
+ *   [group scales: 16 u8 per coded SG][super-group scales: one u16 (bf16 pattern) per coded SG]
+ * where the coded super-groups are those at 2, 4 and 8 bits.  Entry k of a coded
+ * super-group sits at bit offset k*b of its code block, little-endian.
  * The total is rounded up to a multiple of 16. */
 typedef struct {
   uint64_t first_sg;
-  uint32_t n_sg[3];
+  uint32_t n_sg[4];
 } dqo_chunk;
 
-static uint64_t chunk_total_sg(const dqo_chunk *ch) { return (uint64_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2]; }
-static const uint64_t DQO_CODE_BYTES[3] = {64, 128, 256};
+static uint64_t chunk_coded_sg(const dqo_chunk *ch) { return (uint64_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2]; }
+static uint64_t chunk_total_sg(const dqo_chunk *ch) { return chunk_coded_sg(ch) + ch->n_sg[3]; }
+static const uint64_t DQO_CODE_BYTES[4] = {64, 128, 256, 512};
 
 uint64_t dqo_packed_bytes(const dqo_chunk *ch) {
-  uint64_t n = chunk_total_sg(ch);
-  uint64_t sz = 64ull * ch->n_sg[0] + 128ull * ch->n_sg[1] + 256ull * ch->n_sg[2] + 16ull * n + 2ull * n;
+  uint64_t n = chunk_coded_sg(ch);
+  uint64_t sz = 64ull * ch->n_sg[0] + 128ull * ch->n_sg[1] + 256ull * ch->n_sg[2] + 512ull * ch->n_sg[3] + 16ull * n + 2ull * n;
   return (sz + 15ull) & ~15ull;
 }
 
 typedef struct {
-  uint8_t *codes[3];
+  uint8_t *codes[4];
   uint8_t *gscale;
   uint8_t *sgscale;
 } dqo_view;
@@ -302,9 +307,18 @@ static dqo_view chunk_view(const dqo_chunk *ch, void *packed) {
   v.codes[0] = p;
   v.codes[1] = v.codes[0] + 64ull * ch->n_sg[0];
   v.codes[2] = v.codes[1] + 128ull * ch->n_sg[1];
-  v.gscale = v.codes[2] + 256ull * ch->n_sg[2];
-  v.sgscale = v.gscale + 16ull * chunk_total_sg(ch);
+  v.codes[3] = v.codes[2] + 256ull * ch->n_sg[2];
+  v.gscale = v.codes[3] + 512ull * ch->n_sg[3];
+  v.sgscale = v.gscale + 16ull * chunk_coded_sg(ch);
   return v;
+}
+
+/* fp32 -> bf16, round to nearest, ties to even (finite values) */
+static uint16_t f32_to_bf16_rne(float f) {
+  uint32_t b = f32_to_bits(f);
+  uint32_t keep = b >> 16, rest = b & 0xFFFFu;
+  if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u))) keep += 1;
+  return (uint16_t)keep;
 }
 
 static void pack_codes(int b, const uint8_t code[DQO_SG], uint8_t *dst) {
@@ -332,8 +346,10 @@ static int sg_width(const dqo_chunk *ch, uint64_t j, uint64_t *pos) {
   if (j < ch->n_sg[0]) { *pos = j; return 0; }
   j -= ch->n_sg[0];
   if (j < ch->n_sg[1]) { *pos = j; return 1; }
-  *pos = j - ch->n_sg[1];
-  return 2;
+  j -= ch->n_sg[1];
+  if (j < ch->n_sg[2]) { *pos = j; return 2; }
+  *pos = j - ch->n_sg[2];
+  return 3;
 }
 
 /* ---------------------------------------------------------------- the three kernels */
@@ -352,6 +368,11 @@ void dqo_compress(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const vo
     uint16_t sf;
     uint32_t slot;
     for (int k = 0; k < DQO_SG; ++k) v[k] = local_at(local, dtype, j * DQO_SG + k);
+    if (wi == 3) { /* uncompressed: the values themselves, as bf16 */
+      uint16_t *raw = (uint16_t *)(o.codes[3] + pos * 512);
+      for (int k = 0; k < DQO_SG; ++k) raw[k] = f32_to_bf16_rne(v[k]);
+      continue;
+    }
     dqo_draw_sg(c, ch->first_sg + j, rank, gamma, sb, &slot);
     dqo_encode_sg_core(c, wi, v, gamma, sb, slot, code, rG, &sf);
     pack_codes(DQO_BITS[wi], code, o.codes[wi] + pos * DQO_CODE_BYTES[wi]);
@@ -377,6 +398,12 @@ void dqo_dar_hop(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const voi
     uint16_t sf;
     uint32_t slot;
     for (int k = 0; k < DQO_SG; ++k) loc[k] = local_at(local, dtype, j * DQO_SG + k);
+    if (wi == 3) { /* uncompressed: bf16 partial sum + local in fp32, rounded back to bf16 */
+      const uint16_t *raw_in = (const uint16_t *)(in.codes[3] + pos * 512);
+      uint16_t *raw = (uint16_t *)(o.codes[3] + pos * 512);
+      for (int k = 0; k < DQO_SG; ++k) raw[k] = f32_to_bf16_rne(bf16_to_f32(raw_in[k]) + loc[k]);
+      continue;
+    }
     unpack_codes(DQO_BITS[wi], in.codes[wi] + pos * DQO_CODE_BYTES[wi], code);
     memcpy(rG, in.gscale + 16 * j, 16);
     memcpy(&sf, in.sgscale + 2 * j, 2);
@@ -406,6 +433,12 @@ void dqo_decompress(const dqo_ctx *c, const dqo_chunk *ch, const void *packed_in
     uint16_t sf;
     if (local_or_null)
       for (int k = 0; k < DQO_SG; ++k) loc[k] = local_at(local_or_null, dtype, j * DQO_SG + k);
+    if (wi == 3) {
+      const uint16_t *raw_in = (const uint16_t *)(in.codes[3] + pos * 512);
+      for (int k = 0; k < DQO_SG; ++k)
+        out[j * DQO_SG + k] = local_or_null ? bf16_to_f32(raw_in[k]) + loc[k] : bf16_to_f32(raw_in[k]);
+      continue;
+    }
     unpack_codes(DQO_BITS[wi], in.codes[wi] + pos * DQO_CODE_BYTES[wi], code);
     memcpy(rG, in.gscale + 16 * j, 16);
     memcpy(&sf, in.sgscale + 2 * j, 2);

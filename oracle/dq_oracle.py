@@ -39,7 +39,7 @@ class Config(C.Structure):
 
 
 class Chunk(C.Structure):
-    _fields_ = [("first_sg", C.c_uint64), ("n_sg", C.c_uint32 * 3)]
+    _fields_ = [("first_sg", C.c_uint64), ("n_sg", C.c_uint32 * 4)]  # 2, 4, 8, 16 bits
 
 
 _lib = None
@@ -112,7 +112,7 @@ def _dtype_code(a):
 def make_chunk(first_sg, n_sg):
     ch = Chunk()
     ch.first_sg = int(first_sg)
-    for i in range(3):
+    for i in range(len(n_sg)):      # 2, 4, 8 bits and optionally 16
         ch.n_sg[i] = int(n_sg[i])
     return ch
 
@@ -184,7 +184,7 @@ class Oracle:
         return out
 
     def decompress(self, chunk, packed_in, local=None):
-        n = (chunk.n_sg[0] + chunk.n_sg[1] + chunk.n_sg[2]) * 256
+        n = sum(chunk.n_sg) * 256
         out = np.empty(n, np.float32)
         lib().dqo_decompress(self.h, C.byref(chunk), _p(packed_in), None if local is None else _p(local),
                              0 if local is None else _dtype_code(local), _p(out))
@@ -219,16 +219,19 @@ def bf16_ceil(x):
 # ------------------------------------------------------------------ chunking
 
 def split_bucket(n_sg_by_width, n_chunks, first_sg=0):
-    """Cut a reordered bucket (all 2-bit super-groups, then 4-bit, then 8-bit;
-    Section 3.5) into n_chunks chunks of equal super-group count."""
-    total = sum(n_sg_by_width)
+    """Cut a reordered bucket (all 2-bit super-groups, then 4-bit, 8-bit and, if a fourth
+    count is given, 16-bit; Section 3.5) into n_chunks chunks of equal super-group count."""
+    counts = list(n_sg_by_width) + [0] * (4 - len(n_sg_by_width))
+    total = sum(counts)
     assert total % n_chunks == 0, "bucket must be padded to a multiple of the worker count"
     m = total // n_chunks
-    edges = [0, n_sg_by_width[0], n_sg_by_width[0] + n_sg_by_width[1], total]
+    edges = [0]
+    for c in counts:
+        edges.append(edges[-1] + c)
     out = []
     for i in range(n_chunks):
         lo, hi = i * m, (i + 1) * m
-        n_sg = [max(0, min(hi, edges[w + 1]) - max(lo, edges[w])) for w in range(3)]
+        n_sg = [max(0, min(hi, edges[w + 1]) - max(lo, edges[w])) for w in range(4)]
         out.append(make_chunk(first_sg + lo, n_sg))
     return out
 

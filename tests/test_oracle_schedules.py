@@ -29,7 +29,9 @@ def vnmse(out, gs):
 def test_split_bucket_covers_every_super_group_once():
     chunks = O.split_bucket([5, 9, 2], 4, first_sg=100)
     assert [c.first_sg for c in chunks] == [100, 104, 108, 112]
-    assert [list(c.n_sg) for c in chunks] == [[4, 0, 0], [1, 3, 0], [0, 4, 0], [0, 2, 2]]
+    assert [list(c.n_sg) for c in chunks] == [[4, 0, 0, 0], [1, 3, 0, 0], [0, 4, 0, 0], [0, 2, 2, 0]]
+    chunks = O.split_bucket([2, 1, 2, 3], 4)                      # with a run of 16-bit super-groups
+    assert [list(c.n_sg) for c in chunks] == [[2, 0, 0, 0], [0, 1, 1, 0], [0, 0, 1, 1], [0, 0, 0, 2]]
     with pytest.raises(AssertionError):
         O.split_bucket([5, 9, 1], 4)
 
@@ -162,3 +164,50 @@ def test_all_gather_keeps_lattice_values_and_estimates_the_rest():
         g = np.abs(rough[c]).reshape(16, 16).max(axis=1)
         bound = np.repeat(g, 16) * (float(T[7] - T[6]) + 1.0 / 255 + 2.0 ** -7)
         assert np.all(np.abs(out[c] - rough[c]) <= bound)
+
+
+# ----------------------------------------------------------------- 16-bit (uncompressed) super-groups
+
+def test_sixteen_bit_super_groups_travel_as_bf16():
+    """Section 3.2: "16 bits corresponds to uncompressed values".  Such a super-group is 256 raw
+    bf16 numbers: no scales, no randomness; every hop adds in fp32 and rounds to bf16."""
+    import torch
+    n = 4
+    orc = O.Oracle(n, seed=1)
+    rng = np.random.default_rng(5)
+    ch = O.make_chunk(7, [1, 2, 1, 3])
+    assert O.Oracle.packed_bytes(ch) == 64 + 2 * 128 + 256 + 3 * 512 + 4 * 18 + 8     # scales for the 4 coded SGs, padded to 16
+    x = (rng.standard_normal(7 * 256) * 1e-2).astype(np.float32)
+    y = (rng.standard_normal(7 * 256) * 1e-2).astype(np.float32)
+    msg = orc.compress(ch, 0, x)
+    raw = msg[64 + 256 + 256:64 + 256 + 256 + 3 * 512].view(np.uint16)
+    want = torch.from_numpy(x[4 * 256:]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(raw, want)                                   # the values themselves, rounded to nearest even
+    # independent of rank and seed: nothing random in it
+    other = O.Oracle(n, seed=99).compress(ch, 3, x)
+    assert np.array_equal(other[64 + 512:64 + 512 + 3 * 512], msg[64 + 512:64 + 512 + 3 * 512])
+    # one hop: bf16(widen(in) + local), by torch's arithmetic
+    msg2 = orc.dar_hop(ch, 1, msg, y)
+    s = torch.from_numpy(want.view(np.int16)).view(torch.bfloat16).float() + torch.from_numpy(y[4 * 256:])
+    assert np.array_equal(msg2[64 + 512:64 + 512 + 3 * 512].view(np.uint16),
+                          s.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    out = orc.decompress(ch, msg2, x)
+    assert np.array_equal(out[4 * 256:], (s.to(torch.bfloat16).float() + torch.from_numpy(x[4 * 256:])).numpy())
+    plain = orc.decompress(ch, msg2)
+    assert np.array_equal(plain[4 * 256:], s.to(torch.bfloat16).float().numpy())
+    # the coded super-groups in front are what they would be without the 16-bit run
+    ch3 = O.make_chunk(7, [1, 2, 1])
+    assert np.array_equal(orc.compress(ch3, 0, x[:4 * 256])[:64 + 256 + 256], msg[:64 + 256 + 256])
+    assert np.array_equal(orc.decompress(ch3, orc.compress(ch3, 0, x[:4 * 256])), orc.decompress(ch, msg)[:4 * 256])
+
+
+def test_ring_with_sixteen_bit_run_is_exact_on_bf16_friendly_values():
+    n = 4
+    orc = O.Oracle(n, seed=2)
+    rng = np.random.default_rng(6)
+    counts = [0, 0, 0, 8]                                            # everything uncompressed
+    gs = [(rng.integers(-8, 8, 8 * 256) * 2.0 ** -4).astype(np.float32) for _ in range(n)]   # sums stay exact in bf16
+    out = np.concatenate(O.ring_reduce_scatter(orc, gs, counts))
+    assert np.array_equal(out, sum(gs))
+    out = np.concatenate(O.butterfly_reduce_scatter(orc, gs, counts))
+    assert np.array_equal(out, sum(gs))
