@@ -23,7 +23,10 @@
  * a code width of 2, 4 or 8 bits.  A chunk is a run of SGs already reordered by increasing
  * width.  Packed chunk layout (structure of arrays, each array 16-byte aligned, SG order):
  *   [2-bit codes, 64 B per SG][4-bit codes, 128 B per SG][8-bit codes, 256 B per SG]
- *   [group scales, 16 u8 per SG][SG scales, one u16 bf16 pattern per SG], rounded up to 16 B.
+ *   [16-bit values, 512 B per SG: raw bf16, "16 bits corresponds to uncompressed values", Section 3.2]
+ *   [group scales, 16 u8 per coded SG][SG scales, one u16 bf16 pattern per coded SG], rounded up
+ *   to 16 B; the coded SGs are those at 2, 4 and 8 bits.  A 16-bit SG has no scales and uses no
+ *   random numbers: compress rounds to bf16 (nearest even), a DAR hop adds in fp32 and rounds back.
  * Entry k of an SG sits at bit offset k*b of the SG's code block (little-endian);
  * code = sign << (b-1) | level index.
  */
@@ -55,7 +58,7 @@ typedef struct {
 
 typedef struct {
   uint64_t first_sg; /* global (post-reorder) index of the chunk's first SG; keys the PRNG */
-  uint32_t n_sg[3];  /* SGs at 2, 4, 8 bits, in this order */
+  uint32_t n_sg[4];  /* SGs at 2, 4, 8 and 16 bits, in this order (16 bits: raw bf16 values) */
 } dq_chunk;
 
 /* Build the level tables f(eps, r) of Section 3.3 and upload them.  DQ_EINVAL for a null
@@ -104,7 +107,7 @@ dq_status dq_mx_decompress(dq_codec fmt, const void *packed_in, const void *loca
  * hand-off.  One kernel launch per schedule step covers every (worker, chunk) job of that
  * step.  DQ_RING / DQ_BUTTERFLY: worker_grads[w] holds worker w's n_buckets buckets back to
  * back, each n_sg_bucket SGs (a multiple of n_workers; butterfly needs a power of two);
- * bucket b uses widths n_sg_by_width[3*b..3*b+2] and global SG indices starting at
+ * bucket b uses widths n_sg_by_width[4*b..4*b+3] and global SG indices starting at
  * first_sg + b*n_sg_bucket; `out` receives the reduced buckets (the SUM over workers, fp32,
  * same order as the inputs).  DQ_CHAIN: the path of one ring chunk: worker_grads[i] is
  * worker i's slice of that chunk (n_buckets = 1, n_sg_bucket = the chunk's SG count); worker
@@ -122,7 +125,7 @@ typedef struct {
   dq_dtype dtype;
   uint32_t n_buckets;
   uint64_t n_sg_bucket;
-  const uint32_t *n_sg_by_width; /* host, [n_buckets][3] */
+  const uint32_t *n_sg_by_width; /* host, [n_buckets][4]: SGs at 2, 4, 8, 16 bits per bucket */
   uint64_t first_sg;
   uint32_t all_gather; /* 0: reduce-scatter only; 1: append the all-gather phase (see below) */
 } dq_replay_desc;

@@ -37,7 +37,7 @@ class Config(C.Structure):
 
 
 class Chunk(C.Structure):
-    _fields_ = [("first_sg", C.c_uint64), ("n_sg", C.c_uint32 * 3)]
+    _fields_ = [("first_sg", C.c_uint64), ("n_sg", C.c_uint32 * 4)]
 
 
 class ReplayDesc(C.Structure):
@@ -126,7 +126,7 @@ def _dtype(t):
 def make_chunk(first_sg, n_sg):
     ch = Chunk()
     ch.first_sg = int(first_sg)
-    for k in range(3):
+    for k in range(len(n_sg)):      # 2, 4, 8 bits and optionally 16
         ch.n_sg[k] = int(n_sg[k])
     return ch
 
@@ -136,7 +136,7 @@ def dq_packed_bytes(chunk):
 
 
 def _entries(chunk):
-    return (chunk.n_sg[0] + chunk.n_sg[1] + chunk.n_sg[2]) * 256
+    return sum(chunk.n_sg) * 256
 
 
 class Context:
@@ -236,11 +236,11 @@ class Replay:
         self.grads = list(worker_grads)
         dev = self.grads[0].device
         n = len(self.grads)
-        flat = (C.c_uint32 * (3 * n_buckets))()
+        flat = (C.c_uint32 * (4 * n_buckets))()
         if n_sg_by_width is not None:
             for b in range(n_buckets):
-                for k in range(3):
-                    flat[3 * b + k] = int(n_sg_by_width[b][k])
+                for k in range(len(n_sg_by_width[b])):      # 2, 4, 8 bits and optionally 16
+                    flat[4 * b + k] = int(n_sg_by_width[b][k])
         self._widths = flat
         desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg,
                           1 if all_gather else 0)

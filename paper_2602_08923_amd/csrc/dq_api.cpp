@@ -89,7 +89,7 @@ void append_aligned(std::vector<uint32_t> &blob, const std::vector<uint32_t> &pa
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-uint64_t chunk_sgs(const dq_chunk *ch) { return (uint64_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2]; }
+uint64_t chunk_sgs(const dq_chunk *ch) { return (uint64_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2] + ch->n_sg[3]; }
 
 dq_status check_chunk(const dq_ctx *ctx, const dq_chunk *ch, uint32_t rank) {
   if (!ctx || !ch) return DQ_EINVAL;
@@ -243,8 +243,9 @@ dq_status dq_set_round(dq_ctx *ctx, uint32_t round) {
 
 size_t dq_packed_bytes(const dq_chunk *ch) {
   if (!ch) return 0;
-  const size_t n = (size_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2];
-  const size_t sz = 64 * (size_t)ch->n_sg[0] + 128 * (size_t)ch->n_sg[1] + 256 * (size_t)ch->n_sg[2] + 18 * n;
+  const size_t n = (size_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2];  // coded super-groups carry scales
+  const size_t sz = 64 * (size_t)ch->n_sg[0] + 128 * (size_t)ch->n_sg[1] + 256 * (size_t)ch->n_sg[2] +
+                    512 * (size_t)ch->n_sg[3] + 18 * n;
   return (sz + 15) & ~(size_t)15;
 }
 
@@ -255,7 +256,7 @@ dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const dq_c
   if (chunk_sgs(chunk) == 0) return DQ_OK;  // nothing to do
   if (!local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
   if (!aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
-  dq::Job j{nullptr, local, packed_out, chunk->first_sg, {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, rank};
+  dq::Job j{nullptr, local, packed_out, chunk->first_sg, {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, rank};
   return hip_ok(dq::launch_one(dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream))
              ? DQ_OK
              : DQ_EHIP;
@@ -269,7 +270,7 @@ dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_d
   if (!packed_in || !local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
   if (!aligned16(packed_in) || !aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
   dq::Job j{(const uint8_t *)packed_in, local, packed_out, chunk->first_sg,
-            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, rank};
+            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, rank};
   return hip_ok(dq::launch_one(dq::kDar, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream)) ? DQ_OK
                                                                                                           : DQ_EHIP;
 }
@@ -283,7 +284,7 @@ dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or
   if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
   if (!aligned16(packed_in) || !aligned16(out) || !aligned16(local_or_null)) return DQ_EALIGN;
   dq::Job j{(const uint8_t *)packed_in, local_or_null, out, chunk->first_sg,
-            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2]}, 0};
+            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, 0};
   return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->grid_blocks,
                                (hipStream_t)hip_stream))
              ? DQ_OK

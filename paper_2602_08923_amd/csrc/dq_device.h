@@ -21,7 +21,7 @@ struct Job {
   const void *local;   // local slice, may be nullptr for decompress
   void *out;           // packed (compress, DAR) or fp32 (decompress)
   uint64_t first_sg;   // global index of the chunk's first super-group
-  uint32_t n_sg[3];    // super-groups at 2, 4, 8 bits
+  uint32_t n_sg[4];    // super-groups at 2, 4, 8 and 16 bits
   uint32_t rank;       // worker doing the compression (feeds the random streams)
 };
 

@@ -153,11 +153,13 @@ struct TilePos {
   int wi;
 };
 __device__ __forceinline__ TilePos locate(const Job &job, uint32_t t) {
-  const uint32_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2];
-  const uint32_t t0 = (n0 + kWaveSGs - 1) / kWaveSGs, t1 = (n1 + kWaveSGs - 1) / kWaveSGs;
+  const uint32_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2], n3 = job.n_sg[3];
+  const uint32_t t0 = (n0 + kWaveSGs - 1) / kWaveSGs, t1 = (n1 + kWaveSGs - 1) / kWaveSGs,
+                 t2 = (n2 + kWaveSGs - 1) / kWaveSGs;
   if (t < t0) return TilePos{0, n0, t * kWaveSGs, 0};
   if (t < t0 + t1) return TilePos{n0, n1, (t - t0) * kWaveSGs, 1};
-  return TilePos{n0 + n1, n2, (t - t0 - t1) * kWaveSGs, 2};
+  if (t < t0 + t1 + t2) return TilePos{n0 + n1, n2, (t - t0 - t1) * kWaveSGs, 2};
+  return TilePos{n0 + n1 + n2, n3, (t - t0 - t1 - t2) * kWaveSGs, 3};
 }
 
 // Wave-uniform addresses of a tile: 64-bit bases once per tile (scalar registers), so that
@@ -169,10 +171,11 @@ struct TileBase {
   uint32_t last_row;                // rows 0..last_row hold a super-group
   uint64_t G0;                      // global index of the tile's first super-group
   __device__ __forceinline__ TileBase(const Job &job, const TilePos pos) {
-    const size_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2];
-    const size_t gs0 = 64 * n0 + 128 * n1 + 256 * n2;
+    const size_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2], n3 = job.n_sg[3];
+    const size_t c16 = 64 * n0 + 128 * n1 + 256 * n2;  // the raw 16-bit values follow the codes
+    const size_t gs0 = c16 + 512 * n3;                  // then the scales of the coded SGs (2, 4, 8 bits)
     const size_t sg0 = (size_t)pos.seg_first + pos.tile_first;  // position in the chunk
-    code_off = (B == 2 ? 0 : (B == 4 ? 64 * n0 : 64 * n0 + 128 * n1)) + (size_t)pos.tile_first * (32 * B);
+    code_off = (B == 2 ? 0 : (B == 4 ? 64 * n0 : (B == 8 ? 64 * n0 + 128 * n1 : c16))) + (size_t)pos.tile_first * (32 * B);
     gs_off = gs0 + sg0 * 16;
     sf_off = gs0 + 16 * (n0 + n1 + n2) + sg0 * 2;
     first_entry = sg0 * kSG;
@@ -396,6 +399,29 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   }
 }
 
+// A wave tile's 4 KB of fp32 results, v[16] per lane (lane = group), written through the wave's
+// LDS area so that every store instruction covers 1 KB of contiguous memory: lane l parks its 4
+// float4 at slots 4l..4l+3 (slot index xor-ed with bits 2-3 of l so that the 16 lanes of a pass hit
+// different banks); store round r then reads slot r*64 + lane = float4 number r*64 + lane of the tile.
+__device__ __forceinline__ void store_tile_f32(const float (&v)[16], uint32_t xpose, float *outp, uint32_t last_row) {
+  const uint32_t lane = threadIdx.x & 63u;
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (uint32_t i = 0; i < 4; ++i)
+    lds_stf4(xpose + lane * 64 + ((i ^ ((lane >> 2) & 3u)) * 16), f32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]});
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+  for (uint32_t r = 0; r < (uint32_t)kWaveSGs; ++r) {
+    if (r > last_row) break;
+    const uint32_t slot = r * 64 + lane, w = slot >> 2, c = slot & 3u;
+    const f32x4 o = lds_ldf4(xpose + w * 64 + ((c ^ ((w >> 2) & 3u)) * 16));
+    gst<f32x4>(reinterpret_cast<float4 *>(outp) + slot, o);
+  }
+  __builtin_amdgcn_wave_barrier();
+}
+
 // One wave tile of decompress(+accumulate).  Lanes fetch and decode like the DAR tile (a lane
 // owns a group of 16 entries, few wide loads), then the 4 KB of fp32 results are transposed
 // through a per-wave LDS area so that every store instruction writes 1 KB of contiguous memory.
@@ -469,25 +495,75 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
       else v[per * j + k] = t[k] * sfg;
     }
   }
-  // transpose: lane l parks its 4 float4 at slots 4l..4l+3 (chunk index xor-ed with bits 2-3 of
-  // l so that the 16 lanes of a pass hit different banks); store round r then reads slot
-  // r*64 + lane, which is float4 number r*64 + lane of the tile
-  __builtin_amdgcn_wave_barrier();
+  store_tile_f32(v, xpose, static_cast<float *>(job.out) + tb.first_entry, tb.last_row);
+}
+
+// One wave tile of uncompressed (16-bit) super-groups: the packed values are raw bf16
+// ("16 bits corresponds to uncompressed values", Section 3.2).  Compress rounds the local entries
+// to bf16 (nearest even); a DAR hop adds the local entry to the widened incoming value in fp32
+// and rounds the sum back; decompress widens (and adds).  No scales, no random numbers.
+__device__ __forceinline__ uint32_t bf16_rne_pair(float lo, float hi) {
+  const uint32_t a = f2u(lo), b = f2u(hi);
+  const uint32_t ra = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
+  const uint32_t rb = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+  return ra | rb;
+}
+
+template <Kind KIND, typename LT>
+__device__ __forceinline__ void tile16(const Job &job, uint32_t xpose, const TilePos pos) {
+  constexpr bool kHasLocal = !__is_same(LT, NoLocal);
+  const TileBase<16> tb(job, pos);
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t row = lane >> 4;
+  const uint32_t rowc = min(row, tb.last_row);
+  const uint32_t lg = rowc * 16 + (lane & 15u);
+  float v[16];
 #pragma unroll
-  for (uint32_t i = 0; i < 4; ++i)
-    lds_stf4(xpose + lane * 64 + ((i ^ ((lane >> 2) & 3u)) * 16), f32x4{v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]});
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  float *outp = static_cast<float *>(job.out) + tb.first_entry;
+  for (int k = 0; k < 16; ++k) v[k] = 0.0f;
+  if constexpr (kHasLocal) {
+    if constexpr (sizeof(LT) == 4) {
+      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
 #pragma unroll
-  for (uint32_t r = 0; r < (uint32_t)kWaveSGs; ++r) {
-    if (r > tb.last_row) break;
-    const uint32_t slot = r * 64 + lane, w = slot >> 2, c = slot & 3u;
-    const f32x4 o = lds_ldf4(xpose + w * 64 + ((c ^ ((w >> 2) & 3u)) * 16));
-    gst<f32x4>(reinterpret_cast<float4 *>(outp) + slot, o);
+      for (int i = 0; i < 4; ++i) {
+        const uint4 x = gld16(p + i);
+        v[4 * i] = u2f(x.x); v[4 * i + 1] = u2f(x.y); v[4 * i + 2] = u2f(x.z); v[4 * i + 3] = u2f(x.w);
+      }
+    } else {
+      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const uint4 x = gld16(p + i);
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[8 * i + 2 * j] = u2f(w[j] << 16);
+          v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
+        }
+      }
+    }
   }
-  __builtin_amdgcn_wave_barrier();
+  if constexpr (KIND != kCompress) {
+    const uint4 *p = reinterpret_cast<const uint4 *>(job.in + tb.code_off) + lg * 2;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint4 x = gld16(p + i);
+      const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[8 * i + 2 * j] = u2f(w[j] << 16) + v[8 * i + 2 * j];
+        v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u) + v[8 * i + 2 * j + 1];
+      }
+    }
+  }
+  if constexpr (KIND == kDecompress) {
+    store_tile_f32(v, xpose, static_cast<float *>(job.out) + tb.first_entry, tb.last_row);
+  } else if (row <= tb.last_row) {
+    uint8_t *dst = static_cast<uint8_t *>(job.out) + tb.code_off + lg * 32;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      gst<u32x4>(dst + 16 * i, u32x4{bf16_rne_pair(v[8 * i], v[8 * i + 1]), bf16_rne_pair(v[8 * i + 2], v[8 * i + 3]),
+                                     bf16_rne_pair(v[8 * i + 4], v[8 * i + 5]), bf16_rne_pair(v[8 * i + 6], v[8 * i + 7])});
+  }
 }
 
 // `len` consecutive tiles of width B starting at `pos` (their parked draws 128 bytes apart).
@@ -532,7 +608,11 @@ __device__ __forceinline__ void run_range(const Job &job, const Params &P, uint3
     const uint32_t stage = area + j * 128;
     if (p.wi == 0) run_tiles<2, KIND, LT>(job, P, lds0, stage, p, len);
     else if (p.wi == 1) run_tiles<4, KIND, LT>(job, P, lds0, stage, p, len);
-    else run_tiles<8, KIND, LT>(job, P, lds0, stage, p, len);
+    else if (p.wi == 2) run_tiles<8, KIND, LT>(job, P, lds0, stage, p, len);
+    else {
+      TilePos q = p;
+      for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<KIND, LT>(job, 0u, q);
+    }
     j += len;
   }
 }
@@ -543,8 +623,8 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   uint32_t *lds = reinterpret_cast<uint32_t *>(lds_raw);
   const uint32_t n0 = job.n_sg[0], n1 = job.n_sg[1], n2 = job.n_sg[2];
   const uint32_t t0 = (n0 + kWaveSGs - 1) / kWaveSGs, t1 = (n1 + kWaveSGs - 1) / kWaveSGs,
-                 t2 = (n2 + kWaveSGs - 1) / kWaveSGs;
-  const uint32_t total = t0 + t1 + t2;
+                 t2 = (n2 + kWaveSGs - 1) / kWaveSGs, t3 = (job.n_sg[3] + kWaveSGs - 1) / kWaveSGs;
+  const uint32_t total = t0 + t1 + t2 + t3;
   // even split of the tiles over the grid's waves in 32-bit arithmetic: wave v takes q tiles
   // from v*q + min(v, r), one more if v < r (q, r = quotient and remainder of tiles by waves)
   const uint32_t n_waves = gridDim.x * kBlockWaves;
@@ -566,7 +646,7 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
 
   // copy the common tables and the table regions of the widths this block meets; the first
   // 16 bytes per thread of every region are requested together (one round trip, not four)
-  const bool need[4] = {b_lo < t0, b_lo < t0 + t1 && b_hi > t0, b_hi > t0 + t1, true};
+  const bool need[4] = {b_lo < t0, b_lo < t0 + t1 && b_hi > t0, b_lo < t0 + t1 + t2 && b_hi > t0 + t1, true};
   uint4 first[4];
   bool has[4];
 #pragma unroll
@@ -596,7 +676,8 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
       const TilePos p = locate(job, t);
       if (p.wi == 0) tile_da<2, LT>(job, P, lds0, xpose, p);
       else if (p.wi == 1) tile_da<4, LT>(job, P, lds0, xpose, p);
-      else tile_da<8, LT>(job, P, lds0, xpose, p);
+      else if (p.wi == 2) tile_da<8, LT>(job, P, lds0, xpose, p);
+      else tile16<kDecompress, LT>(job, xpose, p);
     }
   } else if (block_draws) {
     run_range<KIND, LT>(job, P, lds0, park0 + (w_lo - b_lo) * 128, w_lo, w_hi - w_lo);
@@ -624,7 +705,7 @@ __global__ __launch_bounds__(kBlockThreads) void k_batch(const Job *jobs, Params
 
 uint32_t job_tiles(const Job &j) {
   return (j.n_sg[0] + kWaveSGs - 1) / kWaveSGs + (j.n_sg[1] + kWaveSGs - 1) / kWaveSGs +
-         (j.n_sg[2] + kWaveSGs - 1) / kWaveSGs;
+         (j.n_sg[2] + kWaveSGs - 1) / kWaveSGs + (j.n_sg[3] + kWaveSGs - 1) / kWaveSGs;
 }
 
 // Grid shape: `grid_blocks` (what the GPU holds at once: CUs x blocks per CU, fixed when the

@@ -18,7 +18,7 @@ struct HostJob {
   const void *local;
   void *out;
   uint64_t first_sg;
-  uint32_t n_sg[3];
+  uint32_t n_sg[4];
   uint32_t rank;
 };
 
@@ -48,21 +48,21 @@ struct Plan {
 
 bool is_mx(dq_codec c) { return c == DQ_MXFP8_E4M3 || c == DQ_MXFP6_E3M2 || c == DQ_MXFP4_E2M1; }
 
-size_t chunk_bytes(dq_codec codec, const uint32_t n_sg[3]) {
-  if (is_mx(codec)) return dq_mx_packed_bytes(codec, ((uint64_t)n_sg[0] + n_sg[1] + n_sg[2]) * 256);
-  dq_chunk ch{0, {n_sg[0], n_sg[1], n_sg[2]}};
+size_t chunk_bytes(dq_codec codec, const uint32_t n_sg[4]) {
+  if (is_mx(codec)) return dq_mx_packed_bytes(codec, ((uint64_t)n_sg[0] + n_sg[1] + n_sg[2] + n_sg[3]) * 256);
+  dq_chunk ch{0, {n_sg[0], n_sg[1], n_sg[2], n_sg[3]}};
   return dq_packed_bytes(&ch);
 }
 
 size_t elt_size(dq_dtype t) { return t == DQ_F32 ? 4 : 2; }
 
 // Width counts of chunk c (of n equal chunks) of a reordered bucket: 2-bit SGs first,
-// then 4-bit, then 8-bit.
-void chunk_widths(const uint32_t by_width[3], uint64_t m, uint32_t c, uint32_t out[3]) {
-  const uint64_t edges[4] = {0, by_width[0], (uint64_t)by_width[0] + by_width[1],
-                             (uint64_t)by_width[0] + by_width[1] + by_width[2]};
+// then 4-bit, 8-bit and 16-bit.
+void chunk_widths(const uint32_t by_width[4], uint64_t m, uint32_t c, uint32_t out[4]) {
+  uint64_t edges[5] = {0, 0, 0, 0, 0};
+  for (int w = 0; w < 4; ++w) edges[w + 1] = edges[w] + by_width[w];
   const uint64_t lo = (uint64_t)c * m, hi = lo + m;
-  for (int w = 0; w < 3; ++w) {
+  for (int w = 0; w < 4; ++w) {
     const uint64_t a = lo > edges[w] ? lo : edges[w], b = hi < edges[w + 1] ? hi : edges[w + 1];
     out[w] = b > a ? (uint32_t)(b - a) : 0;
   }
@@ -96,16 +96,16 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
 
   // per (bucket, chunk): widths, packed size
   struct ChunkInfo {
-    uint32_t n_sg[3];
+    uint32_t n_sg[4];
     uint64_t first_sg;
     size_t bytes;
   };
   std::vector<ChunkInfo> ci((size_t)d->n_buckets * n_chunks);
   for (uint32_t b = 0; b < d->n_buckets; ++b) {
-    uint32_t bw[3] = {(uint32_t)d->n_sg_bucket, 0, 0};
+    uint32_t bw[4] = {(uint32_t)d->n_sg_bucket, 0, 0, 0};
     if (!mx) {
-      memcpy(bw, d->n_sg_by_width + 3 * (size_t)b, sizeof(bw));
-      if ((uint64_t)bw[0] + bw[1] + bw[2] != d->n_sg_bucket) return DQ_EINVAL;
+      memcpy(bw, d->n_sg_by_width + 4 * (size_t)b, sizeof(bw));
+      if ((uint64_t)bw[0] + bw[1] + bw[2] + bw[3] != d->n_sg_bucket) return DQ_EINVAL;
     }
     for (uint32_t c = 0; c < n_chunks; ++c) {
       ChunkInfo &x = ci[(size_t)b * n_chunks + c];
@@ -122,7 +122,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
     return out + (uint64_t)b * bucket_entries + (uint64_t)c * chunk_entries;
   };
   auto mk = [&](const ChunkInfo &x, const uint8_t *in, const void *local, void *o, uint32_t rank) {
-    HostJob j{in, local, o, x.first_sg, {x.n_sg[0], x.n_sg[1], x.n_sg[2]}, rank};
+    HostJob j{in, local, o, x.first_sg, {x.n_sg[0], x.n_sg[1], x.n_sg[2], x.n_sg[3]}, rank};
     return j;
   };
 
@@ -277,8 +277,8 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
       L.n_jobs = (uint32_t)L.jobs.size();
       off += L.jobs.size() * (mx ? sizeof(dq::MxJob) : sizeof(dq::Job));
       for (const HostJob &j : L.jobs) {
-        const uint32_t tiles = (j.n_sg[0] + 3) / 4 + (j.n_sg[1] + 3) / 4 + (j.n_sg[2] + 3) / 4;
-        const uint64_t e = ((uint64_t)j.n_sg[0] + j.n_sg[1] + j.n_sg[2]) * 256;
+        const uint32_t tiles = (j.n_sg[0] + 3) / 4 + (j.n_sg[1] + 3) / 4 + (j.n_sg[2] + 3) / 4 + (j.n_sg[3] + 3) / 4;
+        const uint64_t e = ((uint64_t)j.n_sg[0] + j.n_sg[1] + j.n_sg[2] + j.n_sg[3]) * 256;
         if (tiles > L.max_tiles) L.max_tiles = tiles;
         L.total_tiles += tiles;
         if (e > L.max_entries) L.max_entries = e;
@@ -336,14 +336,14 @@ dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *
         std::vector<dq::MxJob> t(L.jobs.size());
         for (size_t i = 0; i < t.size(); ++i) {
           const HostJob &j = L.jobs[i];
-          t[i] = dq::MxJob{j.in, j.local, j.out, ((uint64_t)j.n_sg[0] + j.n_sg[1] + j.n_sg[2]) * 256};
+          t[i] = dq::MxJob{j.in, j.local, j.out, ((uint64_t)j.n_sg[0] + j.n_sg[1] + j.n_sg[2] + j.n_sg[3]) * 256};
         }
         e = hipMemcpy(r->scratch + L.table_off, t.data(), t.size() * sizeof(dq::MxJob), hipMemcpyHostToDevice);
       } else {
         std::vector<dq::Job> t(L.jobs.size());
         for (size_t i = 0; i < t.size(); ++i) {
           const HostJob &j = L.jobs[i];
-          t[i] = dq::Job{j.in, j.local, j.out, j.first_sg, {j.n_sg[0], j.n_sg[1], j.n_sg[2]}, j.rank};
+          t[i] = dq::Job{j.in, j.local, j.out, j.first_sg, {j.n_sg[0], j.n_sg[1], j.n_sg[2], j.n_sg[3]}, j.rank};
         }
         e = hipMemcpy(r->scratch + L.table_off, t.data(), t.size() * sizeof(dq::Job), hipMemcpyHostToDevice);
       }

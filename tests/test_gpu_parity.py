@@ -407,3 +407,45 @@ def test_all_gather_phase_mx_and_chain(dev):
     rc.run()
     torch.cuda.synchronize()
     assert np.array_equal(host(rc.out), want)
+
+
+# ----------------------------------------------------------------------------- 16-bit (uncompressed) super-groups
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_sg", [[3, 5, 2, 7], [0, 0, 0, 9], [1, 0, 0, 1], [0, 6, 0, 130], [5, 5, 5, 0]])
+def test_sixteen_bit_run(dev, dtype, n_sg):
+    """Chunks with a run of raw-bf16 super-groups behind the coded ones: every call against the oracle."""
+    n = 4
+    total = sum(n_sg) * 256
+    rng = np.random.default_rng(sum(n_sg))
+    a = make_local(rng, total, dtype)
+    b = make_local(rng, total, dtype, scale=3e-3)
+    orc = O.Oracle(n, seed=3)
+    och, gch = O.make_chunk(500, n_sg), B.make_chunk(500, n_sg)
+    assert B.dq_packed_bytes(gch) == O.Oracle.packed_bytes(och)
+    ctx = B.Context(n, seed=3)
+    w1 = orc.compress(och, 1, a)
+    g1 = ctx.dq_compress(to_dev(a, dev), gch, 1)
+    assert np.array_equal(host(g1), w1)
+    w2 = orc.dar_hop(och, 2, w1, b)
+    g2 = ctx.dq_dar_hop(g1, to_dev(b, dev), gch, 2)
+    assert np.array_equal(host(g2), w2)
+    assert np.array_equal(host(ctx.dq_decompress(g2, gch)), orc.decompress(och, w2))
+    assert np.array_equal(host(ctx.dq_decompress(g2, gch, local=to_dev(a, dev))), orc.decompress(och, w2, a))
+
+
+@pytest.mark.parametrize("topology", ["ring", "butterfly"])
+def test_replay_with_sixteen_bit_run(dev, topology):
+    n, n_sg = 8, 8 * 11
+    rng = np.random.default_rng(41)
+    grads = [make_local(rng, n_sg * 256, "bf16") for _ in range(n)]
+    counts = [13, 30, 22, 23]
+    orc = O.Oracle(n, seed=6)
+    rs = (O.ring_reduce_scatter if topology == "ring" else O.butterfly_reduce_scatter)(orc, grads, counts, first_sg=64)
+    want = np.concatenate(O.all_gather(orc, rs, counts, topology, first_sg=64))
+    ctx = B.Context(n, seed=6)
+    topo = B.DQ_RING if topology == "ring" else B.DQ_BUTTERFLY
+    rp = B.Replay(ctx, topo, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], n_sg, [counts], first_sg=64, all_gather=True)
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
