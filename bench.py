@@ -207,7 +207,7 @@ def main():
             "combine_us": round(t_comb, 1), "allocate_us": round(t_alloc, 1),
             "reorder_us": round(t_reo, 1), "reorder_GBps": round(n * entries * 2 * dtype_bytes / t_reo / 1e3, 1),
             "restore_us": round(t_res, 1), "restore_GBps": round(entries * 8 / t_res / 1e3, 1),
-            "sg_by_width_2_4_8_gpu_allocation": [int(c[0]), int(c[1]), int(c[2])],
+            "sg_by_width_2_4_8_gpu_allocation": [int(c[0]), int(c[1]), int(c[2])],   # W = {2,4,8}: c[3] (16-bit) is 0
             "note": "all workers per figure (stats and reorder: one launch per worker); GB/s = bytes read + written",
         }
         del raw, re_out, final

@@ -170,18 +170,21 @@ dq_status dq_sg_stats(const void *x, dq_dtype dtype, uint64_t n_sg, float *mu_ou
 dq_status dq_stats_combine(const float *mu_all, const float *F_all, uint32_t n_workers, uint64_t n_sg, float *mu,
                            float *F, void *hip_stream);
 
-/* Section 3.2 + Appendix A: widths in {2,4,8} from the summed squared norms F of each bucket
- * (F >= 0; negative values and NaN are unspecified input).  A super-group gets 8 bits if F >= T48, else 4 bits if F >= T24 = T48 * 17/512 (one
- * fp32 product), else 2 bits; T48 is the smallest positive fp32 value or +infinity for which
- * sum_j width_j <= max_code_bits (per bucket), found by bisection on the bit pattern.
- * DQ_EINVAL if max_code_bits < 2 * n_sg_per_bucket.  Outputs per bucket:
+/* Section 3.2 + Appendix A: widths from the summed squared norms F of each bucket (F >= 0;
+ * negative values and NaN are unspecified input).  A super-group gets 16 bits if max_width is 16
+ * and F >= T816 = T48 * 2^17/257, else 8 bits if F >= T48, else 4 bits if F >= T24 = T48 * 17/512
+ * (one fp32 product each: the threshold ratios of Section 3.2), else 2 bits; T48 is the smallest
+ * positive fp32 value or +infinity for which sum_j width_j <= max_code_bits (per bucket), found
+ * by bisection on the bit pattern.  max_width: 8 (W = {2,4,8}, the paper's prototype) or 16
+ * (W = {2,4,8,16}, its large-scale simulation).  DQ_EINVAL if max_code_bits < 2 * n_sg_per_bucket.
+ * Outputs per bucket:
  *   widths[j]  the width of super-group j
  *   pos[j]     its index inside the reordered bucket: all 2-bit super-groups first, then the
- *              4-bit, then the 8-bit ones, each class in original order (Section 3.5)
- *   counts[4b .. 4b+3] = {#2-bit, #4-bit, #8-bit, bit pattern of T48} of bucket b
+ *              4-bit, 8-bit and 16-bit ones, each class in original order (Section 3.5)
+ *   counts[5b .. 5b+4] = {#2-bit, #4-bit, #8-bit, #16-bit, bit pattern of T48} of bucket b
  * One thread block per bucket. */
 dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
-                      uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream);
+                      uint32_t max_width, uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream);
 
 /* Sections 3.1 and 3.5: out[super-group pos[j] of the bucket] = x[super-group j] - mu[j], the
  * subtraction in fp32, the result stored in x's dtype (bf16: nearest even).  mu_or_null NULL:

@@ -4,7 +4,7 @@
  * Plain CPU implementation of the steps on either side of DynamiQ's main
  * all-reduce: per-super-group statistics (Section 3.1), their combination over
  * workers (Section 3.1, the "lightweight all-reduce" of Section 3.5), the
- * three-width bit allocation with tied thresholds (Section 3.2, Appendix A),
+ * bit allocation with tied thresholds over W = {2,4,8} or {2,4,8,16} (Section 3.2, Appendix A),
  * the mean-subtracting reorder into increasing width order (Section 3.1 last
  * paragraph, Section 3.5 "reordering stage") and the final restore that puts
  * super-groups back and adds the mean back (Section 3.4, last paragraph).
@@ -72,20 +72,24 @@ void ppo_stats_combine(const float *mu_all, const float *F_all, uint32_t n, uint
   }
 }
 
-/* Width of one super-group for a threshold theta = T_{4,8}: Section 3.2 ties the lower
- * threshold to it, T_{2,4} = 17/512 * T_{4,8}; a super-group with F >= T_{b,c} gets at
- * least c bits.  17/512 is exact in fp32 and the product is one fp32 multiplication. */
-static int pp_width(float F, float theta) {
+/* Width of one super-group for a threshold theta = T_{4,8}: Section 3.2 ties the other
+ * thresholds to it, T_{2,4} = 17/512 * T_{4,8} and T_{4,8} = 257/2^17 * T_{8,16}; a super-group
+ * with F >= T_{b,c} gets at least c bits.  Each tied threshold is one fp32 multiplication of
+ * theta by the fp32 constant (17/512 is exact, 2^17/257 is rounded once).  max_width: 8 for
+ * W = {2,4,8}, 16 for W = {2,4,8,16}. */
+static int pp_width(float F, float theta, int max_width) {
   const float t24 = theta * (17.0f / 512.0f);
+  const float t816 = theta * (131072.0f / 257.0f);
+  if (max_width == 16 && F >= t816) return 16;
   if (F >= theta) return 8;
   if (F >= t24) return 4;
   return 2;
 }
-int ppo_width(float F, float theta) { return pp_width(F, theta); }
+int ppo_width(float F, float theta, int max_width) { return pp_width(F, theta, max_width); }
 
-uint64_t ppo_cost(const float *F, uint64_t J, float theta) {
+uint64_t ppo_cost(const float *F, uint64_t J, float theta, int max_width) {
   uint64_t c = 0;
-  for (uint64_t j = 0; j < J; ++j) c += (uint64_t)pp_width(F[j], theta);
+  for (uint64_t j = 0; j < J; ++j) c += (uint64_t)pp_width(F[j], theta, max_width);
   return c;
 }
 
@@ -99,34 +103,32 @@ uint64_t ppo_cost(const float *F, uint64_t J, float theta) {
  * smallest threshold whose cost fits: no logarithm, no tolerance, the same answer on
  * any machine.  The cost never increases with the threshold, and +infinity (all at
  * 2 bits) always fits when max_code_bits >= 2J; otherwise -1 is returned.
- * Outputs: widths[j] in {2,4,8}; returns the threshold's bit pattern. */
-int64_t ppo_allocate(const float *F, uint64_t J, uint64_t max_code_bits, uint8_t *widths) {
+ * Outputs: widths[j] in {2,4,8(,16)}; returns the threshold's bit pattern. */
+int64_t ppo_allocate(const float *F, uint64_t J, uint64_t max_code_bits, int max_width, uint8_t *widths) {
   const uint32_t inf_bits = 0x7F800000u;
-  if (ppo_cost(F, J, pp_bits_to_f32(inf_bits)) > max_code_bits) return -1;
+  if (ppo_cost(F, J, pp_bits_to_f32(inf_bits), max_width) > max_code_bits) return -1;
   uint32_t lo = 0, hi = inf_bits; /* invariant: cost(hi) fits; lo = 0 stands for "does not fit or not tried" */
   /* smallest pattern in [1, inf_bits] that fits */
   while (hi - lo > 1) {
     const uint32_t mid = lo + (hi - lo) / 2;
-    if (ppo_cost(F, J, pp_bits_to_f32(mid)) <= max_code_bits) hi = mid;
+    if (ppo_cost(F, J, pp_bits_to_f32(mid), max_width) <= max_code_bits) hi = mid;
     else lo = mid;
   }
   const float theta = pp_bits_to_f32(hi);
-  for (uint64_t j = 0; j < J; ++j) widths[j] = (uint8_t)pp_width(F[j], theta);
+  for (uint64_t j = 0; j < J; ++j) widths[j] = (uint8_t)pp_width(F[j], theta, max_width);
   return (int64_t)hi;
 }
 
 /* Section 3.5: super-groups are permuted "into a pre-allocated tensor in monotonically
  * increasing bitwidth order".  Reading: stable, i.e. among equal widths the original
- * order is kept.  pos[j] = destination index of super-group j; counts = {n2, n4, n8}. */
-void ppo_positions(const uint8_t *widths, uint64_t J, uint32_t *pos, uint32_t counts[3]) {
-  uint32_t n[3] = {0, 0, 0};
-  for (uint64_t j = 0; j < J; ++j) n[widths[j] == 2 ? 0 : widths[j] == 4 ? 1 : 2] += 1;
-  uint32_t next[3] = {0, n[0], n[0] + n[1]};
-  for (uint64_t j = 0; j < J; ++j) {
-    const int c = widths[j] == 2 ? 0 : widths[j] == 4 ? 1 : 2;
-    pos[j] = next[c]++;
-  }
-  counts[0] = n[0]; counts[1] = n[1]; counts[2] = n[2];
+ * order is kept.  pos[j] = destination index of super-group j; counts = {n2, n4, n8, n16}. */
+static int pp_class(uint8_t w) { return w == 2 ? 0 : w == 4 ? 1 : w == 8 ? 2 : 3; }
+void ppo_positions(const uint8_t *widths, uint64_t J, uint32_t *pos, uint32_t counts[4]) {
+  uint32_t n[4] = {0, 0, 0, 0};
+  for (uint64_t j = 0; j < J; ++j) n[pp_class(widths[j])] += 1;
+  uint32_t next[4] = {0, n[0], n[0] + n[1], n[0] + n[1] + n[2]};
+  for (uint64_t j = 0; j < J; ++j) pos[j] = next[pp_class(widths[j])]++;
+  for (int c = 0; c < 4; ++c) counts[c] = n[c];
 }
 
 /* Section 3.1: "each worker normalizes their data by subtracting mu_j from each entry in

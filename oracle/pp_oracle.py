@@ -22,11 +22,11 @@ def _lib():
         L.ppo_sg_stats.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p]
         L.ppo_stats_combine.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p]
         L.ppo_width.restype = C.c_int
-        L.ppo_width.argtypes = [C.c_float, C.c_float]
+        L.ppo_width.argtypes = [C.c_float, C.c_float, C.c_int]
         L.ppo_cost.restype = C.c_uint64
-        L.ppo_cost.argtypes = [C.c_void_p, C.c_uint64, C.c_float]
+        L.ppo_cost.argtypes = [C.c_void_p, C.c_uint64, C.c_float, C.c_int]
         L.ppo_allocate.restype = C.c_int64
-        L.ppo_allocate.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p]
+        L.ppo_allocate.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_int, C.c_void_p]
         L.ppo_positions.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
         L.ppo_reorder.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         L.ppo_restore.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p]
@@ -72,20 +72,21 @@ def stats_combine(mu_all, F_all):
     return mu, F
 
 
-def width(F, theta):
-    return int(_lib().ppo_width(np.float32(F), np.float32(theta)))
+def width(F, theta, max_width=8):
+    return int(_lib().ppo_width(np.float32(F), np.float32(theta), int(max_width)))
 
 
-def cost(F, theta):
+def cost(F, theta, max_width=8):
     F = np.ascontiguousarray(F, np.float32)
-    return int(_lib().ppo_cost(_p(F), F.size, np.float32(theta)))
+    return int(_lib().ppo_cost(_p(F), F.size, np.float32(theta), int(max_width)))
 
 
-def allocate(F, max_code_bits):
-    """-> (widths uint8 [J], threshold bit pattern); raises if even 2 bits everywhere do not fit."""
+def allocate(F, max_code_bits, max_width=8):
+    """-> (widths uint8 [J], threshold bit pattern); raises if even 2 bits everywhere do not fit.
+    max_width 8: W = {2,4,8}; 16: W = {2,4,8,16}."""
     F = np.ascontiguousarray(F, np.float32)
     w = np.empty(F.size, np.uint8)
-    t = int(_lib().ppo_allocate(_p(F), F.size, int(max_code_bits), _p(w)))
+    t = int(_lib().ppo_allocate(_p(F), F.size, int(max_code_bits), int(max_width), _p(w)))
     if t < 0:
         raise ValueError("budget below 2 code bits per coordinate")
     return w, t
@@ -94,7 +95,7 @@ def allocate(F, max_code_bits):
 def positions(widths):
     widths = np.ascontiguousarray(widths, np.uint8)
     pos = np.empty(widths.size, np.uint32)
-    counts = np.zeros(3, np.uint32)
+    counts = np.zeros(4, np.uint32)      # 2, 4, 8, 16 bits
     _lib().ppo_positions(_p(widths), widths.size, _p(pos), _p(counts))
     return pos, [int(c) for c in counts]
 

@@ -24,11 +24,12 @@ def true_sum(worker_grads):
 
 
 def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.DQ_DYNAMIQ, seed=0, round=0,
-                        all_gather=True, subtract_mean=True, n_sg_bucket=None, g4=1.3, g8=1.02):
+                        all_gather=True, subtract_mean=True, n_sg_bucket=None, g4=1.3, g8=1.02, max_width=8):
     """Returns (sum estimate in the original order, float32; info dict).
     worker_grads: one tensor per simulated worker (same length, float32 or bfloat16, a whole
     number of buckets of n_sg_bucket super-groups; default: one bucket).  MX codecs skip the
-    statistics, allocation and reorder (they have none) and ignore budget_bits."""
+    statistics, allocation and reorder (they have none) and ignore budget_bits.
+    max_width: 8 for W = {2,4,8}, 16 for W = {2,4,8,16}."""
     n = len(worker_grads)
     entries = worker_grads[0].numel()
     n_sg = entries // 256
@@ -50,8 +51,8 @@ def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.D
     if not subtract_mean:
         mu = None
     budget = int(math.floor(prep.code_bits(budget_bits) * J))
-    widths, pos, counts = B.dq_allocate(F, J, budget)
-    by_width = [[int(v) for v in row[:3]] for row in counts.cpu().tolist()]
+    widths, pos, counts = B.dq_allocate(F, J, budget, max_width=max_width)
+    by_width = [[int(v) for v in row[:4]] for row in counts.cpu().tolist()]
     reordered = [B.dq_reorder(g, pos, J, mu=mu) for g in worker_grads]
     rp = B.Replay(ctx, topology, B.DQ_DYNAMIQ, reordered, J, by_width, n_buckets=nb, all_gather=all_gather)
     rp.run()

@@ -87,7 +87,7 @@ def lib():
         L.dq_replay_destroy.restype = None
         L.dq_sg_stats.argtypes = [vp, i, u64, vp, vp, vp]
         L.dq_stats_combine.argtypes = [vp, vp, u32, u64, vp, vp, vp]
-        L.dq_allocate.argtypes = [vp, u32, u32, u64, vp, vp, vp, vp]
+        L.dq_allocate.argtypes = [vp, u32, u32, u64, u32, vp, vp, vp, vp]
         L.dq_reorder.argtypes = [vp, i, vp, vp, u32, u32, vp, vp]
         L.dq_restore.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp]
         _lib = L
@@ -309,16 +309,17 @@ def dq_stats_combine(mu_all, F_all):
     return mu, F
 
 
-def dq_allocate(F, n_sg_per_bucket, max_code_bits):
-    """F: float32 [n_buckets * n_sg_per_bucket] -> (widths uint8, pos int32 (holds uint32), counts int32 [n_buckets, 4])."""
+def dq_allocate(F, n_sg_per_bucket, max_code_bits, max_width=8):
+    """F: float32 [n_buckets * n_sg_per_bucket] -> (widths uint8, pos int32 (holds uint32),
+    counts int32 [n_buckets, 5] = #2-bit, #4-bit, #8-bit, #16-bit, threshold pattern)."""
     if F.dtype != torch.float32 or F.numel() % n_sg_per_bucket:
         raise DqError("F is float32 with a whole number of buckets")
     nb = F.numel() // n_sg_per_bucket
     widths = torch.empty(F.numel(), dtype=torch.uint8, device=F.device)
     pos = torch.empty(F.numel(), dtype=torch.int32, device=F.device)
-    counts = torch.empty((nb, 4), dtype=torch.int32, device=F.device)
-    _check(lib().dq_allocate(_ptr(F), n_sg_per_bucket, nb, int(max_code_bits), _ptr(widths), _ptr(pos), _ptr(counts),
-                             _stream()))
+    counts = torch.empty((nb, 5), dtype=torch.int32, device=F.device)
+    _check(lib().dq_allocate(_ptr(F), n_sg_per_bucket, nb, int(max_code_bits), int(max_width), _ptr(widths), _ptr(pos),
+                             _ptr(counts), _stream()))
     return widths, pos, counts
 
 

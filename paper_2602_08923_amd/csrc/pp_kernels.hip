@@ -116,18 +116,25 @@ constexpr uint32_t kCap = 4096;   // candidates kept per threshold
 
 __device__ __forceinline__ int32_t pattern_of(float f) { return f > 0.0f ? (int32_t)f2u(f) : 0; }
 
-// class 0, 1, 2 = 2, 4, 8 bits; 3 = no super-group.  Section 3.2's tied thresholds:
-// p8 = pattern of T_{4,8}, p4 = pattern of T_{2,4} = T_{4,8} * 17/512.
-__device__ __forceinline__ uint32_t class_of(int32_t v, int32_t p4, int32_t p8) {
-  return v < 0 ? 3u : (v >= p8 ? 2u : (v >= p4 ? 1u : 0u));
+// class 0, 1, 2, 3 = 2, 4, 8, 16 bits; 4 = no super-group.  Section 3.2's tied thresholds:
+// p8 = pattern of T_{4,8}, p4 = pattern of T_{2,4} = T_{4,8} * 17/512, p16 = pattern of
+// T_{8,16} = T_{4,8} * 2^17/257 (0x7FFFFFFF, above every value, when 16 bits are not allowed).
+__device__ __forceinline__ uint32_t class_of(int32_t v, int32_t p4, int32_t p8, int32_t p16) {
+  return v < 0 ? 4u : (v >= p16 ? 3u : (v >= p8 ? 2u : (v >= p4 ? 1u : 0u)));
+}
+constexpr int32_t kNever = 0x7FFFFFFF;
+__device__ __forceinline__ int32_t p4_from(uint32_t pattern) { return (int32_t)f2u(u2f(pattern) * (17.0f / 512.0f)); }
+__device__ __forceinline__ int32_t p16_from(uint32_t pattern, bool allow16) {
+  return allow16 ? (int32_t)f2u(u2f(pattern) * (131072.0f / 257.0f)) : kNever;
 }
 
 template <bool IN_REGS>
 __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, uint32_t J, uint64_t max_code_bits,
-                                                            uint8_t *widths_all, uint32_t *pos_all, uint32_t *counts_all) {
-  __shared__ uint32_t red[2][2][kAllocWaves];
-  __shared__ uint32_t tot[kRegs * kAllocWaves][3];  // per (row, wave): class counts, then their exclusive scan
-  __shared__ uint32_t wsum[kAllocWaves][3];
+                                                            bool allow16, uint8_t *widths_all, uint32_t *pos_all,
+                                                            uint32_t *counts_all) {
+  __shared__ uint32_t red[2][3][kAllocWaves];
+  __shared__ uint32_t tot[kRegs * kAllocWaves][4];  // per (row, wave): class counts, then their exclusive scan
+  __shared__ uint32_t wsum[kAllocWaves][4];
   __shared__ uint32_t hist[kBins + 2];   // top-11-bit histogram, then suffix counts (register path)
   __shared__ int32_t cand[2][kCap];      // patterns that can still change c8 / c4
   __shared__ uint32_t ncand[2];
@@ -148,10 +155,10 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
   // Counts over the wave of super-groups at or above T_{2,4} and T_{4,8}.  In registers a funnel
   // shift collects the sign bits of 32 differences in a word and one population count per word
   // turns them into the number below the threshold.
-  auto count = [&](int32_t p4, int32_t p8, uint32_t &c4, uint32_t &c8) {
-    uint32_t a4 = 0, a8 = 0;
+  auto count = [&](int32_t p4, int32_t p8, int32_t p16, uint32_t &c4, uint32_t &c8, uint32_t &c16) {
+    uint32_t a4 = 0, a8 = 0, a16 = 0;
     if constexpr (IN_REGS) {
-      uint32_t below4 = 0, below8 = 0;
+      uint32_t below4 = 0, below8 = 0, below16 = 0;
 #pragma unroll
       for (int h = 0; h < kRegs / 32; ++h) {
         uint32_t m4 = 0, m8 = 0;
@@ -162,39 +169,52 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
         }
         below4 += __builtin_popcount(m4);
         below8 += __builtin_popcount(m8);
+        if (allow16) {
+          uint32_t m16 = 0;
+#pragma unroll
+          for (int k = 0; k < 32; ++k) m16 = __builtin_amdgcn_alignbit(m16, (uint32_t)(fr[32 * h + k] - p16), 31);
+          below16 += __builtin_popcount(m16);
+        } else {
+          below16 += 32;
+        }
       }
       a4 = kRegs - below4;
       a8 = kRegs - below8;
+      a16 = kRegs - below16;
     } else {
       for (uint32_t j = tid; j < J; j += kAllocThreads) {
         const int32_t v = pattern_of(gld<float>(F + j));
         a4 += v >= p4 ? 1u : 0u;
         a8 += v >= p8 ? 1u : 0u;
+        a16 += v >= p16 ? 1u : 0u;
       }
     }
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
       a4 += __shfl_xor(a4, d, 64);
       a8 += __shfl_xor(a8, d, 64);
+      a16 += __shfl_xor(a16, d, 64);
     }
-    c4 = a4; c8 = a8;
+    c4 = a4; c8 = a8; c16 = a16;
   };
   // The waves' counts meet in LDS, in one of two buffers by turns, so that one barrier per round
   // is enough: a wave can only be one round ahead of the slowest reader.
   uint32_t turn = 0;
-  auto block_counts = [&](uint32_t pattern, uint32_t &s4, uint32_t &s8) {
-    uint32_t c4, c8;
-    count((int32_t)f2u(u2f(pattern) * (17.0f / 512.0f)), (int32_t)pattern, c4, c8);
+  auto block_counts = [&](uint32_t pattern, uint32_t &s4, uint32_t &s8, uint32_t &s16) {
+    uint32_t c4, c8, c16;
+    count(p4_from(pattern), (int32_t)pattern, p16_from(pattern, allow16), c4, c8, c16);
     if (lane == 0) {
       red[turn][0][wave] = c4;
       red[turn][1][wave] = c8;
+      red[turn][2][wave] = c16;
     }
     __syncthreads();
-    s4 = 0; s8 = 0;
+    s4 = 0; s8 = 0; s16 = 0;
 #pragma unroll
     for (int w = 0; w < kAllocWaves; ++w) {
       s4 += red[turn][0][w];
       s8 += red[turn][1][w];
+      s16 += red[turn][2][w];
     }
     turn ^= 1u;
   };
@@ -207,6 +227,7 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
   bool narrowed = false;
   uint32_t base4 = 0, base8 = 0;
   if constexpr (IN_REGS) {
+  if (!allow16) {  // with a third threshold in play everything is counted every round
     // (1) Histogram of the patterns' top 11 bits (bin b = patterns [b << 20, (b+1) << 20);
     //     2040 << 20 is +infinity), turned into suffix counts S[b] = #{v : bin(v) >= b}.
     for (uint32_t b = tid; b < kBins + 2; b += kAllocThreads) hist[b] = 0;
@@ -326,21 +347,22 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
       }
     }
   }
+  }
   if (!narrowed) {
     while (hi - lo > 1) {
       const uint32_t mid = lo + (hi - lo) / 2;
-      uint32_t s4, s8;
-      block_counts(mid, s4, s8);
-      const uint64_t cost = 2ull * J + 2ull * s4 + 4ull * s8;
+      uint32_t s4, s8, s16;
+      block_counts(mid, s4, s8, s16);
+      const uint64_t cost = 2ull * J + 2ull * s4 + 4ull * s8 + 8ull * s16;
       if (cost <= max_code_bits) hi = mid; else lo = mid;
     }
   }
-  uint32_t s4, s8;
-  block_counts(hi, s4, s8);
-  const int32_t p8 = (int32_t)hi, p4 = (int32_t)f2u(u2f(hi) * (17.0f / 512.0f));
-  const uint32_t n_class[3] = {J - s4, s4 - s8, s8};
+  uint32_t s4, s8, s16;
+  block_counts(hi, s4, s8, s16);
+  const int32_t p8 = (int32_t)hi, p4 = p4_from(hi), p16 = p16_from(hi, allow16);
+  const uint32_t n_class[4] = {J - s4, s4 - s8, s8 - s16, s16};
   // first position of each class in the reordered bucket, advanced chunk by chunk
-  uint32_t next[3] = {0, n_class[0], n_class[0] + n_class[1]};
+  uint32_t next[4] = {0, n_class[0], n_class[0] + n_class[1], n_class[0] + n_class[1] + n_class[2]};
 
   // Positions of the stable reorder, 64 rows of 1024 super-groups at a time: the rank of a
   // super-group inside its class is (members in earlier rows and waves) + (members in lower lanes).
@@ -355,31 +377,33 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
 #pragma unroll
       for (int k = 0; k < kRegs; ++k) {
         if ((uint32_t)k < nr) {
-          const uint32_t c = class_of(fr[k], p4, p8);
-          const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2);
+          const uint32_t c = class_of(fr[k], p4, p8, p16);
+          const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2), b3 = __ballot(c == 3);
           if (lane == 0) {
             tot[k * kAllocWaves + wave][0] = (uint32_t)__builtin_popcountll(b0);
             tot[k * kAllocWaves + wave][1] = (uint32_t)__builtin_popcountll(b1);
             tot[k * kAllocWaves + wave][2] = (uint32_t)__builtin_popcountll(b2);
+            tot[k * kAllocWaves + wave][3] = (uint32_t)__builtin_popcountll(b3);
           }
         }
       }
     } else {
       for (uint32_t k = 0; k < nr; ++k) {
-        const uint32_t c = class_of(slot(k), p4, p8);
-        const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2);
+        const uint32_t c = class_of(slot(k), p4, p8, p16);
+        const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2), b3 = __ballot(c == 3);
         if (lane == 0) {
           tot[k * kAllocWaves + wave][0] = (uint32_t)__builtin_popcountll(b0);
           tot[k * kAllocWaves + wave][1] = (uint32_t)__builtin_popcountll(b1);
           tot[k * kAllocWaves + wave][2] = (uint32_t)__builtin_popcountll(b2);
+          tot[k * kAllocWaves + wave][3] = (uint32_t)__builtin_popcountll(b3);
         }
       }
     }
     __syncthreads();
     // pass 2: exclusive scan of the counts in (row, wave) order; thread e owns entry e
-    uint32_t x[3], inc[3];
+    uint32_t x[4], inc[4];
 #pragma unroll
-    for (int c = 0; c < 3; ++c) {
+    for (int c = 0; c < 4; ++c) {
       x[c] = tid < nr * kAllocWaves ? tot[tid][c] : 0u;
       inc[c] = x[c];
 #pragma unroll
@@ -390,9 +414,9 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
       if (lane == 63) wsum[wave][c] = inc[c];
     }
     __syncthreads();
-    uint32_t chunk_total[3];
+    uint32_t chunk_total[4];
 #pragma unroll
-    for (int c = 0; c < 3; ++c) {
+    for (int c = 0; c < 4; ++c) {
       uint32_t before = 0, all = 0;
 #pragma unroll
       for (int w = 0; w < kAllocWaves; ++w) {
@@ -407,11 +431,11 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
     // pass 3: widths and positions, coalesced
     auto emit = [&](uint32_t k, int32_t v) {
       const uint32_t j = (r0 + k) * kAllocThreads + tid;
-      const uint32_t c = class_of(v, p4, p8);
-      const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2);
-      const uint64_t mine = c == 0 ? b0 : (c == 1 ? b1 : b2);
+      const uint32_t c = class_of(v, p4, p8, p16);
+      const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2), b3 = __ballot(c == 3);
+      const uint64_t mine = c == 0 ? b0 : (c == 1 ? b1 : (c == 2 ? b2 : b3));
       const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mine >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mine, 0u));
-      if (c < 3) {
+      if (c < 4) {
         gst<uint8_t>(widths + j, (uint8_t)(2u << c));
         gst<uint32_t>(pos + j, tot[k * kAllocWaves + wave][c] + rank);
       }
@@ -424,15 +448,16 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
       for (uint32_t k = 0; k < nr; ++k) emit(k, slot(k));
     }
 #pragma unroll
-    for (int c = 0; c < 3; ++c) next[c] += chunk_total[c];
+    for (int c = 0; c < 4; ++c) next[c] += chunk_total[c];
     __syncthreads();  // tot and wsum are reused by the next chunk
   }
   if (tid == 0) {
-    uint32_t *cnt = counts_all + 4ull * blockIdx.x;
+    uint32_t *cnt = counts_all + 5ull * blockIdx.x;
     gst<uint32_t>(cnt, n_class[0]);
     gst<uint32_t>(cnt + 1, n_class[1]);
     gst<uint32_t>(cnt + 2, n_class[2]);
-    gst<uint32_t>(cnt + 3, hi);
+    gst<uint32_t>(cnt + 3, n_class[3]);
+    gst<uint32_t>(cnt + 4, hi);
   }
 }
 
@@ -566,18 +591,18 @@ dq_status dq_stats_combine(const float *mu_all, const float *F_all, uint32_t n_w
 }
 
 dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
-                      uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream) {
+                      uint32_t max_width, uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream) {
   if (n_sg_per_bucket == 0 || n_buckets == 0) return DQ_OK;
-  if (!F || !widths || !pos || !counts) return DQ_EINVAL;
+  if (!F || !widths || !pos || !counts || (max_width != 8 && max_width != 16)) return DQ_EINVAL;
   if (max_code_bits < 2ull * n_sg_per_bucket) return DQ_EINVAL;  // fewer than 2 code bits per coordinate
   if (!aligned(F, 4) || !aligned(pos, 4) || !aligned(counts, 4)) return DQ_EALIGN;
   hipStream_t s = (hipStream_t)hip_stream;
   if (n_sg_per_bucket <= (uint32_t)kRegs * kAllocThreads)
     hipLaunchKernelGGL(k_allocate<true>, dim3(n_buckets), dim3(kAllocThreads), 0, s, F, n_sg_per_bucket, max_code_bits,
-                       widths, pos, counts);
+                       max_width == 16, widths, pos, counts);
   else
     hipLaunchKernelGGL(k_allocate<false>, dim3(n_buckets), dim3(kAllocThreads), 0, s, F, n_sg_per_bucket, max_code_bits,
-                       widths, pos, counts);
+                       max_width == 16, widths, pos, counts);
   return launched();
 }
 

@@ -26,6 +26,7 @@ def main():
     ap.add_argument("--bits", type=float, default=8.5)
     ap.add_argument("--topology", choices=["ring", "butterfly"], default="ring")
     ap.add_argument("--codec", choices=["dynamiq", "mxfp8"], default="dynamiq")
+    ap.add_argument("--max-width", type=int, default=16, choices=[8, 16], help="W = {2,4,8} or {2,4,8,16} (the paper's setting here)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     n, J = args.workers, args.sg
@@ -51,8 +52,8 @@ def main():
         mu, F = B.dq_stats_combine(mu_all, F_all)
         del mu_all, F_all
         budget = int(math.floor(prep.code_bits(args.bits) * J))
-        widths, pos, counts = B.dq_allocate(F, J, budget)
-        by_width = [[int(v) for v in counts.cpu().tolist()[0][:3]]]
+        widths, pos, counts = B.dq_allocate(F, J, budget, max_width=args.max_width)
+        by_width = [[int(v) for v in counts.cpu().tolist()[0][:4]]]
     resident = []
     for w in range(n):                                   # pass 2: the resident (reordered) gradients
         g = workloads.draw_mixture(M, w, seed=args.seed)
@@ -71,7 +72,7 @@ def main():
     err = A.vnmse(out, truth)
     print(json.dumps({
         "workers": n, "super_groups_per_worker": J, "entries_per_worker": entries, "topology": args.topology,
-        "codec": args.codec, "budget_bits": args.bits if dynamiq else 8.25, "sg_by_width_2_4_8": by_width[0] if by_width else None,
+        "codec": args.codec, "budget_bits": args.bits if dynamiq else 8.25, "sg_by_width_2_4_8_16": by_width[0] if by_width else None,
         "vNMSE": err, "gradient_GB_resident": round(n * entries * 2 / 1e9, 2),
         "scratch_GB": round(rp.scratch.numel() / 1e9, 2), "replay_steps": rp.n_steps,
         "seconds": {"generate_stats_reorder": round(t1 - t0, 2), "build_schedule": round(t2 - t1, 2),

@@ -91,12 +91,12 @@ def test_stats_combine(dev):
 
 
 # ---------------------------------------------------------------- allocation
-def check_allocate(dev, F, J, budget):
+def check_allocate(dev, F, J, budget, max_width=8):
     nb = F.size // J
-    widths, pos, counts = B.dq_allocate(torch.from_numpy(F).to(dev), J, budget)
+    widths, pos, counts = B.dq_allocate(torch.from_numpy(F).to(dev), J, budget, max_width=max_width)
     widths, pos, counts = host(widths), host(pos).view(np.uint32), host(counts).view(np.uint32)
     for b in range(nb):
-        w, tbits = P.allocate(F[b * J:(b + 1) * J], budget)
+        w, tbits = P.allocate(F[b * J:(b + 1) * J], budget, max_width=max_width)
         p, c = P.positions(w)
         assert np.array_equal(widths[b * J:(b + 1) * J], w), f"bucket {b}"
         assert np.array_equal(pos[b * J:(b + 1) * J], p), f"bucket {b}"
@@ -109,6 +109,15 @@ def check_allocate(dev, F, J, budget):
 def test_allocate_sizes(dev, J, bits):
     F = lognormal_F(J, J, zeros=min(J // 10, 50), ties=min(J // 7, 40))
     check_allocate(dev, F, J, int(math.floor(prep.code_bits(bits) * J)))
+
+
+@pytest.mark.parametrize("J", [1, 64, 1025, 51200, 70000])
+@pytest.mark.parametrize("bits", [5.0, 8.5, 12.0])
+def test_allocate_with_sixteen_bit_class(dev, J, bits):
+    F = lognormal_F(J + 1, J, zeros=min(J // 10, 50), ties=min(J // 7, 40))
+    c = check_allocate(dev, F, J, int(math.floor(prep.code_bits(bits) * J)), max_width=16)
+    if J >= 1025 and bits >= 8.5:
+        assert c[0][3] > 0                       # some super-groups do get 16 bits
 
 
 def test_allocate_many_buckets_full_size(dev):
@@ -143,7 +152,7 @@ def test_allocate_budget_edges(dev):
     c = check_allocate(dev, F, 2000, 2 * 2000)                       # exactly 2 bits each
     assert c[0][:3].tolist() == [2000, 0, 0]
     c = check_allocate(dev, F, 2000, 8 * 2000 + 5)                   # everything fits
-    assert c[0][:3].tolist() == [0, 0, 2000] and c[0][3] == 1
+    assert c[0][:3].tolist() == [0, 0, 2000] and c[0][4] == 1
     c = check_allocate(dev, np.zeros(512, f32), 512, 3 * 512)        # an all-zero bucket
     assert c[0][:3].tolist() == [512, 0, 0]
     with pytest.raises(B.DqError):
@@ -224,7 +233,7 @@ def test_whole_pipeline_is_consistent(dev):
     widths, pos, counts = B.dq_allocate(F, J, budget)
     c = counts.cpu().numpy()[0]
     w = host(widths).astype(int)
-    assert sum(c[:3]) == J and budget - 6 < int(w.sum()) <= budget
+    assert sum(c[:4]) == J and budget - 6 < int(w.sum()) <= budget
     order = np.argsort(host(F), kind="stable")
     assert np.all(np.diff(w[order]) >= 0)
     re = [B.dq_reorder(x, pos, J, mu=mu) for x in xs]

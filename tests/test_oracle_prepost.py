@@ -201,16 +201,71 @@ def test_allocate_agrees_with_log_bisection(budget_bits):
     assert np.array_equal(w.astype(np.int64), want)
 
 
+# ---------------------------------------------------------------- W = {2,4,8,16}
+def np_cost16(F, theta):
+    theta = f32(theta)
+    t24 = f32(theta * f32(17.0 / 512.0))
+    t816 = f32(theta * f32(131072.0 / 257.0))
+    return 2 * F.size + 2 * int(np.sum(F >= t24)) + 4 * int(np.sum(F >= theta)) + 8 * int(np.sum(F >= t816))
+
+
+def test_sixteen_bit_threshold_ratio():
+    def benefit(a, b):
+        return Fraction(4 ** (b - a) - 1, 4 ** b * (b - a))
+    assert benefit(4, 8) / benefit(8, 16) == Fraction(2 ** 17, 257)      # T_{8,16} / T_{4,8} (Section 3.2)
+    theta = f32(2.0 ** -20)
+    t816 = f32(theta * f32(131072.0 / 257.0))
+    assert P.width(t816, theta, 16) == 16 and P.width(t816, theta, 8) == 8
+    assert P.width(np.nextafter(t816, f32(0)), theta, 16) == 8
+    assert P.width(theta, theta, 16) == 8 and P.width(0.0, theta, 16) == 2
+    assert P.width(1e30, np.inf, 16) == 2
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_allocate_with_sixteen_bits_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    J = int(rng.integers(3, 40))
+    F = np.exp(rng.normal(-6, 3, J)).astype(f32)
+    if seed % 3 == 0:
+        F[rng.integers(0, J, 2)] = 0
+    budget = int(rng.uniform(2.0, 14.0) * J)
+    cands = [f32(np.inf), np.nextafter(f32(0), f32(1))]
+    for f in F[F > 0]:
+        cands += neighbours(f) + neighbours(f32(f) * f32(512.0 / 17.0), 6) + neighbours(f32(f) * f32(257.0 / 131072.0), 6)
+    cands = sorted(set(float(c) for c in cands))
+    fits = [c for c in cands if np_cost16(F, c) <= budget]
+    w, tbits = P.allocate(F, budget, max_width=16)
+    theta = np.array([tbits], np.uint32).view(f32)[0]
+    assert float(theta) == min(fits)
+    assert int(w.astype(int).sum()) == np_cost16(F, theta) <= budget
+    if tbits > 1:
+        assert np_cost16(F, np.array([tbits - 1], np.uint32).view(f32)[0]) > budget
+    assert set(w.tolist()) <= {2, 4, 8, 16}
+    order = np.argsort(F, kind="stable")
+    assert np.all(np.diff(w[order].astype(int)) >= 0)
+
+
+def test_sixteen_bits_go_to_the_largest_norms():
+    rng = np.random.default_rng(77)
+    F = np.exp(rng.normal(-10, 4, 4096)).astype(f32)
+    w16, _ = P.allocate(F, int(7.8125 * 4096), max_width=16)
+    w8, _ = P.allocate(F, int(7.8125 * 4096), max_width=8)
+    assert (w16 == 16).sum() > 0 and F[w16 == 16].min() >= F[w16 != 16].max()
+    assert set(w8.tolist()) <= {2, 4, 8}
+    # the same budget with a 16-bit class moves bits from the middle to the top
+    assert (w16 == 8).sum() < (w8 == 8).sum()
+
+
 # ---------------------------------------------------------------- reorder / restore
 def test_positions_are_the_stable_sort():
     rng = np.random.default_rng(3)
-    w = rng.choice(np.array([2, 4, 8], np.uint8), 1000, p=[0.5, 0.3, 0.2])
+    w = rng.choice(np.array([2, 4, 8, 16], np.uint8), 1000, p=[0.5, 0.3, 0.15, 0.05])
     pos, counts = P.positions(w)
     perm = np.argsort(w, kind="stable")                    # reordered[k] = original[perm[k]]
     inv = np.empty_like(perm)
     inv[perm] = np.arange(perm.size)
     assert np.array_equal(pos.astype(np.int64), inv)
-    assert counts == [int((w == b).sum()) for b in (2, 4, 8)]
+    assert counts == [int((w == b).sum()) for b in (2, 4, 8, 16)]
     assert sorted(pos.tolist()) == list(range(1000))
     ws = w[perm]
     assert np.all(np.diff(ws.astype(int)) >= 0)            # increasing width order (Section 3.5)
@@ -218,9 +273,9 @@ def test_positions_are_the_stable_sort():
 
 def test_positions_degenerate():
     pos, counts = P.positions(np.full(5, 4, np.uint8))
-    assert pos.tolist() == [0, 1, 2, 3, 4] and counts == [0, 5, 0]
+    assert pos.tolist() == [0, 1, 2, 3, 4] and counts == [0, 5, 0, 0]
     pos, counts = P.positions(np.zeros(0, np.uint8))
-    assert pos.size == 0 and counts == [0, 0, 0]
+    assert pos.size == 0 and counts == [0, 0, 0, 0]
 
 
 def test_reorder_moves_whole_super_groups():
