@@ -50,6 +50,7 @@ typedef struct {
   float T[3][128]; /* levels, T[wi][0..R] */
   float D[3][128]; /* gaps   D[wi][r] = T[r+1]-T[r], r < R */
   float inv_n, s_n;
+  uint32_t stride; /* multiplier of the worker index in the permutation, see dqo_perm_stride */
 } dqo_ctx;
 
 static const int DQO_BITS[3] = {2, 4, 8};
@@ -83,6 +84,8 @@ int dqo_levels(int wi, double g, float *T, float *D) {
   return 0;
 }
 
+uint32_t dqo_perm_stride(uint32_t n);
+
 dqo_ctx *dqo_create(const dqo_config *cfg) {
   if (cfg->n_workers < 1 || cfg->n_workers > 8192) return NULL;
   dqo_ctx *c = (dqo_ctx *)calloc(1, sizeof(dqo_ctx));
@@ -95,6 +98,7 @@ dqo_ctx *dqo_create(const dqo_config *cfg) {
   /* constants of the entry uniform (see dqo_entry_uniform) */
   c->inv_n = 1.0f / (float)cfg->n_workers;
   c->s_n = c->inv_n * (1.0f / 256.0f);
+  c->stride = dqo_perm_stride(cfg->n_workers);
   return c;
 }
 void dqo_destroy(dqo_ctx *c) { free(c); }
@@ -143,11 +147,27 @@ static uint8_t word_byte(const uint32_t w[4], int k) { return (uint8_t)(w[k >> 2
  *               (the scale rounding must be independent of the entry rounding, Section 3.3).
  *   slot        pi_rank for the super-group's first group: stream PERM, counter = sg,
  *               NOT keyed by the worker, so all workers derive the same permutation
- *               without communicating.  The permutation is a cyclic shift,
- *               pi_i = (i + c + g) mod n for group g of the super-group, with
- *               c = floor(word0 * n / 2^32): every group sees a permutation, one
- *               worker per interval, and a worker's 16 groups are spread over the
- *               intervals instead of all sharing one. */
+ *               without communicating.  The permutation is affine,
+ *               pi_i = (m*i + c + g) mod n for group g of the super-group, with
+ *               c = floor(word0 * n / 2^32) drawn and m = dqo_perm_stride(n) fixed:
+ *               every group sees a permutation, one worker per interval, a worker's
+ *               16 groups are spread over the intervals, and workers with consecutive
+ *               indices -- the consecutive hops of a ring -- get intervals about
+ *               n/phi apart, so that the rounding direction of an entry does not
+ *               persist from hop to hop (with m = 1 consecutive hops would round the
+ *               same way for long runs and the errors of a long ring would add up
+ *               coherently). */
+
+/* The stride m: the first integer at or above floor(n / phi) that is coprime to n
+ * (phi the golden ratio; floor(n/phi) = floor(n * 0x9E3779B9 / 2^32)), at least 1. */
+static uint32_t pp_gcd(uint32_t a, uint32_t b) { while (b) { uint32_t t = a % b; a = b; b = t; } return a; }
+uint32_t dqo_perm_stride(uint32_t n) {
+  uint32_t m = (uint32_t)(((uint64_t)n * 0x9E3779B9ull) >> 32);
+  if (m < 1) m = 1;
+  while (pp_gcd(m, n) != 1) ++m;
+  return m;
+}
+
 void dqo_draw_sg(const dqo_ctx *c, uint64_t sg, uint32_t rank, uint8_t gamma[DQO_SG],
                  uint8_t scale_byte[DQO_GROUPS_PER_SG], uint32_t *slot) {
   uint32_t w[4];
@@ -160,7 +180,7 @@ void dqo_draw_sg(const dqo_ctx *c, uint64_t sg, uint32_t rank, uint8_t gamma[DQO
   dqo_draw(c, sg, DQO_STREAM_PERM, 0xFFFFu, w);
   uint32_t n = c->cfg.n_workers;
   uint32_t shift = (uint32_t)(((uint64_t)w[0] * n) >> 32);
-  *slot = (rank + shift) % n;
+  *slot = (uint32_t)(((uint64_t)c->stride * rank + shift) % n);
 }
 
 /* ---------------------------------------------------------------- quantizer pieces */

@@ -59,6 +59,8 @@ def lib():
         L.dqo_levels.restype = C.c_int
         L.dqo_levels.argtypes = [C.c_int, C.c_double, C.c_void_p, C.c_void_p]
         L.dqo_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.dqo_perm_stride.restype = C.c_uint32
+        L.dqo_perm_stride.argtypes = [C.c_uint32]
         L.dqo_draw_sg.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.dqo_entry_uniform.restype = C.c_float
         L.dqo_entry_uniform.argtypes = [C.c_void_p, C.c_uint32, C.c_uint8]
@@ -189,6 +191,10 @@ class Oracle:
         lib().dqo_decompress(self.h, C.byref(chunk), _p(packed_in), None if local is None else _p(local),
                              0 if local is None else _dtype_code(local), _p(out))
         return out
+
+
+def perm_stride(n):
+    return int(lib().dqo_perm_stride(int(n)))
 
 
 def sq_index(T, D, x, u):

@@ -79,8 +79,17 @@ def draws(seed, rnd, n, sg, rank):
     w = call(sg, 1, rank)
     sbytes = [(w[g >> 2] >> (8 * (g & 3))) & 0xFF for g in range(16)]
     w = call(sg, 2, 0xFFFF)
-    slot = (rank + ((w[0] * n) >> 32)) % n
+    slot = (perm_stride(n) * rank + ((w[0] * n) >> 32)) % n
     return gamma, sbytes, slot
+
+
+def perm_stride(n):
+    """First integer >= floor(n / golden ratio) coprime to n (at least 1)."""
+    from math import gcd
+    m = max(1, (n * 0x9E3779B9) >> 32)
+    while gcd(m, n) != 1:
+        m += 1
+    return m
 
 
 def encode_sg(b, g, n, seed, rnd, sg, rank, v):

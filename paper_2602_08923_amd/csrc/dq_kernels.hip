@@ -308,7 +308,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const uint32_t sc_word = lds_ld1(stage + rowc * 32 + 16 + (g >> 2) * 4);
   const uint32_t scale_byte = (sc_word >> (8 * (g & 3u))) & 0xFFu;
   const uint32_t shift = __umulhi(perm_w0, P.n_workers);
-  uint32_t slot = job.rank + shift + g;
+  uint32_t slot = job.rank * P.stride + shift + g;  // below 2^27: rank, stride, shift < n <= 8192
   slot = (P.n_mask != 0xFFFFFFFFu) ? (slot & P.n_mask) : (slot % P.n_workers);
   const float o_pi = ((float)slot + (1.0f / 512.0f)) * P.inv_n;
 

@@ -158,11 +158,13 @@ def test_exactly_one_uniform_per_interval(n):
     ranks = range(n) if n <= 100 else list(range(0, n, 517)) + [n - 1]
     for sg in (0, 1, 77, 2 ** 33 + 5):
         slots = [orc.draw_sg(sg, r)[2] for r in ranks]
+        m = O.perm_stride(n)
+        assert math.gcd(m, n) == 1 and (n < 3 or abs(m / n - 0.6180339887) < 2.0 / n + 0.1)
         if n <= 100:
             assert sorted(slots) == list(range(n))
-        else:
-            shift = (slots[0] - ranks[0]) % n
-            assert all((s - r) % n == shift for s, r in zip(slots, ranks))
+        # affine in the worker index: slot = (m * rank + shift) mod n with one shift for all
+        shift = (slots[0] - m * ranks[0]) % n
+        assert all((s - m * r) % n == shift for s, r in zip(slots, ranks))
         for s in slots[:8]:
             for byte in (0, 1, 127, 255):
                 u = float(orc.entry_uniform(s, byte))
