@@ -14,6 +14,7 @@ constexpr int kGroupsPerSG = 16;
 constexpr int kWaveSGs = 4;       // one wave64 = 64 groups = 4 super-groups per tile
 constexpr int kBlockThreads = 256;
 constexpr int kBlockWaves = kBlockThreads / 64;
+constexpr uint32_t kMaxGridRows = 65535;  // documented limit of gridDim.y
 
 // One unit of work: a chunk of one simulated worker.
 struct Job {

@@ -737,7 +737,11 @@ hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, uint64
   if (n_jobs == 0 || max_tiles == 0) return hipSuccess;
   (void)total_tiles;
   const uint32_t blocks = blocks_per_job(max_tiles, n_jobs, grid_blocks);
-  hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), lds_bytes(p, KIND), s, jobs, p);
+  // the grid's y dimension (one row per job) holds at most 65,535 rows: more jobs take more launches
+  for (uint32_t first = 0; first < n_jobs; first += kMaxGridRows) {
+    const uint32_t rows = n_jobs - first < kMaxGridRows ? n_jobs - first : kMaxGridRows;
+    hipLaunchKernelGGL((k_batch<KIND, LT>), dim3(blocks, rows), dim3(kBlockThreads), lds_bytes(p, KIND), s, jobs + first, p);
+  }
   return hipGetLastError();
 }
 

@@ -247,7 +247,11 @@ hipError_t go(const MxJob *one, const MxJob *jobs, uint32_t n_jobs, uint64_t max
   if (cap < 1) cap = 1;
   const uint32_t blocks = (uint32_t)(blocks_needed < cap ? blocks_needed : cap);
   if (one) hipLaunchKernelGGL((mx_one<FMT, KIND, LT>), dim3(blocks), dim3(kBlockThreads), 0, s, *one);
-  else hipLaunchKernelGGL((mx_batch<FMT, KIND, LT>), dim3(blocks, n_jobs), dim3(kBlockThreads), 0, s, jobs);
+  else
+    for (uint32_t first = 0; first < n_jobs; first += kMaxGridRows) {  // gridDim.y holds at most 65,535 rows
+      const uint32_t rows = n_jobs - first < kMaxGridRows ? n_jobs - first : kMaxGridRows;
+      hipLaunchKernelGGL((mx_batch<FMT, KIND, LT>), dim3(blocks, rows), dim3(kBlockThreads), 0, s, jobs + first);
+    }
   return hipGetLastError();
 }
 

@@ -449,3 +449,25 @@ def test_replay_with_sixteen_bit_run(dev, topology):
     rp.run()
     torch.cuda.synchronize()
     assert np.array_equal(host(rp.out), want)
+
+
+def test_more_jobs_than_grid_rows(dev):
+    """512-worker recursive halving: the first steps have 131,072 and 65,536 (worker, chunk) jobs,
+    more than one launch's 65,535 grid rows, so they are split over launches."""
+    n = 512
+    n_sg = n
+    rng = np.random.default_rng(77)
+    grads = [make_local(rng, n_sg * 256, "bf16") for _ in range(n)]
+    counts = [100, 300, 112]
+    want = np.concatenate(O.butterfly_reduce_scatter(O.Oracle(n, seed=4), grads, counts))
+    ctx = B.Context(n, seed=4)
+    rp = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], n_sg, [counts])
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+    rm = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_MXFP4_E2M1, [to_dev(g, dev) for g in grads], n_sg)
+    rm.run()
+    torch.cuda.synchronize()
+    true = sum((g.astype(np.uint32) << 16).view(np.float32).astype(np.float64) for g in grads)
+    got = host(rm.out).astype(np.float64)
+    assert ((got - true) ** 2).sum() / (true ** 2).sum() < 0.2
