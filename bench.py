@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 # 2^30 bytes on the same box: FETCH_SIZE counts half the bytes read (x2.0), WRITE_SIZE all of
 # them (x1.0).  Key: (workload, codec).  The summary with the commands sits in profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    (2, 0): int((16122.3 * 2.0 + 6229.8 * 1.0) * 1024),
+    (2, 0): int((16130.8 * 2.0 + 6227.1 * 1.0) * 1024),
 }
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E published peak
 
