@@ -54,6 +54,9 @@ typedef struct {
   uint64_t seed;      /* PRNG seed shared by all workers (Section 2.4) */
   uint32_t round;     /* training round: a new round draws fresh random numbers */
   uint32_t n_workers; /* n of the correlated rounding u_i = (pi_i + gamma_i)/n, 1..8192 */
+  uint32_t independent_rounding; /* 0: correlated rounding (Section 3.3).  1: every worker rounds on its own,
+                         u = gamma in [0,1): the baseline of Section 2.4, kept for comparisons */
+  uint32_t reserved;  /* 0 */
 } dq_config;
 
 typedef struct {

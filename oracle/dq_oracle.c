@@ -42,6 +42,8 @@ typedef struct {
   uint64_t seed;      /* shared PRNG seed (Section 2.4: workers share a seed) */
   uint32_t round;     /* training round, so that every round draws fresh numbers */
   uint32_t n_workers; /* n in u_i = (pi_i + gamma_i)/n */
+  uint32_t independent; /* 1: every worker rounds on its own, u = gamma (the baseline that Section 2.4 improves on) */
+  uint32_t reserved;
 } dqo_config;
 
 typedef struct {
@@ -96,7 +98,8 @@ dqo_ctx *dqo_create(const dqo_config *cfg) {
     return NULL;
   }
   /* constants of the entry uniform (see dqo_entry_uniform) */
-  c->inv_n = 1.0f / (float)cfg->n_workers;
+  /* independent rounding is the case n = 1 of the same formula: one interval, u = (byte + 1/2)/256 */
+  c->inv_n = cfg->independent ? 1.0f : 1.0f / (float)cfg->n_workers;
   c->s_n = c->inv_n * (1.0f / 256.0f);
   c->stride = dqo_perm_stride(cfg->n_workers);
   return c;
@@ -180,7 +183,7 @@ void dqo_draw_sg(const dqo_ctx *c, uint64_t sg, uint32_t rank, uint8_t gamma[DQO
   dqo_draw(c, sg, DQO_STREAM_PERM, 0xFFFFu, w);
   uint32_t n = c->cfg.n_workers;
   uint32_t shift = (uint32_t)(((uint64_t)w[0] * n) >> 32);
-  *slot = (uint32_t)(((uint64_t)c->stride * rank + shift) % n);
+  *slot = c->cfg.independent ? 0u : (uint32_t)(((uint64_t)c->stride * rank + shift) % n);
 }
 
 /* ---------------------------------------------------------------- quantizer pieces */
@@ -258,7 +261,8 @@ void dqo_encode_sg_core(const dqo_ctx *c, int wi, const float v[DQO_SG], const u
     float inv = 1.0f / m; /* one divide per group */
     for (int k = 0; k < DQO_GROUP; ++k) {
       float x = fminf(fabsf(vg[k]) * inv, 1.0f);
-      float u = dqo_entry_uniform(c, (slot + (uint32_t)g) % c->cfg.n_workers, gamma[g * DQO_GROUP + k]);
+      const uint32_t pi = c->cfg.independent ? 0u : (slot + (uint32_t)g) % c->cfg.n_workers;
+      float u = dqo_entry_uniform(c, pi, gamma[g * DQO_GROUP + k]);
       int r = dqo_sq_index(T, D, R, x, u);
       cg[k] = (uint8_t)(((f32_to_bits(vg[k]) >> 31) << (b - 1)) | (uint32_t)r);
     }

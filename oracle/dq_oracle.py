@@ -35,7 +35,7 @@ def build(force=False):
 
 class Config(C.Structure):
     _fields_ = [("g4", C.c_double), ("g8", C.c_double), ("seed", C.c_uint64),
-                ("round", C.c_uint32), ("n_workers", C.c_uint32)]
+                ("round", C.c_uint32), ("n_workers", C.c_uint32), ("independent", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class Chunk(C.Structure):
@@ -122,8 +122,8 @@ def make_chunk(first_sg, n_sg):
 class Oracle:
     """One codec context: level tables + PRNG key (seed, round) + worker count."""
 
-    def __init__(self, n_workers, seed=0, round=0, g4=1.3, g8=1.02):
-        self.cfg = Config(g4, g8, seed, round, n_workers)
+    def __init__(self, n_workers, seed=0, round=0, g4=1.3, g8=1.02, independent=False):
+        self.cfg = Config(g4, g8, seed, round, n_workers, 1 if independent else 0, 0)
         self.n_workers = n_workers
         self.h = lib().dqo_create(C.byref(self.cfg))
         if not self.h:

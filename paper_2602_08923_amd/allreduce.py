@@ -24,7 +24,8 @@ def true_sum(worker_grads):
 
 
 def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.DQ_DYNAMIQ, seed=0, round=0,
-                        all_gather=True, subtract_mean=True, n_sg_bucket=None, g4=1.3, g8=1.02, max_width=8):
+                        all_gather=True, subtract_mean=True, n_sg_bucket=None, g4=1.3, g8=1.02, max_width=8,
+                        independent_rounding=False):
     """Returns (sum estimate in the original order, float32; info dict).
     worker_grads: one tensor per simulated worker (same length, float32 or bfloat16, a whole
     number of buckets of n_sg_bucket super-groups; default: one bucket).  MX codecs skip the
@@ -37,7 +38,7 @@ def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.D
     if entries % 256 or n_sg % J or J % n:
         raise B.DqError("buckets must hold a multiple of n_workers super-groups of 256 entries")
     nb = n_sg // J
-    ctx = B.Context(n, seed=seed, round=round, g4=g4, g8=g8)
+    ctx = B.Context(n, seed=seed, round=round, g4=g4, g8=g8, independent_rounding=independent_rounding)
     if codec != B.DQ_DYNAMIQ:
         rp = B.Replay(ctx, topology, codec, worker_grads, J, n_buckets=nb, all_gather=all_gather)
         rp.run()

@@ -33,7 +33,7 @@ class DqError(RuntimeError):
 
 class Config(C.Structure):
     _fields_ = [("g4", C.c_double), ("g8", C.c_double), ("seed", C.c_uint64), ("round", C.c_uint32),
-                ("n_workers", C.c_uint32)]
+                ("n_workers", C.c_uint32), ("independent_rounding", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class Chunk(C.Structure):
@@ -142,10 +142,10 @@ def _entries(chunk):
 class Context:
     """dq_ctx: level tables on the device + PRNG key (seed, round) + worker count."""
 
-    def __init__(self, n_workers, seed=0, round=0, g4=1.3, g8=1.02):
+    def __init__(self, n_workers, seed=0, round=0, g4=1.3, g8=1.02, independent_rounding=False):
         self.h = C.c_void_p()
         self.n_workers = n_workers
-        cfg = Config(g4, g8, seed, round, n_workers)
+        cfg = Config(g4, g8, seed, round, n_workers, 1 if independent_rounding else 0, 0)
         _check(lib().dq_create(C.byref(cfg), C.byref(self.h)))
 
     def close(self):

@@ -231,6 +231,10 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
     P.stride = m;
   }
   P.inv_n = 1.0f / (float)cfg->n_workers;
+  if (cfg->independent_rounding) {  // the case n = 1 of the same arithmetic: one interval, slot 0
+    P.inv_n = 1.0f;
+    P.n_mask = 0;
+  }
   P.s_n = P.inv_n * (1.0f / 256.0f);
   ctx->params = P;
   *out = ctx;

@@ -49,9 +49,9 @@ def test_null_arguments_are_rejected_without_a_gpu():
     L = B.lib()
     h = ctypes.c_void_p()
     assert L.dq_create(None, ctypes.byref(h)) == B.DQ_EINVAL
-    cfg = B.Config(1.3, 1.02, 0, 0, 0)   # zero workers
+    cfg = B.Config(1.3, 1.02, 0, 0, 0, 0, 0)   # zero workers
     assert L.dq_create(ctypes.byref(cfg), ctypes.byref(h)) == B.DQ_EINVAL
-    cfg = B.Config(1.0, 1.02, 0, 0, 4)   # degenerate level set
+    cfg = B.Config(1.0, 1.02, 0, 0, 4, 0, 0)   # degenerate level set
     assert L.dq_create(ctypes.byref(cfg), ctypes.byref(h)) == B.DQ_EINVAL
     assert L.dq_compress(None, None, 0, None, 0, None, None) == B.DQ_EINVAL
     assert L.dq_mx_compress(1, None, 0, 256, None, None) == B.DQ_EINVAL

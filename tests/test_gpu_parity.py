@@ -471,3 +471,25 @@ def test_more_jobs_than_grid_rows(dev):
     true = sum((g.astype(np.uint32) << 16).view(np.float32).astype(np.float64) for g in grads)
     got = host(rm.out).astype(np.float64)
     assert ((got - true) ** 2).sum() / (true ** 2).sum() < 0.2
+
+
+def test_independent_rounding_mode(dev):
+    """dq_config.independent_rounding: u = gamma for every worker (the baseline of Section 2.4)."""
+    n, n_sg = 8, [9, 14, 9]
+    total = sum(n_sg) * 256
+    rng = np.random.default_rng(8)
+    a, b = make_local(rng, total, "bf16"), make_local(rng, total, "bf16")
+    orc = O.Oracle(n, seed=2, independent=True)
+    och, gch = O.make_chunk(10, n_sg), B.make_chunk(10, n_sg)
+    ctx = B.Context(n, seed=2, independent_rounding=True)
+    w1 = orc.compress(och, 3, a)
+    g1 = ctx.dq_compress(to_dev(a, dev), gch, 3)
+    assert np.array_equal(host(g1), w1)
+    assert np.array_equal(host(ctx.dq_dar_hop(g1, to_dev(b, dev), gch, 5)), orc.dar_hop(och, 5, w1, b))
+    assert not np.array_equal(w1, O.Oracle(n, seed=2).compress(och, 3, a))      # not the correlated codes
+    grads = [make_local(rng, 32 * 256, "bf16") for _ in range(n)]
+    want = np.concatenate(O.ring_reduce_scatter(orc, grads, [8, 16, 8]))
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], 32, [[8, 16, 8]])
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)

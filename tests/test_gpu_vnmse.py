@@ -74,3 +74,19 @@ def test_rounds_draw_fresh_randomness_and_average_out(dev):
     assert avg < 0.2 * mean_single, (avg, mean_single)
     assert avg - mean_single / R < 0.1 * mean_single            # the bias part
     assert len({round(s, 12) for s in single}) == R           # every round differs
+
+
+def test_correlated_rounding_beats_independent_rounding(dev):
+    """Section 2.4 / the paper's ablation: sharing the permutation lowers the error of the sum."""
+    J = 4096
+    rows = []
+    for n, topo in ((8, B.DQ_RING), (64, B.DQ_RING), (64, B.DQ_BUTTERFLY)):
+        M = workloads.mixture_magnitudes(J, seed=8, device=dev)
+        grads = [workloads.draw_mixture(M, w, seed=8) for w in range(n)]
+        truth = A.true_sum(grads)
+        cor = A.vnmse(A.simulated_allreduce(grads, 5.0, topology=topo, seed=4)[0], truth)
+        ind = A.vnmse(A.simulated_allreduce(grads, 5.0, topology=topo, seed=4, independent_rounding=True)[0], truth)
+        rows.append((n, topo, cor, ind))
+    print("\ncorrelated vs independent rounding:", ["n=%d %s %.3e vs %.3e" % (n, "ring" if t == B.DQ_RING else "bfly", c, i) for n, t, c, i in rows])
+    for n, topo, cor, ind in rows:
+        assert cor < ind
