@@ -15,7 +15,9 @@
 // The stochastic rounding follows the division-free form  T + u*D < x'  with
 // u = (pi + gamma)/n built from one Philox byte per entry (Section 3.3 "Correlated rounding").
 // The per-SG random numbers (group-scale bytes, shared permutation) of up to 8 tiles are
-// drawn by ONE wave-wide Philox call (each lane a different counter) and parked in LDS.
+// drawn by ONE wave-wide Philox call (each lane a different counter) and parked in LDS; a block
+// with few tiles draws for all its waves at once.  A chunk may end in a run of 16-bit
+// super-groups (raw bf16 values, Section 3.2): those tiles only add and round.
 //
 // All arithmetic that decides a code is IEEE binary32 with explicit fused multiply-adds
 // only where written (this file is compiled with -ffp-contract=off and correctly rounded
@@ -145,7 +147,7 @@ __device__ __forceinline__ uint32_t lut_addr(const Params &P, uint32_t lds0) {
   else return lds0 + P.off_lut[2] * 4;
 }
 
-// Where a tile (index t in the job's concatenated 2-, 4-, 8-bit tile sequence) sits.
+// Where a tile (index t in the job's concatenated 2-, 4-, 8-, 16-bit tile sequence) sits.
 struct TilePos {
   uint32_t seg_first;   // position in the chunk of the first SG of the tile's width
   uint32_t n_seg;       // SGs of that width in the chunk
