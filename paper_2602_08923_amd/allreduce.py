@@ -25,12 +25,13 @@ def true_sum(worker_grads):
 
 def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.DQ_DYNAMIQ, seed=0, round=0,
                         all_gather=True, subtract_mean=True, n_sg_bucket=None, g4=1.3, g8=1.02, max_width=8,
-                        independent_rounding=False):
+                        independent_rounding=False, uniform_width=None):
     """Returns (sum estimate in the original order, float32; info dict).
     worker_grads: one tensor per simulated worker (same length, float32 or bfloat16, a whole
     number of buckets of n_sg_bucket super-groups; default: one bucket).  MX codecs skip the
     statistics, allocation and reorder (they have none) and ignore budget_bits.
-    max_width: 8 for W = {2,4,8}, 16 for W = {2,4,8,16}."""
+    max_width: 8 for W = {2,4,8}, 16 for W = {2,4,8,16}.  uniform_width (2, 4 or 8): no allocation,
+    every super-group at that width (the baseline the variable allocation is compared with)."""
     n = len(worker_grads)
     entries = worker_grads[0].numel()
     n_sg = entries // 256
@@ -51,9 +52,15 @@ def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.D
     mu, F = B.dq_stats_combine(mu_all, F_all)
     if not subtract_mean:
         mu = None
-    budget = int(math.floor(prep.code_bits(budget_bits) * J))
-    widths, pos, counts = B.dq_allocate(F, J, budget, max_width=max_width)
-    by_width = [[int(v) for v in row[:4]] for row in counts.cpu().tolist()]
+    if uniform_width is None:
+        budget = int(math.floor(prep.code_bits(budget_bits) * J))
+        widths, pos, counts = B.dq_allocate(F, J, budget, max_width=max_width)
+        by_width = [[int(v) for v in row[:4]] for row in counts.cpu().tolist()]
+    else:
+        pos = torch.arange(J, dtype=torch.int32, device=dev).repeat(nb)
+        row = [0, 0, 0, 0]
+        row[{2: 0, 4: 1, 8: 2, 16: 3}[uniform_width]] = J
+        by_width = [row] * nb
     reordered = [B.dq_reorder(g, pos, J, mu=mu) for g in worker_grads]
     rp = B.Replay(ctx, topology, B.DQ_DYNAMIQ, reordered, J, by_width, n_buckets=nb, all_gather=all_gather)
     rp.run()
