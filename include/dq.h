@@ -25,7 +25,7 @@
  *   [2-bit codes, 64 B per SG][4-bit codes, 128 B per SG][8-bit codes, 256 B per SG]
  *   [16-bit values, 512 B per SG: raw bf16, "16 bits corresponds to uncompressed values", Section 3.2]
  *   [group scales, 16 u8 per coded SG][SG scales, one u16 bf16 pattern per coded SG], rounded up
- *   to 16 B; the coded SGs are those at 2, 4 and 8 bits.  A 16-bit SG has no scales and uses no
+ *   to 16 B (the kernels never write those padding bytes); the coded SGs are those at 2, 4 and 8 bits.  A 16-bit SG has no scales and uses no
  *   random numbers: compress rounds to bf16 (nearest even), a DAR hop adds in fp32 and rounds back.
  * Entry k of an SG sits at bit offset k*b of the SG's code block (little-endian);
  * code = sign << (b-1) | level index.
@@ -201,6 +201,23 @@ dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, const f
  * mean-subtracted entries).  mu_or_null NULL: only the permutation is undone. */
 dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_or_null, uint32_t n_workers,
                      uint32_t n_sg_per_bucket, uint32_t n_buckets, float *out, void *hip_stream);
+
+/* ---- Block-wise pipelining (Section 4, "RDMA engine": as soon as a gradient block completes its
+ * decompress-accumulate-recompress, its transfer begins while subsequent blocks are processed).
+ * One hop of one chunk, cut every block_sg super-groups; on the wire each block is a packed chunk
+ * of its own (first_sg advanced, widths as they fall), the blocks back to back, each starting
+ * at a multiple of 256 bytes: dq_pipelined_wire_bytes in all.  Block i is (re-)encoded on
+ * compute_stream into one half of `stage` (dq_pipelined_stage_bytes, two blocks) and copied from
+ * there to its place in wire_out on copy_stream -- a device-to-device copy standing in for the
+ * network -- while block i+1 is being encoded.  wire_in NULL: the first hop (compress).  The two
+ * streams must differ; when the call returns, compute_stream has been made to wait for the last
+ * copies, so synchronising it is enough.  Events are created inside the context at the first call;
+ * one pipelined call at a time per context. */
+size_t dq_pipelined_wire_bytes(const dq_chunk *chunk, uint32_t block_sg);
+size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg);
+dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *local, dq_dtype dtype,
+                               const dq_chunk *chunk, uint32_t rank, uint32_t block_sg, void *stage, void *wire_out,
+                               void *compute_stream, void *copy_stream);
 
 const char *dq_status_str(dq_status s);
 /* Last HIP error string seen by this library on the calling thread (for DQ_EHIP). */

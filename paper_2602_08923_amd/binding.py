@@ -24,6 +24,7 @@ EXPORTS = [
     "dq_replay_step_info",
     "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
     "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_reorder", "dq_restore",
+    "dq_pipelined_wire_bytes", "dq_pipelined_stage_bytes", "dq_dar_hop_pipelined",
 ]
 
 
@@ -90,6 +91,11 @@ def lib():
         L.dq_allocate.argtypes = [vp, u32, u32, u64, u32, vp, vp, vp, vp]
         L.dq_reorder.argtypes = [vp, i, vp, vp, u32, u32, vp, vp]
         L.dq_restore.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp]
+        L.dq_pipelined_wire_bytes.argtypes = [C.POINTER(Chunk), u32]
+        L.dq_pipelined_wire_bytes.restype = C.c_size_t
+        L.dq_pipelined_stage_bytes.argtypes = [C.POINTER(Chunk), u32]
+        L.dq_pipelined_stage_bytes.restype = C.c_size_t
+        L.dq_dar_hop_pipelined.argtypes = [vp, vp, vp, i, C.POINTER(Chunk), u32, u32, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -345,3 +351,28 @@ def dq_restore(total, pos, n_sg_per_bucket, n_workers, mu=None, out=None):
         out = torch.empty_like(total)
     _check(lib().dq_restore(_ptr(total), _ptr(pos), _ptr(mu), n_workers, n_sg_per_bucket, nb, _ptr(out), _stream()))
     return out
+
+
+# ------------------------------------------------------------------ block-wise pipelining
+def dq_pipelined_wire_bytes(chunk, block_sg):
+    return lib().dq_pipelined_wire_bytes(C.byref(chunk), block_sg)
+
+
+def dq_pipelined_stage_bytes(chunk, block_sg):
+    return lib().dq_pipelined_stage_bytes(C.byref(chunk), block_sg)
+
+
+def dq_dar_hop_pipelined(ctx, wire_in, local, chunk, rank, block_sg, compute_stream, copy_stream, stage=None,
+                         wire_out=None):
+    """One hop of a chunk in blocks of block_sg super-groups: block i is encoded on compute_stream
+    while block i-1 travels (a device copy) on copy_stream.  wire_in None: the first hop."""
+    dev = local.device
+    if stage is None:
+        # zeros: the kernels never write the padding at the end of a packed block
+        stage = torch.zeros(dq_pipelined_stage_bytes(chunk, block_sg), dtype=torch.uint8, device=dev)
+    if wire_out is None:
+        wire_out = torch.zeros(dq_pipelined_wire_bytes(chunk, block_sg), dtype=torch.uint8, device=dev)
+    _check(lib().dq_dar_hop_pipelined(ctx.h, _ptr(wire_in), _ptr(local), _dtype(local), C.byref(chunk), rank, block_sg,
+                                      _ptr(stage), _ptr(wire_out), C.c_void_p(compute_stream.cuda_stream),
+                                      C.c_void_p(copy_stream.cuda_stream)))
+    return wire_out

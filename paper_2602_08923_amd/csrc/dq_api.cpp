@@ -201,6 +201,7 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
   if (!ctx) return DQ_EINVAL;
   ctx->cfg = *cfg;
   ctx->blob_dev = nullptr;
+  ctx->have_events = false;
   hipDeviceProp_t prop;
   if (!hip_ok(hipGetDevice(&ctx->device)) || !hip_ok(hipGetDeviceProperties(&prop, ctx->device)) ||
       !hip_ok(hipMalloc(&ctx->blob_dev, blob.size() * 4)) ||
@@ -244,6 +245,11 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
 void dq_destroy(dq_ctx *ctx) {
   if (!ctx) return;
   if (ctx->blob_dev) (void)hipFree(ctx->blob_dev);
+  if (ctx->have_events)
+    for (int i = 0; i < 2; ++i) {
+      (void)hipEventDestroy(ctx->stage_filled[i]);
+      (void)hipEventDestroy(ctx->stage_free[i]);
+    }
   delete ctx;
 }
 
@@ -302,6 +308,104 @@ dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or
                                (hipStream_t)hip_stream))
              ? DQ_OK
              : DQ_EHIP;
+}
+
+}  // extern "C"
+
+// ---- block-wise pipelining -------------------------------------------------------------
+
+namespace {
+
+// Block b of a chunk cut every block_sg super-groups: a chunk of its own.
+dq_chunk block_of(const dq_chunk *ch, uint32_t block_sg, uint64_t b) {
+  uint64_t edges[5] = {0, 0, 0, 0, 0};
+  for (int w = 0; w < 4; ++w) edges[w + 1] = edges[w] + ch->n_sg[w];
+  const uint64_t lo = b * block_sg, hi = lo + block_sg < edges[4] ? lo + block_sg : edges[4];
+  dq_chunk out;
+  out.first_sg = ch->first_sg + lo;
+  for (int w = 0; w < 4; ++w) {
+    const uint64_t a = lo > edges[w] ? lo : edges[w], e = hi < edges[w + 1] ? hi : edges[w + 1];
+    out.n_sg[w] = e > a ? (uint32_t)(e - a) : 0;
+  }
+  return out;
+}
+
+size_t wire_slot(const dq_chunk *blk) { return (dq_packed_bytes(blk) + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+size_t dq_pipelined_wire_bytes(const dq_chunk *chunk, uint32_t block_sg) {
+  if (!chunk || block_sg == 0) return 0;
+  const uint64_t n = chunk_sgs(chunk), blocks = (n + block_sg - 1) / block_sg;
+  size_t total = 0;
+  for (uint64_t b = 0; b < blocks; ++b) {
+    const dq_chunk blk = block_of(chunk, block_sg, b);
+    total += wire_slot(&blk);
+  }
+  return total;
+}
+
+size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg) {
+  if (!chunk || block_sg == 0) return 0;
+  const uint64_t n = chunk_sgs(chunk), blocks = (n + block_sg - 1) / block_sg;
+  size_t biggest = 0;
+  for (uint64_t b = 0; b < blocks; ++b) {
+    const dq_chunk blk = block_of(chunk, block_sg, b);
+    const size_t s = wire_slot(&blk);
+    if (s > biggest) biggest = s;
+  }
+  return 2 * biggest;
+}
+
+dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *local, dq_dtype dtype, const dq_chunk *chunk,
+                               uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
+                               void *copy_stream) {
+  dq_status st = check_chunk(ctx, chunk, rank);
+  if (st != DQ_OK) return st;
+  const uint64_t n = chunk_sgs(chunk);
+  if (n == 0) return DQ_OK;
+  if (!local || !stage || !wire_out || block_sg == 0 || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
+  if (compute_stream == copy_stream) return DQ_EINVAL;  // the overlap needs two streams
+  if (!aligned16(wire_in) || !aligned16(local) || !aligned16(stage) || !aligned16(wire_out)) return DQ_EALIGN;
+  hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
+  if (!ctx->have_events) {
+    for (int i = 0; i < 2; ++i)
+      if (!hip_ok(hipEventCreateWithFlags(&ctx->stage_filled[i], hipEventDisableTiming)) ||
+          !hip_ok(hipEventCreateWithFlags(&ctx->stage_free[i], hipEventDisableTiming)))
+        return DQ_EHIP;
+    ctx->have_events = true;
+  }
+  const size_t half = dq_pipelined_stage_bytes(chunk, block_sg) / 2;
+  const size_t es = dtype == DQ_F32 ? 4 : 2;
+  const uint64_t blocks = (n + block_sg - 1) / block_sg;
+  size_t wire_off = 0;
+  for (uint64_t b = 0; b < blocks; ++b) {
+    const dq_chunk blk = block_of(chunk, block_sg, b);
+    const size_t bytes = dq_packed_bytes(&blk);
+    const int slot = (int)(b & 1);
+    uint8_t *stg = static_cast<uint8_t *>(stage) + slot * half;
+    // the stage half is free again once the copy of block b-2 has left it
+    if (b >= 2 && !hip_ok(hipStreamWaitEvent(cs, ctx->stage_free[slot], 0))) return DQ_EHIP;
+    // the kernels do not write the padding at the end of a packed block: clear the last 16 bytes first,
+    // or a block would carry bytes of the one that used this half before
+    if (bytes >= 16 && !hip_ok(hipMemsetAsync(stg + bytes - 16, 0, 16, cs))) return DQ_EHIP;
+    dq::Job j{wire_in ? static_cast<const uint8_t *>(wire_in) + wire_off : nullptr,
+              static_cast<const uint8_t *>(local) + b * (uint64_t)block_sg * 256 * es, stg, blk.first_sg,
+              {blk.n_sg[0], blk.n_sg[1], blk.n_sg[2], blk.n_sg[3]}, rank};
+    if (!hip_ok(dq::launch_one(wire_in ? dq::kDar : dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, cs)))
+      return DQ_EHIP;
+    if (!hip_ok(hipEventRecord(ctx->stage_filled[slot], cs)) || !hip_ok(hipStreamWaitEvent(xs, ctx->stage_filled[slot], 0)) ||
+        !hip_ok(hipMemcpyAsync(static_cast<uint8_t *>(wire_out) + wire_off, stg, bytes, hipMemcpyDeviceToDevice, xs)) ||
+        !hip_ok(hipEventRecord(ctx->stage_free[slot], xs)))
+      return DQ_EHIP;
+    wire_off += wire_slot(&blk);
+  }
+  // whoever waits for the compute stream also waits for the last transfers
+  for (int slot = 0; slot < 2 && (uint64_t)slot < blocks; ++slot)
+    if (!hip_ok(hipStreamWaitEvent(cs, ctx->stage_free[slot], 0))) return DQ_EHIP;
+  return DQ_OK;
 }
 
 }  // extern "C"

@@ -86,4 +86,6 @@ struct dq_ctx {
   uint32_t n_cu;
   uint32_t grid_blocks;  // n_cu x blocks per CU (6, or the DQ_BLOCKS_PER_CU environment variable at dq_create)
   int device;
+  hipEvent_t stage_filled[2], stage_free[2];  // block pipeline: created on first use, destroyed with the context
+  bool have_events;
 };

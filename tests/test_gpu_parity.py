@@ -493,3 +493,46 @@ def test_independent_rounding_mode(dev):
     rp.run()
     torch.cuda.synchronize()
     assert np.array_equal(host(rp.out), want)
+
+
+# ----------------------------------------------------------------------------- block-wise pipelining
+
+def block_chunks(n_sg, block_sg, first_sg):
+    counts = list(n_sg) + [0] * (4 - len(n_sg))
+    edges = np.cumsum([0] + counts)
+    total = int(edges[-1])
+    out = []
+    for lo in range(0, total, block_sg):
+        hi = min(lo + block_sg, total)
+        out.append((lo, hi, [int(max(0, min(hi, edges[w + 1]) - max(lo, edges[w]))) for w in range(4)]))
+    return [(lo, hi, O.make_chunk(first_sg + lo, c)) for lo, hi, c in out]
+
+
+@pytest.mark.parametrize("block_sg", [4, 7, 64, 1000])
+def test_pipelined_hops_match_blockwise_oracle(dev, block_sg):
+    """Section 4: a chunk travels in blocks, each a packed chunk of its own; three hops in a row."""
+    n, n_sg, first = 4, [30, 41, 20, 9], 300
+    total = sum(n_sg)
+    rng = np.random.default_rng(block_sg)
+    xs = [make_local(rng, total * 256, "bf16") for _ in range(3)]
+    orc = O.Oracle(n, seed=12)
+    ctx = B.Context(n, seed=12)
+    gch = B.make_chunk(first, n_sg)
+    blocks = block_chunks(n_sg, block_sg, first)
+    want, msgs = [], [None] * len(blocks)
+    for hop, x in enumerate(xs):
+        for i, (lo, hi, ch) in enumerate(blocks):
+            sl = x[lo * 256:hi * 256]
+            msgs[i] = orc.compress(ch, hop, sl) if hop == 0 else orc.dar_hop(ch, hop, msgs[i], sl)
+    for m in msgs:
+        want.append(np.concatenate([m, np.zeros((-len(m)) % 256, np.uint8)]))
+    want = np.concatenate(want)
+    assert B.dq_pipelined_wire_bytes(gch, block_sg) == want.size
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    wire = None
+    for hop, x in enumerate(xs):
+        wire = B.dq_dar_hop_pipelined(ctx, wire, to_dev(x, dev), gch, hop, block_sg, s1, s2)
+        s1.synchronize()
+    assert np.array_equal(host(wire), want)
+    with pytest.raises(B.DqError):
+        B.dq_dar_hop_pipelined(ctx, wire, to_dev(xs[0], dev), gch, 0, block_sg, s1, s1)     # one stream: no overlap possible
