@@ -4,7 +4,7 @@
 A "step" is one pass of the whole hot path over one batch of synthetic input: the full
 reduce-scatter hop replay of the chosen workload (compress, every DAR hop, the final
 decompress-accumulate) for all simulated workers, inputs resident in HBM.  The default
-workload is the benchmark's config 2: 8-worker ring over one 25 MB bf16 DDP bucket per
+workload is benchmark configuration 2: 8-worker ring over one 25 MB bf16 DDP bucket per
 worker (13,107,200 entries, N(0,1e-3) with 0.1 % x100 outliers), DynamiQ at ~4 bits/entry.
 
 Prints ONE JSON line.  `value` = gradient bytes processed per second over the whole replay
@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 5], help="BASELINE.json config number")
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 5], help="benchmark configuration number")
     ap.add_argument("--mx-format", type=int, default=1, choices=[1, 2, 3], help="config 3 only: 1 FP8, 2 FP6, 3 FP4")
     ap.add_argument("--entries", type=int, default=None, help="override entries per worker (multiple of 256*workers)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")

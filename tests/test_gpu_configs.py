@@ -1,4 +1,4 @@
-"""The five BASELINE configurations at FULL size, in the launch configuration bench.py times
+"""The five benchmark configurations at FULL size, in the launch configuration bench.py times
 (the hop replay), against the CPU oracle.
 
 Configs 1-3: the oracle replays the whole schedule and every output entry is compared.

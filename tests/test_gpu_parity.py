@@ -187,7 +187,7 @@ def prepared(wl, dev, entries=None, bucket=0):
 
 
 def test_ring_replay_config1_full(dev):
-    """BASELINE config 1 at full size: 4 workers, 2^20 fp32 entries each, b = 5."""
+    """Benchmark configuration 1 at full size: 4 workers, 2^20 fp32 entries each, b = 5."""
     wl = workloads.CONFIGS[1]
     re, counts = prepared(wl, dev)
     assert sum(counts) == 4096 and counts[1] > 0
