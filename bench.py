@@ -29,6 +29,13 @@ sys.path.insert(0, ROOT)
 MEASURED_TRAFFIC_BYTES = {
     (2, 0): int((16130.8 * 2.0 + 6227.1 * 1.0) * 1024),
 }
+# Vector-ALU wave instructions per DAR launch, from `rocprofv3 --pmc SQ_INSTS_VALU` on the same
+# command (profiles/); one wave instruction is 64 lane operations.
+MEASURED_VALU_WAVE_INSTR = {
+    (2, 0): 5_493_358,
+}
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: lane operations per second the vector ALUs can issue
+VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E published peak
 
 
@@ -162,6 +169,12 @@ def main():
         "avg_launch_us": round(dar_ms * 1e3, 2),
         "gradient_GBps_per_dar_hop": round(dar_entries * dtype_bytes / (dar_ms * 1e-3) / 1e9, 1) if dar_steps else None,
         "launches_per_replay": n_dar,
+        # the kernel is bound by vector-ALU issue, not by HBM: the same launch priced against the issue rate
+        "alu_view": None if (args.workload, codec) not in MEASURED_VALU_WAVE_INSTR or not dar_steps else {
+            "bound": "alu", "unit": "T lane-op/s", "peak": round(VALU_PEAK_TLANEOPS, 2),
+            "achieved": round(MEASURED_VALU_WAVE_INSTR[(args.workload, codec)] * 64 / (dar_ms * 1e-3) / 1e12, 2),
+            "frac": round(MEASURED_VALU_WAVE_INSTR[(args.workload, codec)] * 64 / (dar_ms * 1e-3) / 1e12 / VALU_PEAK_TLANEOPS, 4),
+            "valu_wave_instructions_per_launch": MEASURED_VALU_WAVE_INSTR[(args.workload, codec)]},
         "timing": f"HIP events on the launch stream bracketing the consecutive DAR launches of every {every}-th replay inside the timed region ({len(events)} brackets)",
     }
 
