@@ -365,6 +365,19 @@ static float local_at(const void *local, int dtype, uint64_t j) {
   return bf16_to_f32(((const uint16_t *)local)[j]);
 }
 
+/* Section 3.1: every worker subtracts the super-group's mean mu_j from its entries before
+ * they are quantized.  Reading: the subtraction is one fp32 operation on the widened entry,
+ * done where the entry enters the main stage (never stored back in the gradient's dtype:
+ * rounding x - mu to bf16 returns x whenever |mu| is below half an ulp of x, and then all
+ * n workers err by +mu together).  mu is indexed by the super-group's place in the chunk;
+ * NULL = nothing is subtracted. */
+static void local_sg(const void *local, int dtype, const float *mu_or_null, uint64_t j, float v[DQO_SG]) {
+  for (int k = 0; k < DQO_SG; ++k) {
+    const float x = local_at(local, dtype, j * DQO_SG + k);
+    v[k] = mu_or_null ? x - mu_or_null[j] : x;
+  }
+}
+
 /* width index and position inside its code array of the j-th super-group of a chunk */
 static int sg_width(const dqo_chunk *ch, uint64_t j, uint64_t *pos) {
   if (j < ch->n_sg[0]) { *pos = j; return 0; }
@@ -380,7 +393,8 @@ static int sg_width(const dqo_chunk *ch, uint64_t j, uint64_t *pos) {
 
 /* Leaf node: compress the local chunk (Section 4, kernel 1).  `rank` is the
  * worker doing the compression. */
-void dqo_compress(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const void *local, int dtype, void *packed_out) {
+void dqo_compress(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const void *local, int dtype,
+                  const float *mu_or_null, void *packed_out) {
   dqo_view o = chunk_view(ch, packed_out);
   uint64_t n = chunk_total_sg(ch);
   memset(packed_out, 0, dqo_packed_bytes(ch));
@@ -391,7 +405,7 @@ void dqo_compress(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const vo
     uint8_t gamma[DQO_SG], sb[16], code[DQO_SG], rG[16];
     uint16_t sf;
     uint32_t slot;
-    for (int k = 0; k < DQO_SG; ++k) v[k] = local_at(local, dtype, j * DQO_SG + k);
+    local_sg(local, dtype, mu_or_null, j, v);
     if (wi == 3) { /* uncompressed: the values themselves, as bf16 */
       uint16_t *raw = (uint16_t *)(o.codes[3] + pos * 512);
       for (int k = 0; k < DQO_SG; ++k) raw[k] = f32_to_bf16_rne(v[k]);
@@ -408,7 +422,7 @@ void dqo_compress(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const vo
 /* Internal node: decode the received partial sum, add the local slice, re-encode
  * (Section 4, kernel 3); nothing but registers between the three steps. */
 void dqo_dar_hop(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const void *packed_in, const void *local,
-                 int dtype, void *packed_out) {
+                 int dtype, const float *mu_or_null, void *packed_out) {
   dqo_view in = chunk_view(ch, (void *)packed_in);
   uint64_t n = chunk_total_sg(ch);
   uint64_t bytes = dqo_packed_bytes(ch);
@@ -421,7 +435,7 @@ void dqo_dar_hop(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const voi
     uint8_t gamma[DQO_SG], sb[16], code[DQO_SG], rG[16];
     uint16_t sf;
     uint32_t slot;
-    for (int k = 0; k < DQO_SG; ++k) loc[k] = local_at(local, dtype, j * DQO_SG + k);
+    local_sg(local, dtype, mu_or_null, j, loc);
     if (wi == 3) { /* uncompressed: bf16 partial sum + local in fp32, rounded back to bf16 */
       const uint16_t *raw_in = (const uint16_t *)(in.codes[3] + pos * 512);
       uint16_t *raw = (uint16_t *)(o.codes[3] + pos * 512);
@@ -443,10 +457,10 @@ void dqo_dar_hop(const dqo_ctx *c, const dqo_chunk *ch, uint32_t rank, const voi
 }
 
 /* Sink of the reduce-scatter, non-last parents in a butterfly, all-gather
- * receivers: decode, optionally add the local slice, write fp32 (Section 4,
- * kernels 2 and 4).  out may alias an fp32 local. */
+ * receivers: decode, optionally add the local slice (minus its means), write fp32
+ * (Section 4, kernels 2 and 4).  out may alias an fp32 local. */
 void dqo_decompress(const dqo_ctx *c, const dqo_chunk *ch, const void *packed_in, const void *local_or_null, int dtype,
-                    float *out) {
+                    const float *mu_or_null, float *out) {
   dqo_view in = chunk_view(ch, (void *)packed_in);
   uint64_t n = chunk_total_sg(ch);
   for (uint64_t j = 0; j < n; ++j) {
@@ -455,8 +469,7 @@ void dqo_decompress(const dqo_ctx *c, const dqo_chunk *ch, const void *packed_in
     float loc[DQO_SG], v[DQO_SG];
     uint8_t code[DQO_SG], rG[16];
     uint16_t sf;
-    if (local_or_null)
-      for (int k = 0; k < DQO_SG; ++k) loc[k] = local_at(local_or_null, dtype, j * DQO_SG + k);
+    if (local_or_null) local_sg(local_or_null, dtype, mu_or_null, j, loc);
     if (wi == 3) {
       const uint16_t *raw_in = (const uint16_t *)(in.codes[3] + pos * 512);
       for (int k = 0; k < DQO_SG; ++k)

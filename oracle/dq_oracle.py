@@ -74,10 +74,12 @@ def lib():
                                          C.c_void_p]
         L.dqo_packed_bytes.restype = C.c_uint64
         L.dqo_packed_bytes.argtypes = [C.POINTER(Chunk)]
-        L.dqo_compress.argtypes = [C.c_void_p, C.POINTER(Chunk), C.c_uint32, C.c_void_p, C.c_int, C.c_void_p]
+        L.dqo_compress.argtypes = [C.c_void_p, C.POINTER(Chunk), C.c_uint32, C.c_void_p, C.c_int, C.c_void_p,
+                                   C.c_void_p]
         L.dqo_dar_hop.argtypes = [C.c_void_p, C.POINTER(Chunk), C.c_uint32, C.c_void_p, C.c_void_p, C.c_int,
-                                  C.c_void_p]
-        L.dqo_decompress.argtypes = [C.c_void_p, C.POINTER(Chunk), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+                                  C.c_void_p, C.c_void_p]
+        L.dqo_decompress.argtypes = [C.c_void_p, C.POINTER(Chunk), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                     C.c_void_p]
         if hasattr(L, "mxo_packed_bytes"):
             L.mxo_packed_bytes.restype = C.c_uint64
             L.mxo_packed_bytes.argtypes = [C.c_int, C.c_uint64]
@@ -109,6 +111,15 @@ def _dtype_code(a):
     if a.dtype == np.uint16:
         return BF16  # bf16 bit patterns
     raise TypeError("local must be float32 or uint16 (bf16 bit patterns)")
+
+
+def _mu_arg(mu, chunk):
+    """Per-super-group means of a chunk as a float32 array (kept alive by the caller), or None."""
+    if mu is None:
+        return None
+    mu = np.ascontiguousarray(mu, np.float32)
+    assert mu.size == sum(chunk.n_sg), "one mean per super-group of the chunk"
+    return mu
 
 
 def make_chunk(first_sg, n_sg):
@@ -175,21 +186,28 @@ class Oracle:
     def packed_bytes(chunk):
         return lib().dqo_packed_bytes(C.byref(chunk))
 
-    def compress(self, chunk, rank, local):
+    def compress(self, chunk, rank, local, mu=None):
+        """mu: one mean per super-group of the chunk, subtracted from the local entries in fp32
+        (Section 3.1), or None."""
         out = np.zeros(self.packed_bytes(chunk), np.uint8)
-        lib().dqo_compress(self.h, C.byref(chunk), rank, _p(local), _dtype_code(local), _p(out))
+        mu = _mu_arg(mu, chunk)
+        lib().dqo_compress(self.h, C.byref(chunk), rank, _p(local), _dtype_code(local),
+                           None if mu is None else _p(mu), _p(out))
         return out
 
-    def dar_hop(self, chunk, rank, packed_in, local):
+    def dar_hop(self, chunk, rank, packed_in, local, mu=None):
         out = np.zeros(self.packed_bytes(chunk), np.uint8)
-        lib().dqo_dar_hop(self.h, C.byref(chunk), rank, _p(packed_in), _p(local), _dtype_code(local), _p(out))
+        mu = _mu_arg(mu, chunk)
+        lib().dqo_dar_hop(self.h, C.byref(chunk), rank, _p(packed_in), _p(local), _dtype_code(local),
+                          None if mu is None else _p(mu), _p(out))
         return out
 
-    def decompress(self, chunk, packed_in, local=None):
+    def decompress(self, chunk, packed_in, local=None, mu=None):
         n = sum(chunk.n_sg) * 256
         out = np.empty(n, np.float32)
+        mu = None if local is None else _mu_arg(mu, chunk)
         lib().dqo_decompress(self.h, C.byref(chunk), _p(packed_in), None if local is None else _p(local),
-                             0 if local is None else _dtype_code(local), _p(out))
+                             0 if local is None else _dtype_code(local), None if mu is None else _p(mu), _p(out))
         return out
 
 
@@ -244,13 +262,14 @@ def split_bucket(n_sg_by_width, n_chunks, first_sg=0):
 
 # ------------------------------------------------------------------ hop schedules
 
-def ring_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None):
+def ring_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None, mu=None):
     """Ring reduce-scatter (Section 3.4): chunk c starts at worker c (leaf,
     compress), visits workers c+1 .. c+n-2 (decompress-accumulate-recompress)
     and ends at worker c+n-1 (sink: decompress + add local).  grads[w] is worker
     w's reordered bucket (float32 or bf16 bit patterns).  Returns the list of
     fp32 sums per chunk; trace (a dict) receives every packed message as
-    trace[(step, chunk)]."""
+    trace[(step, chunk)].  mu: the bucket's per-super-group means in reordered order,
+    subtracted from every worker's entries where they enter (Section 3.1), or None."""
     n = orc.n_workers
     chunks = split_bucket(n_sg_by_width, n, first_sg)
     m = sum(n_sg_by_width) // n * 256
@@ -258,33 +277,36 @@ def ring_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None):
     for c in range(n):
         ch = chunks[c]
         sl = slice(c * m, (c + 1) * m)
+        mc = None if mu is None else mu[c * m // 256:(c + 1) * m // 256]
         if n == 1:
             g = grads[0][sl]
-            out.append(g.astype(np.float32) if g.dtype == np.float32 else
-                       (g.astype(np.uint32) << 16).view(np.float32))
+            g = g.astype(np.float32) if g.dtype == np.float32 else (g.astype(np.uint32) << 16).view(np.float32)
+            out.append(g if mc is None else g - np.repeat(np.asarray(mc, np.float32), 256))
             continue
         w = c
-        msg = orc.compress(ch, w, np.ascontiguousarray(grads[w][sl]))
+        msg = orc.compress(ch, w, np.ascontiguousarray(grads[w][sl]), mc)
         if trace is not None:
             trace[(0, c)] = msg
         for t in range(1, n - 1):
             w = (c + t) % n
-            msg = orc.dar_hop(ch, w, msg, np.ascontiguousarray(grads[w][sl]))
+            msg = orc.dar_hop(ch, w, msg, np.ascontiguousarray(grads[w][sl]), mc)
             if trace is not None:
                 trace[(t, c)] = msg
         w = (c + n - 1) % n
-        out.append(orc.decompress(ch, msg, np.ascontiguousarray(grads[w][sl])))
+        out.append(orc.decompress(ch, msg, np.ascontiguousarray(grads[w][sl]), mc))
     return out
 
 
-def butterfly_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None):
+def butterfly_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None, mu=None):
     """Recursive-halving reduce-scatter (Appendix B): at step k = 1..log2 n worker
     w exchanges with w XOR (n >> k); it keeps the half of its current range whose
     index bit matches its own and sends the other half.  What it sends at step 1
     is compress(local half); a message received at step k covers the range kept at
     step k: the part sent at step k+1 goes through decompress-accumulate-recompress,
     the part kept through decompress-accumulate into an fp32 buffer that is the
-    `local` of later steps.  Worker w ends with the sum of chunk w."""
+    `local` of later steps.  Worker w ends with the sum of chunk w.  mu (the bucket's means
+    in reordered order, or None) is subtracted where a worker's raw gradient enters a kernel,
+    never from an fp32 buffer that already holds mean-subtracted sums."""
     n = orc.n_workers
     L = n.bit_length() - 1
     assert n == 1 << L and n >= 2
@@ -296,6 +318,11 @@ def butterfly_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None):
 
     # acc[w][c]: worker w's current accumulation of chunk c (raw gradient slice at the start)
     acc = [{c: np.ascontiguousarray(grads[w][sl(c)]) for c in range(n)} for w in range(n)]
+    raw = [{c: True for c in range(n)} for w in range(n)]  # acc[w][c] is still the raw gradient slice
+
+    def mean_of(w, c):
+        return mu[c * m // 256:(c + 1) * m // 256] if (mu is not None and raw[w][c]) else None
+
     lo = [0] * n
     ln = [n] * n
     inbox = [dict() for _ in range(n)]  # chunk -> packed message waiting at the worker
@@ -308,23 +335,24 @@ def butterfly_reduce_scatter(orc, grads, n_sg_by_width, first_sg=0, trace=None):
             partner = w ^ half
             for c in range(send_lo, send_lo + half):
                 if k == 1:
-                    msg = orc.compress(chunks[c], w, acc[w][c])
+                    msg = orc.compress(chunks[c], w, acc[w][c], mean_of(w, c))
                 else:
-                    msg = orc.dar_hop(chunks[c], w, inbox[w].pop(c), acc[w][c])
+                    msg = orc.dar_hop(chunks[c], w, inbox[w].pop(c), acc[w][c], mean_of(w, c))
                 sends.append((partner, c, msg))
                 if trace is not None:
                     trace[(k, w, c)] = msg
                 del acc[w][c]
             if k > 1:
                 for c in range(keep_lo, keep_lo + half):
-                    acc[w][c] = orc.decompress(chunks[c], inbox[w].pop(c), acc[w][c])
+                    acc[w][c] = orc.decompress(chunks[c], inbox[w].pop(c), acc[w][c], mean_of(w, c))
+                    raw[w][c] = False
             lo[w], ln[w] = keep_lo, half
         for partner, c, msg in sends:
             inbox[partner][c] = msg
     out = []
     for w in range(n):
         assert lo[w] == w and ln[w] == 1
-        out.append(orc.decompress(chunks[w], inbox[w].pop(w), acc[w][w]))
+        out.append(orc.decompress(chunks[w], inbox[w].pop(w), acc[w][w], mean_of(w, w)))
     return out
 
 

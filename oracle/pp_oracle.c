@@ -5,9 +5,9 @@
  * all-reduce: per-super-group statistics (Section 3.1), their combination over
  * workers (Section 3.1, the "lightweight all-reduce" of Section 3.5), the
  * bit allocation with tied thresholds over W = {2,4,8} or {2,4,8,16} (Section 3.2, Appendix A),
- * the mean-subtracting reorder into increasing width order (Section 3.1 last
- * paragraph, Section 3.5 "reordering stage") and the final restore that puts
- * super-groups back and adds the mean back (Section 3.4, last paragraph).
+ * the reorder into increasing width order (Section 3.5 "reordering stage"), the
+ * means the main stage subtracts (Section 3.1 last paragraph) and the final restore that
+ * puts super-groups back and adds the mean back (Section 3.4, last paragraph).
  * Only tests, the smoke check and the benchmark's cpu_baseline leg use it; it
  * shares nothing with the GPU library.
  *
@@ -131,33 +131,32 @@ void ppo_positions(const uint8_t *widths, uint64_t J, uint32_t *pos, uint32_t co
   for (int c = 0; c < 4; ++c) counts[c] = n[c];
 }
 
+/* Section 3.5: every worker copies its super-groups into increasing-width order.  A plain
+ * permutation of whole super-groups; the bucket has J of them. */
+void ppo_reorder(const void *x, int dtype, const uint32_t *pos, uint64_t J, void *out) {
+  const size_t esz = dtype == 0 ? 4 : 2;
+  for (uint64_t j = 0; j < J; ++j)
+    memcpy((uint8_t *)out + (uint64_t)pos[j] * PPO_SG * esz, (const uint8_t *)x + j * PPO_SG * esz, PPO_SG * esz);
+}
+
 /* Section 3.1: "each worker normalizes their data by subtracting mu_j from each entry in
- * super-group j", then reorders.  Reading: the subtraction is one fp32 operation on the
- * widened entry and the result is stored in the gradient's own dtype (bf16: round to
- * nearest even), so the main stage reads as many bytes as the raw gradient has.
- * mu may be NULL (no subtraction).  The bucket has J super-groups. */
-void ppo_reorder(const void *x, int dtype, const uint32_t *pos, const float *mu, uint64_t J, void *out) {
-  for (uint64_t j = 0; j < J; ++j) {
-    const float m = mu ? mu[j] : 0.0f;
-    for (int k = 0; k < PPO_SG; ++k) {
-      const uint64_t src = j * PPO_SG + k, dst = (uint64_t)pos[j] * PPO_SG + k;
-      if (dtype == 0) {
-        ((float *)out)[dst] = ((const float *)x)[src] - m;
-      } else {
-        const float v = pp_bits_to_f32((uint32_t)((const uint16_t *)x)[src] << 16);
-        ((uint16_t *)out)[dst] = pp_bf16_rne(v - m);
-      }
-    }
-  }
+ * super-group j".  The main stage does that subtraction itself, in fp32, where an entry
+ * enters it, so what it needs is the means in the reordered order.  Reading: a super-group
+ * sent uncompressed (16 bits) is not normalized, its mean is taken as zero: a raw bf16 value
+ * gains nothing from the subtraction and rounding x - mu back to bf16 would bias the sum.
+ * n16 = the number of 16-bit super-groups (they are the last n16 of the reordered bucket). */
+void ppo_reorder_mean(const float *mu, const uint32_t *pos, uint64_t J, uint32_t n16, float *mu_main) {
+  for (uint64_t j = 0; j < J; ++j) mu_main[pos[j]] = (uint64_t)pos[j] + n16 < J ? mu[j] : 0.0f;
 }
 
 /* Section 3.4, last paragraph: "entries are restored to their original order and
  * unnormalized by adding back the mean value".  The main stage returns the SUM over the
- * n workers of the mean-subtracted entries, so what is added back is n*mu_j: one fp32
- * multiplication per super-group, one fp32 addition per entry.  mu may be NULL. */
-void ppo_restore(const float *sum, const uint32_t *pos, const float *mu, uint32_t n, uint64_t J, float *out) {
+ * n workers of the mean-subtracted entries, so what is added back is n times the mean the
+ * main stage subtracted (mu_main, in reordered order): one fp32 multiplication per
+ * super-group, one fp32 addition per entry.  mu_main may be NULL. */
+void ppo_restore(const float *sum, const uint32_t *pos, const float *mu_main, uint32_t n, uint64_t J, float *out) {
   for (uint64_t j = 0; j < J; ++j) {
-    const float back = mu ? (float)n * mu[j] : 0.0f;
+    const float back = mu_main ? (float)n * mu_main[pos[j]] : 0.0f;
     for (int k = 0; k < PPO_SG; ++k)
       out[j * PPO_SG + k] = sum[(uint64_t)pos[j] * PPO_SG + k] + back;
   }

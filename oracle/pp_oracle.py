@@ -1,5 +1,5 @@
 """ctypes front end of pp_oracle.c: the steps before and after the main all-reduce
-(statistics, their combination, bit allocation, reorder, restore).
+(statistics, their combination, bit allocation, reorder, the means of the main stage, restore).
 
 TEST INFRASTRUCTURE, NOT PRODUCT CODE: only tests, the smoke check and the
 benchmark's cpu_baseline leg may import this module.
@@ -28,7 +28,8 @@ def _lib():
         L.ppo_allocate.restype = C.c_int64
         L.ppo_allocate.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_int, C.c_void_p]
         L.ppo_positions.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
-        L.ppo_reorder.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.ppo_reorder.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.ppo_reorder_mean.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]
         L.ppo_restore.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p]
         _ready = True
     return L
@@ -100,19 +101,30 @@ def positions(widths):
     return pos, [int(c) for c in counts]
 
 
-def reorder(x, pos, mu=None):
+def reorder(x, pos):
+    """Whole super-groups of x moved to their places pos (Section 3.5)."""
     x = np.ascontiguousarray(x)
     pos = np.ascontiguousarray(pos, np.uint32)
     out = np.empty_like(x)
-    m = None if mu is None else np.ascontiguousarray(mu, np.float32)
-    _lib().ppo_reorder(_p(x), _dtype_code(x), _p(pos), None if m is None else _p(m), pos.size, _p(out))
+    _lib().ppo_reorder(_p(x), _dtype_code(x), _p(pos), pos.size, _p(out))
     return out
 
 
-def restore(total, pos, mu, n_workers):
+def reorder_mean(mu, pos, n16):
+    """The means the main stage subtracts, in reordered order: zero for the last n16
+    (uncompressed) super-groups."""
+    mu = np.ascontiguousarray(mu, np.float32)
+    pos = np.ascontiguousarray(pos, np.uint32)
+    out = np.empty_like(mu)
+    _lib().ppo_reorder_mean(_p(mu), _p(pos), pos.size, int(n16), _p(out))
+    return out
+
+
+def restore(total, pos, mu_main, n_workers):
+    """total: the main stage's sums in reordered order; mu_main: what reorder_mean returned, or None."""
     total = np.ascontiguousarray(total, np.float32)
     pos = np.ascontiguousarray(pos, np.uint32)
     out = np.empty_like(total)
-    m = None if mu is None else np.ascontiguousarray(mu, np.float32)
+    m = None if mu_main is None else np.ascontiguousarray(mu_main, np.float32)
     _lib().ppo_restore(_p(total), _p(pos), None if m is None else _p(m), int(n_workers), pos.size, _p(out))
     return out

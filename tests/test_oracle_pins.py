@@ -492,6 +492,38 @@ def test_bf16_local_equals_widened_fp32_local():
     assert np.array_equal(orc.decompress(ch, p16, h), orc.decompress(ch, p32, wide))
 
 
+def test_mean_is_subtracted_in_fp32_where_the_entry_enters():
+    """Section 3.1: a call with means equals the same call on entries from which the mean was
+    taken off beforehand in fp32 (never rounded back to bf16), for every kernel and width."""
+    orc = O.Oracle(4, seed=9)
+    ch = O.make_chunk(3, [1, 2, 1, 1])
+    rng = np.random.default_rng(12)
+    h = ((rng.standard_normal(5 * 256) * 0.01).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    wide = (h.astype(np.uint32) << 16).view(np.float32)
+    mu = (rng.standard_normal(5) * 1e-3).astype(np.float32)
+    pre = wide - np.repeat(mu, 256)                      # one fp32 subtraction per entry
+    assert not np.array_equal(pre, wide)
+    p = orc.compress(ch, 1, h, mu)
+    assert np.array_equal(p, orc.compress(ch, 1, pre))
+    assert np.array_equal(p, orc.compress(ch, 1, wide, mu))
+    assert not np.array_equal(p, orc.compress(ch, 1, h))
+    assert np.array_equal(orc.dar_hop(ch, 2, p, h, mu), orc.dar_hop(ch, 2, p, pre))
+    assert np.array_equal(orc.decompress(ch, p, h, mu), orc.decompress(ch, p, pre))
+    assert np.array_equal(orc.decompress(ch, p, None, mu), orc.decompress(ch, p))   # no local: nothing to subtract
+
+
+def test_constant_super_group_minus_its_mean_is_zero():
+    """A wrong sign (x + mu) or a mean taken from the wrong super-group would leave 2c or c."""
+    orc = O.Oracle(2, seed=1)
+    ch = O.make_chunk(0, [1, 1, 1])
+    c = np.array([0.375, -2.5, 7.0], np.float32)
+    x = np.repeat(c, 256)
+    p = orc.compress(ch, 0, x, c)
+    assert not np.any(orc.decompress(ch, p))
+    got = orc.decompress(ch, p, x, c[::-1].copy())       # decode 0 + (x - other mean): exact differences
+    assert np.array_equal(got, x - np.repeat(c[::-1], 256))
+
+
 # ----------------------------------------------------------------- independent re-implementation
 
 @pytest.mark.parametrize("b,wi", [(2, 0), (4, 1), (8, 2)])

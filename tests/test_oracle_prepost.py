@@ -288,22 +288,24 @@ def test_reorder_moves_whole_super_groups():
         assert np.array_equal(out[pos[j] * 256:(pos[j] + 1) * 256], x[j * 256:(j + 1) * 256])
 
 
-def test_reorder_subtracts_the_mean_in_fp32_and_rounds_bf16_to_nearest_even():
+def test_reorder_keeps_bf16_patterns():
     rng = np.random.default_rng(6)
     J = 6
-    v = torch.from_numpy(rng.standard_normal(J * 256).astype(f32) * f32(1e-3)).to(torch.bfloat16)
-    xb = v.view(torch.int16).numpy().view(np.uint16)
-    mu = (rng.standard_normal(J) * 1e-4).astype(f32)
+    xb = rng.integers(0, 1 << 16, J * 256).astype(np.uint16)          # any pattern: the copy looks at no value
     pos = np.array([3, 0, 5, 1, 4, 2], np.uint32)
-    out = P.reorder(xb, pos, mu)
-    diff = v.float().numpy().reshape(J, 256) - mu[:, None]            # one fp32 subtraction
-    want = torch.from_numpy(diff).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    out = P.reorder(xb, pos)
     for j in range(J):
-        assert np.array_equal(out[pos[j] * 256:(pos[j] + 1) * 256], want[j])
-    x32 = v.float().numpy()
-    out32 = P.reorder(x32, pos, mu)
-    for j in range(J):
-        assert np.array_equal(out32[pos[j] * 256:(pos[j] + 1) * 256], diff[j])
+        assert np.array_equal(out[pos[j] * 256:(pos[j] + 1) * 256], xb[j * 256:(j + 1) * 256])
+
+
+def test_reorder_mean_follows_the_positions_and_zeroes_uncompressed_super_groups():
+    w = np.array([8, 16, 2, 4, 16, 8, 2], np.uint8)
+    mu = np.arange(1, 8, dtype=f32)                                    # mu[j] = j + 1
+    pos, counts = P.positions(w)
+    mm = P.reorder_mean(mu, pos, counts[3])
+    # reordered order: the 2-bit ones (j = 2, 6), the 4-bit one (3), the 8-bit ones (0, 5), the 16-bit ones (1, 4)
+    assert mm.tolist() == [3.0, 7.0, 4.0, 1.0, 6.0, 0.0, 0.0]
+    assert P.reorder_mean(mu, pos, 0).tolist() == [3.0, 7.0, 4.0, 1.0, 6.0, 2.0, 5.0]
 
 
 def test_restore_inverts_reorder_and_adds_n_mu():
@@ -312,12 +314,15 @@ def test_restore_inverts_reorder_and_adds_n_mu():
     # small integers times 2^-6: every sum and difference below is exact in fp32
     xs = [(rng.integers(-64, 64, J * 256) * 2.0 ** -6).astype(f32) for _ in range(n)]
     mu = (rng.integers(-8, 8, J) * 2.0 ** -6).astype(f32)
-    w = rng.choice(np.array([2, 4, 8], np.uint8), J)
-    pos, _ = P.positions(w)
-    total = sum(P.reorder(x, pos, mu) for x in xs)          # what an exact main stage would return
-    out = P.restore(total, pos, mu, n)
+    w = rng.choice(np.array([2, 4, 8, 16], np.uint8), J)
+    pos, counts = P.positions(w)
+    mm = P.reorder_mean(mu, pos, counts[3])
+    # what an exact main stage would return: the sum over workers of (entry - its mean), reordered
+    total = sum(P.reorder(x, pos) for x in xs) - n * np.repeat(mm, 256)
+    out = P.restore(total, pos, mm, n)
     assert np.array_equal(out, sum(xs))                     # sum_i (x_i - mu) + n mu = sum_i x_i
-    assert np.array_equal(P.restore(total, pos, None, n), sum(xs) - n * np.repeat(mu, 256))
+    kept = np.where(w == 16, f32(0), mu)                    # in the original order
+    assert np.array_equal(P.restore(total, pos, None, n), sum(xs) - n * np.repeat(kept, 256))
 
 
 def test_pipeline_on_real_shapes():

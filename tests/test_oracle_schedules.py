@@ -239,3 +239,39 @@ def test_ring_error_grows_about_linearly_with_the_hops():
         return vnmse(out, gs)
     e16, e64 = run(16), run(64)
     assert e64 < 2.5e-3 and 2.0 < e64 / e16 < 7.0, (e16, e64)
+
+
+# ----------------------------------------------------------------- mean subtraction (Section 3.1)
+
+@pytest.mark.parametrize("n", [2, 4, 8])
+def test_schedules_subtract_each_workers_mean_exactly_once(n):
+    """bf16 gradients and a mean per super-group: both schedules return bit for bit what they
+    return on fp32 gradients from which the mean was taken off beforehand.  A mean subtracted
+    twice (from a butterfly's fp32 buffer) or never (at one kind of node) would show."""
+    J = 2 * n
+    counts = [n // 2, n // 2, n - 2, 2]
+    orc = O.Oracle(n, seed=17)
+    gs = grads(n, J, 21, np.uint16)
+    rng = np.random.default_rng(22)
+    mu = (rng.standard_normal(J) * 3e-4).astype(np.float32)
+    pre = [widen(g) - np.repeat(mu, 256) for g in gs]
+    for fn in (O.ring_reduce_scatter, O.butterfly_reduce_scatter):
+        got = np.concatenate(fn(orc, gs, counts, first_sg=5, mu=mu))
+        want = np.concatenate(fn(orc, pre, counts, first_sg=5))
+        assert np.array_equal(got, want), fn.__name__
+        assert not np.array_equal(got, np.concatenate(fn(orc, gs, counts, first_sg=5)))
+
+
+def test_mean_subtraction_removes_a_common_offset_from_the_error():
+    """Entries c + noise: without the mean the 4-bit error is relative to c, with it to the noise."""
+    n, J = 4, 8
+    rng = np.random.default_rng(23)
+    gs = [(1.0 + rng.standard_normal(J * 256) * 1e-2).astype(np.float32) for _ in range(n)]
+    mu = np.mean([g.reshape(J, 256).mean(axis=1) for g in gs], axis=0).astype(np.float32)
+    orc = O.Oracle(n, seed=4)
+    truth = sum(g.astype(np.float64) for g in gs)
+    plain = np.concatenate(O.ring_reduce_scatter(orc, gs, [0, J, 0])).astype(np.float64)
+    normd = np.concatenate(O.ring_reduce_scatter(orc, gs, [0, J, 0], mu=mu)).astype(np.float64) + n * np.repeat(mu, 256).astype(np.float64)
+    e_plain = ((plain - truth) ** 2).sum()
+    e_normd = ((normd - truth) ** 2).sum()
+    assert e_normd < e_plain / 100
