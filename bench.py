@@ -27,12 +27,12 @@ sys.path.insert(0, ROOT)
 # 2^30 bytes on the same box: FETCH_SIZE counts half the bytes read (x2.0), WRITE_SIZE all of
 # them (x1.0).  Key: (workload, codec).  The summary with the commands sits in profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    (2, 0): int((16130.8 * 2.0 + 6227.1 * 1.0) * 1024),
+    (2, 0): int((16260.4 * 2.0 + 6237.2 * 1.0) * 1024),
 }
 # Vector-ALU wave instructions per DAR launch, from `rocprofv3 --pmc SQ_INSTS_VALU` on the same
 # command (profiles/); one wave instruction is 64 lane operations.
 MEASURED_VALU_WAVE_INSTR = {
-    (2, 0): 5_493_358,
+    (2, 0): 5_782_393,
 }
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: lane operations per second the vector ALUs can issue
 VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
@@ -45,6 +45,7 @@ def algorithmic_bytes_per_entry(codec, counts_total, n_sg_total, dtype_bytes, ki
     MX: 8/6/4-bit codes + one E8M0 byte per 32 entries."""
     if codec == 0:
         packed = (64 * counts_total[0] + 128 * counts_total[1] + 256 * counts_total[2] + 18 * n_sg_total) / (256.0 * n_sg_total)
+        dtype_bytes = dtype_bytes + 4.0 / 256.0  # one fp32 mean per super-group read beside the local entries
     else:
         packed = {1: 8, 2: 6, 3: 4}[codec] / 8.0 + 1.0 / 32.0
     if kind == "compress":
@@ -65,6 +66,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline (0 = skip)")
     ap.add_argument("--no-prepost", action="store_true",
                     help="skip the context timings of the steps before and after the main stage")
+    ap.add_argument("--no-mean", action="store_true",
+                    help="run the main stage without per-super-group means (the default subtracts them, Section 3.1)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, as the known-size reference row for HBM counters")
     args = ap.parse_args()
@@ -101,7 +104,17 @@ def main():
         counts = [entries // 256, 0, 0]
     n_sg = entries // 256
     ctx = B.Context(n, seed=20260208, round=0)
-    rp = B.Replay(ctx, topo, codec, grads, n_sg, [counts])
+    # the per-super-group means the main stage subtracts (Section 3.1), from the library's own
+    # statistics of the reordered gradients (untimed: the statistics exchange precedes the main stage)
+    mu_main = None
+    if codec == B.DQ_DYNAMIQ and not args.no_mean:
+        mu_all = torch.empty((n, n_sg), dtype=torch.float32, device=dev)
+        F_all = torch.empty((n, n_sg), dtype=torch.float32, device=dev)
+        for w in range(n):
+            B.dq_sg_stats(grads[w], mu_all[w], F_all[w])
+        mu_main, _ = B.dq_stats_combine(mu_all, F_all)
+        del mu_all, F_all
+    rp = B.Replay(ctx, topo, codec, grads, n_sg, [counts], mu=mu_main)
     n_steps = rp.n_steps
     infos = [rp.step_info(i) for i in range(n_steps)]
     hop_entries = sum(a + b for _, a, b in infos)  # entries handled by all launches of one replay
@@ -179,8 +192,8 @@ def main():
     }
 
     # ---- context only: the steps before and after the main stage on this workload's shape
-    # (statistics of every worker, their combination, allocation, mean-subtracting reorder of
-    # every worker, restore of the result), each timed with events over `reps` runs
+    # (statistics of every worker, their combination, allocation, reorder of every worker,
+    # restore of the result), each timed with events over `reps` runs
     prepost = None
     if codec == 0 and not args.no_prepost and wl.topology != "chain":
         import math
@@ -202,12 +215,15 @@ def main():
         def f_alloc():
             state["w"], state["pos"], state["counts"] = B.dq_allocate(state["F"], n_sg, budget)
 
+        def f_mean():
+            state["mu_main"] = B.dq_reorder_mean(state["mu"], state["pos"], n_sg, state["counts"])
+
         def f_reorder():
             for w in range(n):
-                B.dq_reorder(raw[w], state["pos"], n_sg, mu=state["mu"], out=re_out)
+                B.dq_reorder(raw[w], state["pos"], n_sg, out=re_out)
 
         def f_restore():
-            B.dq_restore(rp.out, state["pos"], n_sg, n, mu=state["mu"], out=final)
+            B.dq_restore(rp.out, state["pos"], n_sg, n, mu_main=state["mu_main"], out=final)
 
         def timed(fn):
             fn()
@@ -220,11 +236,12 @@ def main():
             b.synchronize()
             return a.elapsed_time(b) * 1e3 / reps
 
-        t_stats, t_comb, t_alloc, t_reo, t_res = timed(f_stats), timed(f_combine), timed(f_alloc), timed(f_reorder), timed(f_restore)
+        t_stats, t_comb, t_alloc, t_mean = timed(f_stats), timed(f_combine), timed(f_alloc), timed(f_mean)
+        t_reo, t_res = timed(f_reorder), timed(f_restore)
         c = state["counts"].cpu().numpy()[0]
         prepost = {
             "stats_us": round(t_stats, 1), "stats_GBps": round(n * entries * dtype_bytes / t_stats / 1e3, 1),
-            "combine_us": round(t_comb, 1), "allocate_us": round(t_alloc, 1),
+            "combine_us": round(t_comb, 1), "allocate_us": round(t_alloc, 1), "reorder_mean_us": round(t_mean, 1),
             "reorder_us": round(t_reo, 1), "reorder_GBps": round(n * entries * 2 * dtype_bytes / t_reo / 1e3, 1),
             "restore_us": round(t_res, 1), "restore_GBps": round(entries * 8 / t_res / 1e3, 1),
             "sg_by_width_2_4_8_gpu_allocation": [int(c[0]), int(c[1]), int(c[2])],   # W = {2,4,8}: c[3] (16-bit) is 0
@@ -254,17 +271,18 @@ def main():
             orc = O.Oracle(n, seed=20260208, round=0)
             pick = torch.cat([torch.arange(int(edges[w]), int(edges[w]) + cw[w]) for w in range(3)]).to(dev)
             sl = [workloads.to_numpy(g.reshape(-1, 256)[pick].reshape(-1)) for g in grads[:3]]
+            omu = None if mu_main is None else mu_main[pick].cpu().numpy()
         else:
             sl = [workloads.to_numpy(g[:sample_sg * 256]) for g in grads[:3]]
         if codec == 0:
-            msg = orc.compress(och, 0, sl[0])
+            msg = orc.compress(och, 0, sl[0], omu)
         else:
             msg = O.mx_compress(codec, sl[0])
         hops, t_cpu = 0, 0.0
         c0 = time.perf_counter()
         while True:
             if codec == 0:
-                msg = orc.dar_hop(och, 1 + (hops & 1), msg, sl[1 + (hops & 1)])
+                msg = orc.dar_hop(och, 1 + (hops & 1), msg, sl[1 + (hops & 1)], omu)
             else:
                 msg = O.mx_dar_hop(codec, msg, sl[1 + (hops & 1)])
             hops += 1
@@ -287,6 +305,7 @@ def main():
         "config": {"workload": wl.name, "topology": wl.topology, "simulated_workers": n, "entries_per_worker": entries,
                    "grad_dtype": wl.dtype, "codec": "dynamiq" if codec == 0 else {1: "mxfp8_e4m3", 2: "mxfp6_e3m2", 3: "mxfp4_e2m1"}[codec],
                    "budget_bits": wl.budget_bits if codec == 0 else None, "sg_by_width_2_4_8": counts if codec == 0 else None,
+                   "mean_subtraction": mu_main is not None,
                    "hop_steps_per_replay": n_steps, "entries_all_hops": hop_entries},
         "roofline": roofline,
         "prepost": prepost,

@@ -75,22 +75,30 @@ dq_status dq_set_round(dq_ctx *ctx, uint32_t round);
 /* Bytes of the packed form of a chunk (pure; layout above). */
 size_t dq_packed_bytes(const dq_chunk *chunk);
 
+/* The three calls below take `mu_or_null`: NULL, or one fp32 mean per super-group of the chunk
+ * (device, 4-byte aligned, in the chunk's order).  Section 3.1: every worker subtracts mu_j from
+ * each entry of super-group j before it is quantized; here that is one fp32 subtraction on the
+ * widened local entry, done where the entry enters the main stage, for every width (callers pass
+ * zero for the 16-bit super-groups: see dq_reorder_mean).  Pass NULL when `local` is not a
+ * worker's own gradient but a buffer of sums whose means are already off. */
+
 /* Leaf node of the aggregation topology (Section 3.4 "Fused kernels", kernel 1 of Section 4):
- * quantize the local chunk.  local: chunk entries, contiguous, `dtype`.  rank: the worker
- * doing the compression (0..n_workers-1).  packed_out: dq_packed_bytes(chunk) bytes. */
-dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const dq_chunk *chunk, uint32_t rank,
-                      void *packed_out, void *hip_stream);
+ * quantize the local chunk (minus its means).  local: chunk entries, contiguous, `dtype`.  rank:
+ * the worker doing the compression (0..n_workers-1).  packed_out: dq_packed_bytes(chunk) bytes. */
+dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const float *mu_or_null, const dq_chunk *chunk,
+                      uint32_t rank, void *packed_out, void *hip_stream);
 
 /* Internal node (kernel 3 of Section 4): decode the received partial sum, add the local
- * slice, re-quantize; intermediates never leave registers.  packed_out may alias packed_in. */
-dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const dq_chunk *chunk,
-                     uint32_t rank, void *packed_out, void *hip_stream);
+ * slice (minus its means), re-quantize; intermediates never leave registers.  packed_out may
+ * alias packed_in. */
+dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const float *mu_or_null,
+                     const dq_chunk *chunk, uint32_t rank, void *packed_out, void *hip_stream);
 
 /* Sink of the reduce-scatter, non-last parents of a butterfly node, all-gather receivers
- * (kernels 2 and 4 of Section 4): out = decode(packed_in) [+ local].  local_or_null may be
- * NULL (then dtype is ignored); out (fp32, one per entry) may alias an fp32 local. */
+ * (kernels 2 and 4 of Section 4): out = decode(packed_in) [+ (local - mu)].  local_or_null may be
+ * NULL (then dtype and mu_or_null are ignored); out (fp32, one per entry) may alias an fp32 local. */
 dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
-                        const dq_chunk *chunk, float *out, void *hip_stream);
+                        const float *mu_or_null, const dq_chunk *chunk, float *out, void *hip_stream);
 
 /* ---- OCP Microscaling comparison codec (blocks of 32, E8M0 shared scale, elements
  * E4M3 / E3M2 / E2M1, round-to-nearest-even, saturating; the formats the paper compares
@@ -130,7 +138,11 @@ typedef struct {
   uint64_t n_sg_bucket;
   const uint32_t *n_sg_by_width; /* host, [n_buckets][4]: SGs at 2, 4, 8, 16 bits per bucket */
   uint64_t first_sg;
-  uint32_t all_gather; /* 0: reduce-scatter only; 1: append the all-gather phase (see below) */
+  uint32_t all_gather; /* 0: reduce-scatter only; 1: append the all-gather phase (see above) */
+  const float *mu;     /* device, NULL or [n_buckets][n_sg_bucket] means in reordered order (Section 3.1),
+                          the same for every worker: taken off each worker's gradient where it enters a
+                          kernel, never off an fp32 buffer of sums; `out` is then the sum of the
+                          mean-subtracted entries.  DQ_DYNAMIQ only; must stay valid like scratch. */
 } dq_replay_desc;
 
 /* Device scratch the replay needs (job tables, packed messages, fp32 keep-buffers). */
@@ -189,17 +201,25 @@ dq_status dq_stats_combine(const float *mu_all, const float *F_all, uint32_t n_w
 dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
                       uint32_t max_width, uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream);
 
-/* Sections 3.1 and 3.5: out[super-group pos[j] of the bucket] = x[super-group j] - mu[j], the
- * subtraction in fp32, the result stored in x's dtype (bf16: nearest even).  mu_or_null NULL:
- * a plain permutation.  out must not overlap x.  At most 2^24 super-groups per bucket and
- * 65535 buckets (DQ_EUNSUPPORTED beyond). */
-dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, const float *mu_or_null,
-                     uint32_t n_sg_per_bucket, uint32_t n_buckets, void *out, void *hip_stream);
+/* Section 3.5: out[super-group pos[j] of the bucket] = x[super-group j]: whole super-groups
+ * copied into increasing-width order.  out must not overlap x.  At most 2^24 super-groups per
+ * bucket and 65535 buckets (DQ_EUNSUPPORTED beyond). */
+dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, uint32_t n_sg_per_bucket, uint32_t n_buckets,
+                     void *out, void *hip_stream);
 
-/* Section 3.4, last paragraph: out[super-group j] = sum[super-group pos[j]] + n_workers * mu[j]
- * (fp32; `sum` is the main stage's result in reordered order, a sum over the workers of
- * mean-subtracted entries).  mu_or_null NULL: only the permutation is undone. */
-dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_or_null, uint32_t n_workers,
+/* Section 3.1: the means the main stage subtracts, in its (reordered) order:
+ * mu_main[pos[j]] = mu[j], except that the 16-bit super-groups of a bucket -- its last
+ * counts[5b + 3] places, `counts` being what dq_allocate wrote -- get zero: a value sent as raw
+ * bf16 gains nothing from the subtraction, and rounding x - mu back to bf16 would make all
+ * workers err the same way.  counts_or_null NULL: no 16-bit class.  mu_main must not be mu. */
+dq_status dq_reorder_mean(const float *mu, const uint32_t *pos, const uint32_t *counts_or_null,
+                          uint32_t n_sg_per_bucket, uint32_t n_buckets, float *mu_main, void *hip_stream);
+
+/* Section 3.4, last paragraph: out[super-group j] = sum[super-group pos[j]] + n_workers *
+ * mu_main[pos[j]] (fp32: one product per super-group, one addition per entry; `sum` is the main
+ * stage's result in reordered order, a sum over the workers of mean-subtracted entries, mu_main
+ * what dq_reorder_mean wrote).  mu_main_or_null NULL: only the permutation is undone. */
+dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_main_or_null, uint32_t n_workers,
                      uint32_t n_sg_per_bucket, uint32_t n_buckets, float *out, void *hip_stream);
 
 /* ---- Block-wise pipelining (Section 4, "RDMA engine": as soon as a gradient block completes its
@@ -209,15 +229,16 @@ dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_or_n
  * at a multiple of 256 bytes: dq_pipelined_wire_bytes in all.  Block i is (re-)encoded on
  * compute_stream into one half of `stage` (dq_pipelined_stage_bytes, two blocks) and copied from
  * there to its place in wire_out on copy_stream -- a device-to-device copy standing in for the
- * network -- while block i+1 is being encoded.  wire_in NULL: the first hop (compress).  The two
+ * network -- while block i+1 is being encoded.  wire_in NULL: the first hop (compress).  mu_or_null:
+ * as for dq_dar_hop, one mean per super-group of the whole chunk.  The two
  * streams must differ; when the call returns, compute_stream has been made to wait for the last
  * copies, so synchronising it is enough.  Events are created inside the context at the first call;
  * one pipelined call at a time per context. */
 size_t dq_pipelined_wire_bytes(const dq_chunk *chunk, uint32_t block_sg);
 size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg);
 dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *local, dq_dtype dtype,
-                               const dq_chunk *chunk, uint32_t rank, uint32_t block_sg, void *stage, void *wire_out,
-                               void *compute_stream, void *copy_stream);
+                               const float *mu_or_null, const dq_chunk *chunk, uint32_t rank, uint32_t block_sg,
+                               void *stage, void *wire_out, void *compute_stream, void *copy_stream);
 
 const char *dq_status_str(dq_status s);
 /* Last HIP error string seen by this library on the calling thread (for DQ_EHIP). */

@@ -1,6 +1,7 @@
 """The whole simulated all-reduce of one bucket set on one GPU, as a sequence of boundary calls:
-statistics -> their combination -> bit allocation -> mean-subtracting reorder -> hop replay
-(reduce-scatter, optionally the all-gather) -> restore (Sections 3.1-3.4).  Host glue only:
+statistics -> their combination -> bit allocation -> reorder -> hop replay (reduce-scatter with
+the means subtracted where the gradients enter, optionally the all-gather) -> restore
+(Sections 3.1-3.4).  Host glue only:
 every step runs in the library's kernels.  Also the error measure the paper reports."""
 import math
 
@@ -52,6 +53,7 @@ def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.D
     mu, F = B.dq_stats_combine(mu_all, F_all)
     if not subtract_mean:
         mu = None
+    counts = None
     if uniform_width is None:
         budget = int(math.floor(prep.code_bits(budget_bits) * J))
         widths, pos, counts = B.dq_allocate(F, J, budget, max_width=max_width)
@@ -61,8 +63,12 @@ def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.D
         row = [0, 0, 0, 0]
         row[{2: 0, 4: 1, 8: 2, 16: 3}[uniform_width]] = J
         by_width = [row] * nb
-    reordered = [B.dq_reorder(g, pos, J, mu=mu) for g in worker_grads]
-    rp = B.Replay(ctx, topology, B.DQ_DYNAMIQ, reordered, J, by_width, n_buckets=nb, all_gather=all_gather)
+        if uniform_width == 16:
+            mu = None                                    # uncompressed super-groups are not normalized
+    mu_main = None if mu is None else B.dq_reorder_mean(mu, pos, J, counts)
+    reordered = [B.dq_reorder(g, pos, J) for g in worker_grads]
+    rp = B.Replay(ctx, topology, B.DQ_DYNAMIQ, reordered, J, by_width, n_buckets=nb, all_gather=all_gather,
+                  mu=mu_main)
     rp.run()
-    out = B.dq_restore(rp.out, pos, J, n, mu=mu)
+    out = B.dq_restore(rp.out, pos, J, n, mu_main=mu_main)
     return out, {"sg_by_width": by_width, "replay_steps": rp.n_steps}

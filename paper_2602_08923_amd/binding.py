@@ -23,7 +23,7 @@ EXPORTS = [
     "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_run_steps",
     "dq_replay_step_info",
     "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
-    "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_reorder", "dq_restore",
+    "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_reorder", "dq_reorder_mean", "dq_restore",
     "dq_pipelined_wire_bytes", "dq_pipelined_stage_bytes", "dq_dar_hop_pipelined",
 ]
 
@@ -44,7 +44,7 @@ class Chunk(C.Structure):
 class ReplayDesc(C.Structure):
     _fields_ = [("topology", C.c_int), ("codec", C.c_int), ("dtype", C.c_int), ("n_buckets", C.c_uint32),
                 ("n_sg_bucket", C.c_uint64), ("n_sg_by_width", C.POINTER(C.c_uint32)), ("first_sg", C.c_uint64),
-                ("all_gather", C.c_uint32)]
+                ("all_gather", C.c_uint32), ("mu", C.c_void_p)]
 
 
 _lib = None
@@ -65,9 +65,9 @@ def lib():
         L.dq_set_round.argtypes = [vp, u32]
         L.dq_packed_bytes.argtypes = [C.POINTER(Chunk)]
         L.dq_packed_bytes.restype = C.c_size_t
-        L.dq_compress.argtypes = [vp, vp, i, C.POINTER(Chunk), u32, vp, vp]
-        L.dq_dar_hop.argtypes = [vp, vp, vp, i, C.POINTER(Chunk), u32, vp, vp]
-        L.dq_decompress.argtypes = [vp, vp, vp, i, C.POINTER(Chunk), vp, vp]
+        L.dq_compress.argtypes = [vp, vp, i, vp, C.POINTER(Chunk), u32, vp, vp]
+        L.dq_dar_hop.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), u32, vp, vp]
+        L.dq_decompress.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), vp, vp]
         L.dq_status_str.argtypes = [i]
         L.dq_status_str.restype = C.c_char_p
         L.dq_last_hip_error.restype = C.c_char_p
@@ -89,13 +89,14 @@ def lib():
         L.dq_sg_stats.argtypes = [vp, i, u64, vp, vp, vp]
         L.dq_stats_combine.argtypes = [vp, vp, u32, u64, vp, vp, vp]
         L.dq_allocate.argtypes = [vp, u32, u32, u64, u32, vp, vp, vp, vp]
-        L.dq_reorder.argtypes = [vp, i, vp, vp, u32, u32, vp, vp]
+        L.dq_reorder.argtypes = [vp, i, vp, u32, u32, vp, vp]
+        L.dq_reorder_mean.argtypes = [vp, vp, vp, u32, u32, vp, vp]
         L.dq_restore.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp]
         L.dq_pipelined_wire_bytes.argtypes = [C.POINTER(Chunk), u32]
         L.dq_pipelined_wire_bytes.restype = C.c_size_t
         L.dq_pipelined_stage_bytes.argtypes = [C.POINTER(Chunk), u32]
         L.dq_pipelined_stage_bytes.restype = C.c_size_t
-        L.dq_dar_hop_pipelined.argtypes = [vp, vp, vp, i, C.POINTER(Chunk), u32, u32, vp, vp, vp, vp]
+        L.dq_dar_hop_pipelined.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), u32, u32, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -145,6 +146,13 @@ def _entries(chunk):
     return sum(chunk.n_sg) * 256
 
 
+def _mean(mu, chunk):
+    """The chunk's per-super-group means (float32, one each) or None."""
+    if mu is not None and (mu.dtype != torch.float32 or mu.numel() != sum(chunk.n_sg)):
+        raise DqError("mu is float32, one per super-group of the chunk")
+    return mu
+
+
 class Context:
     """dq_ctx: level tables on the device + PRNG key (seed, round) + worker count."""
 
@@ -164,28 +172,29 @@ class Context:
     def set_round(self, r):
         _check(lib().dq_set_round(self.h, r))
 
-    def dq_compress(self, local, chunk, rank, packed_out=None):
+    def dq_compress(self, local, chunk, rank, packed_out=None, mu=None):
         if local.numel() != _entries(chunk):
             raise DqError("local slice does not match the chunk")
         if packed_out is None:
             packed_out = torch.zeros(dq_packed_bytes(chunk), dtype=torch.uint8, device=local.device)
         if packed_out.numel() < dq_packed_bytes(chunk):
             raise DqError("packed_out too small")
-        _check(lib().dq_compress(self.h, _ptr(local), _dtype(local), C.byref(chunk), rank, _ptr(packed_out), _stream()))
+        _check(lib().dq_compress(self.h, _ptr(local), _dtype(local), _ptr(_mean(mu, chunk)), C.byref(chunk), rank,
+                                 _ptr(packed_out), _stream()))
         return packed_out
 
-    def dq_dar_hop(self, packed_in, local, chunk, rank, packed_out=None):
+    def dq_dar_hop(self, packed_in, local, chunk, rank, packed_out=None, mu=None):
         if local.numel() != _entries(chunk) or packed_in.numel() < dq_packed_bytes(chunk):
             raise DqError("buffers do not match the chunk")
         if packed_out is None:
             packed_out = torch.zeros(dq_packed_bytes(chunk), dtype=torch.uint8, device=local.device)
         if packed_out.numel() < dq_packed_bytes(chunk):
             raise DqError("packed_out too small")
-        _check(lib().dq_dar_hop(self.h, _ptr(packed_in), _ptr(local), _dtype(local), C.byref(chunk), rank,
-                                _ptr(packed_out), _stream()))
+        _check(lib().dq_dar_hop(self.h, _ptr(packed_in), _ptr(local), _dtype(local), _ptr(_mean(mu, chunk)),
+                                C.byref(chunk), rank, _ptr(packed_out), _stream()))
         return packed_out
 
-    def dq_decompress(self, packed_in, chunk, local=None, out=None):
+    def dq_decompress(self, packed_in, chunk, local=None, out=None, mu=None):
         if packed_in.numel() < dq_packed_bytes(chunk) or (local is not None and local.numel() != _entries(chunk)):
             raise DqError("buffers do not match the chunk")
         if out is None:
@@ -193,7 +202,7 @@ class Context:
         if out.numel() != _entries(chunk) or out.dtype != torch.float32:
             raise DqError("out must be float32 with one element per entry")
         _check(lib().dq_decompress(self.h, _ptr(packed_in), _ptr(local), 0 if local is None else _dtype(local),
-                                   C.byref(chunk), _ptr(out), _stream()))
+                                   _ptr(_mean(mu, chunk)), C.byref(chunk), _ptr(out), _stream()))
         return out
 
 
@@ -237,8 +246,12 @@ class Replay:
     """dq_replay: a prepared ring / butterfly / chain schedule over N simulated workers."""
 
     def __init__(self, ctx, topology, codec, worker_grads, n_sg_bucket, n_sg_by_width=None, n_buckets=1, first_sg=0,
-                 all_gather=False):
+                 all_gather=False, mu=None):
+        """mu: None, or the float32 means of all n_buckets * n_sg_bucket super-groups in reordered order."""
         self.ctx = ctx
+        self.mu = mu
+        if mu is not None and (mu.dtype != torch.float32 or mu.numel() != n_buckets * n_sg_bucket):
+            raise DqError("mu is float32, one per super-group")
         self.grads = list(worker_grads)
         dev = self.grads[0].device
         n = len(self.grads)
@@ -249,7 +262,7 @@ class Replay:
                     flat[4 * b + k] = int(n_sg_by_width[b][k])
         self._widths = flat
         desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg,
-                          1 if all_gather else 0)
+                          1 if all_gather else 0, _ptr(mu))
         self.desc = desc
         entries = n_sg_bucket * 256 * n_buckets
         for g in self.grads:
@@ -329,27 +342,39 @@ def dq_allocate(F, n_sg_per_bucket, max_code_bits, max_width=8):
     return widths, pos, counts
 
 
-def dq_reorder(x, pos, n_sg_per_bucket, mu=None, out=None):
+def dq_reorder(x, pos, n_sg_per_bucket, out=None):
     nb = pos.numel() // n_sg_per_bucket
     if x.numel() != pos.numel() * 256 or pos.numel() % n_sg_per_bucket or pos.dtype != torch.int32:
         raise DqError("x holds 256 entries per position; positions are int32, a whole number of buckets")
-    if mu is not None and (mu.dtype != torch.float32 or mu.numel() != pos.numel()):
-        raise DqError("mu is float32, one per super-group")
     if out is None:
         out = torch.empty_like(x)
-    _check(lib().dq_reorder(_ptr(x), _dtype(x), _ptr(pos), _ptr(mu), n_sg_per_bucket, nb, _ptr(out), _stream()))
+    _check(lib().dq_reorder(_ptr(x), _dtype(x), _ptr(pos), n_sg_per_bucket, nb, _ptr(out), _stream()))
     return out
 
 
-def dq_restore(total, pos, n_sg_per_bucket, n_workers, mu=None, out=None):
+def dq_reorder_mean(mu, pos, n_sg_per_bucket, counts=None, out=None):
+    """The means the main stage subtracts, in reordered order (zero for 16-bit super-groups).
+    counts: what dq_allocate returned (int32 [n_buckets, 5]) or None (no 16-bit class)."""
+    nb = pos.numel() // n_sg_per_bucket
+    if mu.dtype != torch.float32 or mu.numel() != pos.numel() or pos.numel() % n_sg_per_bucket or pos.dtype != torch.int32:
+        raise DqError("mu is float32, one per position; positions are int32, a whole number of buckets")
+    if counts is not None and (counts.dtype != torch.int32 or counts.numel() != 5 * nb):
+        raise DqError("counts is int32 [n_buckets, 5]")
+    if out is None:
+        out = torch.empty_like(mu)
+    _check(lib().dq_reorder_mean(_ptr(mu), _ptr(pos), _ptr(counts), n_sg_per_bucket, nb, _ptr(out), _stream()))
+    return out
+
+
+def dq_restore(total, pos, n_sg_per_bucket, n_workers, mu_main=None, out=None):
     nb = pos.numel() // n_sg_per_bucket
     if total.dtype != torch.float32 or total.numel() != pos.numel() * 256 or pos.dtype != torch.int32:
         raise DqError("the main stage's result is float32, 256 entries per position")
-    if mu is not None and (mu.dtype != torch.float32 or mu.numel() != pos.numel()):
-        raise DqError("mu is float32, one per super-group")
+    if mu_main is not None and (mu_main.dtype != torch.float32 or mu_main.numel() != pos.numel()):
+        raise DqError("mu_main is float32, one per super-group")
     if out is None:
         out = torch.empty_like(total)
-    _check(lib().dq_restore(_ptr(total), _ptr(pos), _ptr(mu), n_workers, n_sg_per_bucket, nb, _ptr(out), _stream()))
+    _check(lib().dq_restore(_ptr(total), _ptr(pos), _ptr(mu_main), n_workers, n_sg_per_bucket, nb, _ptr(out), _stream()))
     return out
 
 
@@ -363,7 +388,7 @@ def dq_pipelined_stage_bytes(chunk, block_sg):
 
 
 def dq_dar_hop_pipelined(ctx, wire_in, local, chunk, rank, block_sg, compute_stream, copy_stream, stage=None,
-                         wire_out=None):
+                         wire_out=None, mu=None):
     """One hop of a chunk in blocks of block_sg super-groups: block i is encoded on compute_stream
     while block i-1 travels (a device copy) on copy_stream.  wire_in None: the first hop."""
     dev = local.device
@@ -372,7 +397,8 @@ def dq_dar_hop_pipelined(ctx, wire_in, local, chunk, rank, block_sg, compute_str
         stage = torch.zeros(dq_pipelined_stage_bytes(chunk, block_sg), dtype=torch.uint8, device=dev)
     if wire_out is None:
         wire_out = torch.zeros(dq_pipelined_wire_bytes(chunk, block_sg), dtype=torch.uint8, device=dev)
-    _check(lib().dq_dar_hop_pipelined(ctx.h, _ptr(wire_in), _ptr(local), _dtype(local), C.byref(chunk), rank, block_sg,
+    _check(lib().dq_dar_hop_pipelined(ctx.h, _ptr(wire_in), _ptr(local), _dtype(local), _ptr(_mean(mu, chunk)),
+                                      C.byref(chunk), rank, block_sg,
                                       _ptr(stage), _ptr(wire_out), C.c_void_p(compute_stream.cuda_stream),
                                       C.c_void_p(copy_stream.cuda_stream)))
     return wire_out

@@ -88,6 +88,7 @@ void append_aligned(std::vector<uint32_t> &blob, const std::vector<uint32_t> &pa
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
 uint64_t chunk_sgs(const dq_chunk *ch) { return (uint64_t)ch->n_sg[0] + ch->n_sg[1] + ch->n_sg[2] + ch->n_sg[3]; }
 
@@ -268,41 +269,41 @@ size_t dq_packed_bytes(const dq_chunk *ch) {
   return (sz + 15) & ~(size_t)15;
 }
 
-dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const dq_chunk *chunk, uint32_t rank,
-                      void *packed_out, void *hip_stream) {
+dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const float *mu_or_null, const dq_chunk *chunk,
+                      uint32_t rank, void *packed_out, void *hip_stream) {
   dq_status st = check_chunk(ctx, chunk, rank);
   if (st != DQ_OK) return st;
   if (chunk_sgs(chunk) == 0) return DQ_OK;  // nothing to do
   if (!local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
-  if (!aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
-  dq::Job j{nullptr, local, packed_out, chunk->first_sg, {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, rank};
+  if (!aligned16(local) || !aligned16(packed_out) || !aligned4(mu_or_null)) return DQ_EALIGN;
+  dq::Job j{nullptr, local, mu_or_null, packed_out, chunk->first_sg, {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, rank};
   return hip_ok(dq::launch_one(dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream))
              ? DQ_OK
              : DQ_EHIP;
 }
 
-dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const dq_chunk *chunk,
-                     uint32_t rank, void *packed_out, void *hip_stream) {
+dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const float *mu_or_null,
+                     const dq_chunk *chunk, uint32_t rank, void *packed_out, void *hip_stream) {
   dq_status st = check_chunk(ctx, chunk, rank);
   if (st != DQ_OK) return st;
   if (chunk_sgs(chunk) == 0) return DQ_OK;
   if (!packed_in || !local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
-  if (!aligned16(packed_in) || !aligned16(local) || !aligned16(packed_out)) return DQ_EALIGN;
-  dq::Job j{(const uint8_t *)packed_in, local, packed_out, chunk->first_sg,
+  if (!aligned16(packed_in) || !aligned16(local) || !aligned16(packed_out) || !aligned4(mu_or_null)) return DQ_EALIGN;
+  dq::Job j{(const uint8_t *)packed_in, local, mu_or_null, packed_out, chunk->first_sg,
             {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, rank};
   return hip_ok(dq::launch_one(dq::kDar, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream)) ? DQ_OK
                                                                                                           : DQ_EHIP;
 }
 
 dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
-                        const dq_chunk *chunk, float *out, void *hip_stream) {
+                        const float *mu_or_null, const dq_chunk *chunk, float *out, void *hip_stream) {
   dq_status st = check_chunk(ctx, chunk, 0);
   if (st != DQ_OK) return st;
   if (chunk_sgs(chunk) == 0) return DQ_OK;
   if (!packed_in || !out) return DQ_EINVAL;
   if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
-  if (!aligned16(packed_in) || !aligned16(out) || !aligned16(local_or_null)) return DQ_EALIGN;
-  dq::Job j{(const uint8_t *)packed_in, local_or_null, out, chunk->first_sg,
+  if (!aligned16(packed_in) || !aligned16(out) || !aligned16(local_or_null) || !aligned4(mu_or_null)) return DQ_EALIGN;
+  dq::Job j{(const uint8_t *)packed_in, local_or_null, local_or_null ? mu_or_null : nullptr, out, chunk->first_sg,
             {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, 0};
   return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->grid_blocks,
                                (hipStream_t)hip_stream))
@@ -359,16 +360,17 @@ size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg) {
   return 2 * biggest;
 }
 
-dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *local, dq_dtype dtype, const dq_chunk *chunk,
-                               uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
-                               void *copy_stream) {
+dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *local, dq_dtype dtype,
+                               const float *mu_or_null, const dq_chunk *chunk, uint32_t rank, uint32_t block_sg,
+                               void *stage, void *wire_out, void *compute_stream, void *copy_stream) {
   dq_status st = check_chunk(ctx, chunk, rank);
   if (st != DQ_OK) return st;
   const uint64_t n = chunk_sgs(chunk);
   if (n == 0) return DQ_OK;
   if (!local || !stage || !wire_out || block_sg == 0 || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
   if (compute_stream == copy_stream) return DQ_EINVAL;  // the overlap needs two streams
-  if (!aligned16(wire_in) || !aligned16(local) || !aligned16(stage) || !aligned16(wire_out)) return DQ_EALIGN;
+  if (!aligned16(wire_in) || !aligned16(local) || !aligned16(stage) || !aligned16(wire_out) || !aligned4(mu_or_null))
+    return DQ_EALIGN;
   hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
   if (!ctx->have_events) {
     for (int i = 0; i < 2; ++i)
@@ -392,7 +394,8 @@ dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *loc
     // or a block would carry bytes of the one that used this half before
     if (bytes >= 16 && !hip_ok(hipMemsetAsync(stg + bytes - 16, 0, 16, cs))) return DQ_EHIP;
     dq::Job j{wire_in ? static_cast<const uint8_t *>(wire_in) + wire_off : nullptr,
-              static_cast<const uint8_t *>(local) + b * (uint64_t)block_sg * 256 * es, stg, blk.first_sg,
+              static_cast<const uint8_t *>(local) + b * (uint64_t)block_sg * 256 * es,
+              mu_or_null ? mu_or_null + b * (uint64_t)block_sg : nullptr, stg, blk.first_sg,
               {blk.n_sg[0], blk.n_sg[1], blk.n_sg[2], blk.n_sg[3]}, rank};
     if (!hip_ok(dq::launch_one(wire_in ? dq::kDar : dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, cs)))
       return DQ_EHIP;

@@ -20,6 +20,7 @@ constexpr uint32_t kMaxGridRows = 65535;  // documented limit of gridDim.y
 struct Job {
   const uint8_t *in;   // packed partial sum (DAR, decompress) or nullptr (compress)
   const void *local;   // local slice, may be nullptr for decompress
+  const float *mu;     // one mean per super-group of the chunk, taken off the local entries, or nullptr
   void *out;           // packed (compress, DAR) or fp32 (decompress)
   uint64_t first_sg;   // global index of the chunk's first super-group
   uint32_t n_sg[4];    // super-groups at 2, 4, 8 and 16 bits

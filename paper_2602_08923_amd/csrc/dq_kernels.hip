@@ -199,10 +199,24 @@ __device__ __forceinline__ float c255_over_sf(uint32_t sfb, uint32_t rec0) {
   return sfb ? u2f(q - (((sfb >> 7) - 127u) << 23)) : 0.0f;
 }
 
+// Section 3.1: the mean of a super-group is subtracted from the local entries in fp32 where they
+// enter (one operation per entry on the widened value).  job.mu holds one mean per super-group
+// of the chunk, or is null.
+__device__ __forceinline__ float local_mean(const Job &job, size_t first_entry, uint32_t row) {
+  return job.mu ? gld<float>(job.mu + (first_entry / kSG) + row) : 0.0f;
+}
+__device__ __forceinline__ void subtract_mean(const Job &job, float mu, float (&v)[16]) {
+  if (job.mu) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = v[k] - mu;
+  }
+}
+
 // What one lane fetches for one tile of compress / DAR: raw words only.
 template <int B, Kind KIND, typename LT>
 struct Fetch {
   uint4 loc[sizeof(LT) == 4 ? 4 : 2];  // the lane's 16 local entries
+  float mu;                            // the mean to take off them (if the job has means)
   uint32_t cw[B / 2];                  // DAR: their incoming codes
   uint32_t rg_in, sf_in;               // DAR: incoming group scale (u8) and SG scale (bf16 pattern)
 };
@@ -223,6 +237,7 @@ __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePo
     f.loc[0] = gld16(p);
     f.loc[1] = gld16(p + 1);
   }
+  f.mu = local_mean(job, tb.first_entry, rowc);
   if constexpr (KIND == kDar) {
     const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
     if constexpr (B == 2) {
@@ -276,6 +291,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
       }
     }
   }
+  subtract_mean(job, f.mu, v);
 
   if constexpr (KIND == kDar) {
     // decode: sf_G = r_G * (sf_SG / 255); estimate = +-T[r] * sf_G, accumulated by one fma
@@ -463,6 +479,8 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
       }
     }
   }
+  float mu = 0.0f;
+  if constexpr (kHasLocal) mu = local_mean(job, tb.first_entry, rowc);
   uint32_t cw[W::words];
   const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
   if constexpr (B == 2) {
@@ -477,6 +495,8 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
   const uint32_t rg_in = gld<uint8_t>(job.in + tb.gs_off + lg);
   const uint32_t sf_in = gld<uint16_t>(job.in + tb.sf_off + rowc * 2);
   const float sfg = (float)rg_in * sf_over_255(sf_in, rec0);
+  // after every load of the tile has been issued: the branch would otherwise hold the later loads back
+  if constexpr (kHasLocal) subtract_mean(job, mu, v);
 #pragma unroll
   for (int j = 0; j < 2 * B; ++j) {  // one table entry per code byte
     const uint32_t byte = (cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
@@ -544,11 +564,19 @@ __device__ __forceinline__ void tile16(const Job &job, uint32_t xpose, const Til
       }
     }
   }
+  float mu = 0.0f;
+  if constexpr (kHasLocal) mu = local_mean(job, tb.first_entry, rowc);
+  uint4 in[2];
   if constexpr (KIND != kCompress) {
     const uint4 *p = reinterpret_cast<const uint4 *>(job.in + tb.code_off) + lg * 2;
+    in[0] = gld16(p);
+    in[1] = gld16(p + 1);
+  }
+  if constexpr (kHasLocal) subtract_mean(job, mu, v);  // after every load of the tile has been issued
+  if constexpr (KIND != kCompress) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const uint4 x = gld16(p + i);
+      const uint4 x = in[i];
       const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {

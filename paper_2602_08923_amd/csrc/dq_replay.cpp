@@ -16,6 +16,7 @@ namespace {
 struct HostJob {
   const uint8_t *in;
   const void *local;
+  const float *mu;
   void *out;
   uint64_t first_sg;
   uint32_t n_sg[4];
@@ -79,6 +80,8 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
   if (d->dtype != DQ_F32 && d->dtype != DQ_BF16) return DQ_EINVAL;
   if (n < 2 || d->n_buckets < 1 || d->n_sg_bucket < 1) return DQ_EINVAL;
   if (!mx && !d->n_sg_by_width) return DQ_EINVAL;
+  if (mx && d->mu) return DQ_EINVAL;  // the MX codec has no normalization
+  if (reinterpret_cast<uintptr_t>(d->mu) & 3u) return DQ_EALIGN;
   if (d->topology == DQ_CHAIN) {
     if (d->n_buckets != 1) return DQ_EINVAL;
   } else if (d->topology == DQ_RING || d->topology == DQ_BUTTERFLY) {
@@ -121,8 +124,11 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
   auto out_ptr = [&](uint32_t b, uint32_t c) -> float * {
     return out + (uint64_t)b * bucket_entries + (uint64_t)c * chunk_entries;
   };
-  auto mk = [&](const ChunkInfo &x, const uint8_t *in, const void *local, void *o, uint32_t rank) {
-    HostJob j{in, local, o, x.first_sg, {x.n_sg[0], x.n_sg[1], x.n_sg[2], x.n_sg[3]}, rank};
+  // raw: `local` is a worker's own gradient (its means are still to be taken off), not an fp32
+  // buffer of sums that already had them taken off
+  auto mk = [&](const ChunkInfo &x, const uint8_t *in, const void *local, bool raw, void *o, uint32_t rank) {
+    const float *mu = (raw && d->mu) ? d->mu + (x.first_sg - d->first_sg) : nullptr;
+    HostJob j{in, local, mu, o, x.first_sg, {x.n_sg[0], x.n_sg[1], x.n_sg[2], x.n_sg[3]}, rank};
     return j;
   };
 
@@ -153,7 +159,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
           const void *local = d->topology == DQ_CHAIN ? grad_ptr(w, 0, 0) : grad_ptr(w, b, c);
           const uint8_t *in = t == 0 ? nullptr : msg[(t - 1) & 1] + slot[i];
           void *o = t == n - 1 ? (void *)out_ptr(b, c) : (void *)(msg[t & 1] + slot[i]);
-          L.jobs.push_back(mk(ci[i], in, local, o, w));
+          L.jobs.push_back(mk(ci[i], in, local, true, o, w));
         }
       st.launches.push_back(std::move(L));
       plan->steps.push_back(std::move(st));
@@ -208,13 +214,13 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
             const ChunkInfo &x = ci[(size_t)b * n + c];
             const uint8_t *in = k == 1 ? nullptr : msg_ptr(k - 1, b, w, c);
             const void *local = k <= 2 ? grad_ptr(w, b, c) : (const void *)acc_ptr(w, b, c);
-            send.jobs.push_back(mk(x, in, local, msg_ptr(k, b, partner, c), w));
+            send.jobs.push_back(mk(x, in, local, k <= 2, msg_ptr(k, b, partner, c), w));
           }
           if (k >= 2)
             for (uint32_t c = klo; c < klo + half; ++c) {
               const ChunkInfo &x = ci[(size_t)b * n + c];
               const void *local = k == 2 ? grad_ptr(w, b, c) : (const void *)acc_ptr(w, b, c);
-              keep.jobs.push_back(mk(x, msg_ptr(k - 1, b, w, c), local, acc_ptr(w, b, c), w));
+              keep.jobs.push_back(mk(x, msg_ptr(k - 1, b, w, c), local, k == 2, acc_ptr(w, b, c), w));
             }
         }
       st.launches.push_back(std::move(send));
@@ -230,7 +236,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
       for (uint32_t w = 0; w < n; ++w) {
         const ChunkInfo &x = ci[(size_t)b * n + w];
         const void *local = Lg == 1 ? grad_ptr(w, b, w) : (const void *)acc_ptr(w, b, w);
-        fin.jobs.push_back(mk(x, msg_ptr(Lg, b, w, w), local, out_ptr(b, w), w));
+        fin.jobs.push_back(mk(x, msg_ptr(Lg, b, w, w), local, Lg == 1, out_ptr(b, w), w));
       }
     st.launches.push_back(std::move(fin));
     plan->steps.push_back(std::move(st));
@@ -260,8 +266,8 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
       for (uint32_t c = 0; c < n_chunks; ++c) {
         const size_t i = (size_t)b * n_chunks + c;
         const uint32_t sink = d->topology == DQ_CHAIN ? n - 1 : (d->topology == DQ_RING ? (c + n - 1) % n : c);
-        comp.jobs.push_back(mk(ci[i], nullptr, out_ptr(b, c), ag + slot[i], sink));
-        dec.jobs.push_back(mk(ci[i], ag + slot[i], nullptr, out_ptr(b, c), sink));
+        comp.jobs.push_back(mk(ci[i], nullptr, out_ptr(b, c), false, ag + slot[i], sink));
+        dec.jobs.push_back(mk(ci[i], ag + slot[i], nullptr, false, out_ptr(b, c), sink));
       }
     sc.launches.push_back(std::move(comp));
     sd.launches.push_back(std::move(dec));
@@ -343,7 +349,7 @@ dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *
         std::vector<dq::Job> t(L.jobs.size());
         for (size_t i = 0; i < t.size(); ++i) {
           const HostJob &j = L.jobs[i];
-          t[i] = dq::Job{j.in, j.local, j.out, j.first_sg, {j.n_sg[0], j.n_sg[1], j.n_sg[2], j.n_sg[3]}, j.rank};
+          t[i] = dq::Job{j.in, j.local, j.mu, j.out, j.first_sg, {j.n_sg[0], j.n_sg[1], j.n_sg[2], j.n_sg[3]}, j.rank};
         }
         e = hipMemcpy(r->scratch + L.table_off, t.data(), t.size() * sizeof(dq::Job), hipMemcpyHostToDevice);
       }

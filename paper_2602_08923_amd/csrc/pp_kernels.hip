@@ -468,51 +468,41 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
 // wave has 4 KB in flight.
 constexpr int kUnroll = 4;
 
-template <typename LT>
-__global__ void __launch_bounds__(kThreads) k_reorder(const void *x_all, const uint32_t *pos_all, const float *mu_all,
-                                                      uint32_t J, void *out_all) {
-  constexpr uint32_t pps = kSG * sizeof(LT) / 16;
+template <uint32_t PPS>  // 16-byte pieces per super-group: 64 (fp32) or 32 (bf16)
+__global__ void __launch_bounds__(kThreads) k_reorder(const void *x_all, const uint32_t *pos_all, uint32_t J, void *out_all) {
   const uint64_t bucket_first = (uint64_t)blockIdx.y * J;  // blockIdx.y = bucket
-  const uint8_t *x = static_cast<const uint8_t *>(x_all) + bucket_first * pps * 16;
-  uint8_t *out = static_cast<uint8_t *>(out_all) + bucket_first * pps * 16;
+  const uint8_t *x = static_cast<const uint8_t *>(x_all) + bucket_first * PPS * 16;
+  uint8_t *out = static_cast<uint8_t *>(out_all) + bucket_first * PPS * 16;
   const uint32_t *pos = pos_all + bucket_first;
-  const float *mu = mu_all ? mu_all + bucket_first : nullptr;
-  const uint32_t n_pieces = J * pps;
+  const uint32_t n_pieces = J * PPS;
   const uint32_t stride = gridDim.x * kThreads * kUnroll;
   for (uint32_t base = blockIdx.x * kThreads * kUnroll + threadIdx.x; base < n_pieces; base += stride) {
     u32x4 d[kUnroll];
     uint32_t dst[kUnroll];
-    float m[kUnroll];
 #pragma unroll
     for (int i = 0; i < kUnroll; ++i) {
       const uint32_t c = base + i * kThreads;
       if (c < n_pieces) {
-        const uint32_t sg = c / pps;
         d[i] = gld<u32x4>(x + (uint64_t)c * 16);
-        dst[i] = gld<uint32_t>(pos + sg) * pps + c % pps;
-        m[i] = mu ? gld<float>(mu + sg) : 0.0f;
+        dst[i] = gld<uint32_t>(pos + c / PPS) * PPS + c % PPS;
       }
     }
 #pragma unroll
-    for (int i = 0; i < kUnroll; ++i) {
-      const uint32_t c = base + i * kThreads;
-      if (c < n_pieces) {
-        const uint32_t w[4] = {d[i].x, d[i].y, d[i].z, d[i].w};
-        uint32_t r[4];
-        if constexpr (sizeof(LT) == 4) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) r[k] = f2u(u2f(w[k]) - m[i]);
-        } else {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const uint32_t lo = bf16_rne(u2f(w[k] << 16) - m[i]);
-            const uint32_t hi = bf16_rne(u2f(w[k] & 0xFFFF0000u) - m[i]);
-            r[k] = (lo & 0xFFFFu) | (hi << 16);
-          }
-        }
-        gst<u32x4>(out + (uint64_t)dst[i] * 16, u32x4{r[0], r[1], r[2], r[3]});
-      }
-    }
+    for (int i = 0; i < kUnroll; ++i)
+      if (base + i * kThreads < n_pieces) gst<u32x4>(out + (uint64_t)dst[i] * 16, d[i]);
+  }
+}
+
+// The means the main stage subtracts, in reordered order; zero for the 16-bit super-groups (the
+// last counts[5b + 3] places of bucket b).  One thread per super-group.
+__global__ void __launch_bounds__(kThreads) k_reorder_mean(const float *mu_all, const uint32_t *pos_all, const uint32_t *counts,
+                                                           uint32_t J, float *mu_main) {
+  const uint64_t bucket_first = (uint64_t)blockIdx.y * J;
+  const uint32_t n16 = counts ? gld<uint32_t>(counts + 5ull * blockIdx.y + 3) : 0u;
+  for (uint32_t j = blockIdx.x * kThreads + threadIdx.x; j < J; j += gridDim.x * kThreads) {
+    const uint32_t p = gld<uint32_t>(pos_all + bucket_first + j);
+    const float m = gld<float>(mu_all + bucket_first + j);
+    gst<float>(mu_main + bucket_first + p, (p < J - n16) ? m : 0.0f);
   }
 }
 
@@ -523,7 +513,7 @@ __global__ void __launch_bounds__(kThreads) k_restore(const float *sum_all, cons
   const uint8_t *sum = reinterpret_cast<const uint8_t *>(sum_all) + bucket_first * pps * 16;
   uint8_t *out = reinterpret_cast<uint8_t *>(out_all) + bucket_first * pps * 16;
   const uint32_t *pos = pos_all + bucket_first;
-  const float *mu = mu_all ? mu_all + bucket_first : nullptr;
+  const float *mu = mu_all ? mu_all + bucket_first : nullptr;  // in reordered order
   const uint32_t n_pieces = J * pps;
   const uint32_t stride = gridDim.x * kThreads * kUnroll;
   for (uint32_t base = blockIdx.x * kThreads * kUnroll + threadIdx.x; base < n_pieces; base += stride) {
@@ -533,10 +523,9 @@ __global__ void __launch_bounds__(kThreads) k_restore(const float *sum_all, cons
     for (int i = 0; i < kUnroll; ++i) {
       const uint32_t c = base + i * kThreads;
       if (c < n_pieces) {
-        const uint32_t sg = c / pps;
-        const uint32_t src = gld<uint32_t>(pos + sg) * pps + c % pps;
-        d[i] = gld<f32x4>(sum + (uint64_t)src * 16);
-        back[i] = mu ? n * gld<float>(mu + sg) : 0.0f;
+        const uint32_t p = gld<uint32_t>(pos + c / pps);
+        d[i] = gld<f32x4>(sum + ((uint64_t)p * pps + c % pps) * 16);
+        back[i] = mu ? n * gld<float>(mu + p) : 0.0f;
       }
     }
 #pragma unroll
@@ -606,31 +595,43 @@ dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_bucke
   return launched();
 }
 
-dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, const float *mu_or_null,
-                     uint32_t n_sg_per_bucket, uint32_t n_buckets, void *out, void *hip_stream) {
+dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, uint32_t n_sg_per_bucket, uint32_t n_buckets,
+                     void *out, void *hip_stream) {
   if (n_sg_per_bucket == 0 || n_buckets == 0) return DQ_OK;
   if (!x || !pos || !out || x == out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
   if (n_sg_per_bucket > (1u << 24) || n_buckets > 65535u) return DQ_EUNSUPPORTED;
-  if (!aligned(x, 16) || !aligned(out, 16) || !aligned(pos, 4) || !aligned(mu_or_null, 4)) return DQ_EALIGN;
+  if (!aligned(x, 16) || !aligned(out, 16) || !aligned(pos, 4)) return DQ_EALIGN;
   const uint64_t pieces = (uint64_t)n_sg_per_bucket * (dtype == DQ_F32 ? 64 : 32);
   const uint32_t blocks = stream_blocks((uint64_t)kThreads * kUnroll, pieces, n_buckets);
   hipStream_t s = (hipStream_t)hip_stream;
   if (dtype == DQ_F32)
-    hipLaunchKernelGGL(k_reorder<float>, dim3(blocks, n_buckets), dim3(kThreads), 0, s, x, pos, mu_or_null, n_sg_per_bucket, out);
+    hipLaunchKernelGGL(k_reorder<64>, dim3(blocks, n_buckets), dim3(kThreads), 0, s, x, pos, n_sg_per_bucket, out);
   else
-    hipLaunchKernelGGL(k_reorder<uint16_t>, dim3(blocks, n_buckets), dim3(kThreads), 0, s, x, pos, mu_or_null, n_sg_per_bucket, out);
+    hipLaunchKernelGGL(k_reorder<32>, dim3(blocks, n_buckets), dim3(kThreads), 0, s, x, pos, n_sg_per_bucket, out);
   return launched();
 }
 
-dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_or_null, uint32_t n_workers,
+dq_status dq_reorder_mean(const float *mu, const uint32_t *pos, const uint32_t *counts_or_null, uint32_t n_sg_per_bucket,
+                          uint32_t n_buckets, float *mu_main, void *hip_stream) {
+  if (n_sg_per_bucket == 0 || n_buckets == 0) return DQ_OK;
+  if (!mu || !pos || !mu_main || mu == mu_main) return DQ_EINVAL;
+  if (n_sg_per_bucket > (1u << 24) || n_buckets > 65535u) return DQ_EUNSUPPORTED;
+  if (!aligned(mu, 4) || !aligned(pos, 4) || !aligned(counts_or_null, 4) || !aligned(mu_main, 4)) return DQ_EALIGN;
+  const uint32_t blocks = stream_blocks(kThreads, n_sg_per_bucket, n_buckets);
+  hipLaunchKernelGGL(k_reorder_mean, dim3(blocks, n_buckets), dim3(kThreads), 0, (hipStream_t)hip_stream, mu, pos,
+                     counts_or_null, n_sg_per_bucket, mu_main);
+  return launched();
+}
+
+dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_main_or_null, uint32_t n_workers,
                      uint32_t n_sg_per_bucket, uint32_t n_buckets, float *out, void *hip_stream) {
   if (n_sg_per_bucket == 0 || n_buckets == 0) return DQ_OK;
   if (!sum || !pos || !out || sum == out || n_workers == 0) return DQ_EINVAL;
   if (n_sg_per_bucket > (1u << 24) || n_buckets > 65535u) return DQ_EUNSUPPORTED;
-  if (!aligned(sum, 16) || !aligned(out, 16) || !aligned(pos, 4) || !aligned(mu_or_null, 4)) return DQ_EALIGN;
+  if (!aligned(sum, 16) || !aligned(out, 16) || !aligned(pos, 4) || !aligned(mu_main_or_null, 4)) return DQ_EALIGN;
   const uint32_t blocks = stream_blocks((uint64_t)kThreads * kUnroll, (uint64_t)n_sg_per_bucket * 64, n_buckets);
-  hipLaunchKernelGGL(k_restore, dim3(blocks, n_buckets), dim3(kThreads), 0, (hipStream_t)hip_stream, sum, pos, mu_or_null,
-                     (float)n_workers, n_sg_per_bucket, out);
+  hipLaunchKernelGGL(k_restore, dim3(blocks, n_buckets), dim3(kThreads), 0, (hipStream_t)hip_stream, sum, pos,
+                     mu_main_or_null, (float)n_workers, n_sg_per_bucket, out);
   return launched();
 }
 

@@ -538,3 +538,93 @@ def test_pipelined_hops_match_blockwise_oracle(dev, block_sg):
     assert np.array_equal(host(wire), want)
     with pytest.raises(B.DqError):
         B.dq_dar_hop_pipelined(ctx, wire, to_dev(xs[0], dev), gch, 0, block_sg, s1, s1)     # one stream: no overlap possible
+
+
+# ----------------------------------------------------------------------------- mean subtraction (Section 3.1)
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_sg", [[5, 7, 3, 0], [1, 2, 1, 6], [0, 0, 13, 0], [9, 0, 0, 1]])
+def test_single_chunk_calls_with_means(dev, dtype, n_sg):
+    n, first, rank = 8, 1000, 3
+    total = sum(n_sg)
+    rng = np.random.default_rng(total)
+    a, b, c = (make_local(rng, total * 256, dtype) for _ in range(3))
+    mu = (rng.standard_normal(total) * 2e-4).astype(np.float32)
+    mu_t = torch.from_numpy(mu).to(dev)
+    orc, ctx = O.Oracle(n, seed=31, round=2), B.Context(n, seed=31, round=2)
+    och, gch = O.make_chunk(first, n_sg), B.make_chunk(first, n_sg)
+    w1 = orc.compress(och, rank, a, mu)
+    g1 = ctx.dq_compress(to_dev(a, dev), gch, rank, mu=mu_t)
+    assert np.array_equal(host(g1), w1)
+    assert not np.array_equal(w1, orc.compress(och, rank, a))
+    w2 = orc.dar_hop(och, rank + 1, w1, b, mu)
+    g2 = ctx.dq_dar_hop(g1, to_dev(b, dev), gch, rank + 1, mu=mu_t)
+    assert np.array_equal(host(g2), w2)
+    assert np.array_equal(host(ctx.dq_decompress(g2, gch, local=to_dev(c, dev), mu=mu_t)), orc.decompress(och, w2, c, mu))
+    assert np.array_equal(host(ctx.dq_decompress(g2, gch, mu=mu_t)), orc.decompress(och, w2))   # no local: means ignored
+    with pytest.raises(B.DqError):
+        ctx.dq_compress(to_dev(a, dev), gch, rank, mu=mu_t[:-1] if total > 1 else torch.zeros(2, device=dev))
+
+
+@pytest.mark.parametrize("topology,n", [("ring", 4), ("ring", 5), ("butterfly", 2), ("butterfly", 4), ("butterfly", 16)])
+def test_replay_with_means(dev, topology, n):
+    """The means are taken off every worker's raw gradient exactly once, never off a butterfly's fp32 buffers."""
+    J, buckets = 3 * n, 2
+    counts = [[n, n // 2, n, 3 * n - 2 * n - n // 2], [0, 2 * n, n, 0]]
+    rng = np.random.default_rng(n)
+    d = J * 256
+    grads = [make_local(rng, d * buckets, "bf16") for _ in range(n)]
+    mu = (rng.standard_normal(J * buckets) * 2e-4).astype(np.float32)
+    orc, ctx = O.Oracle(n, seed=9), B.Context(n, seed=9)
+    fn = O.ring_reduce_scatter if topology == "ring" else O.butterfly_reduce_scatter
+    want = []
+    for b in range(buckets):
+        rs = fn(orc, [g[b * d:(b + 1) * d] for g in grads], counts[b], first_sg=50 + b * J, mu=mu[b * J:(b + 1) * J])
+        want += O.all_gather(orc, rs, counts[b], topology, first_sg=50 + b * J)
+    topo = B.DQ_RING if topology == "ring" else B.DQ_BUTTERFLY
+    rp = B.Replay(ctx, topo, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], J, counts, n_buckets=buckets, first_sg=50,
+                  all_gather=True, mu=torch.from_numpy(mu).to(dev))
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), np.concatenate(want))
+
+
+def test_chain_and_pipelined_hops_with_means(dev):
+    n, n_sg, first = 4, [6, 9, 4, 3], 40
+    total = sum(n_sg)
+    rng = np.random.default_rng(3)
+    sl = [make_local(rng, total * 256, "bf16") for _ in range(n)]
+    mu = (rng.standard_normal(total) * 2e-4).astype(np.float32)
+    mu_t = torch.from_numpy(mu).to(dev)
+    orc, ctx = O.Oracle(n, seed=14), B.Context(n, seed=14)
+    och, gch = O.make_chunk(first, n_sg), B.make_chunk(first, n_sg)
+    msg = orc.compress(och, 0, sl[0], mu)
+    for i in (1, 2):
+        msg = orc.dar_hop(och, i, msg, sl[i], mu)
+    want = orc.decompress(och, msg, sl[3], mu)
+    rc = B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, [to_dev(s, dev) for s in sl], total, [n_sg], first_sg=first, mu=mu_t)
+    rc.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rc.out), want)
+    # block-wise: block i takes the means of its own super-groups
+    block_sg = 5
+    blocks = block_chunks(n_sg, block_sg, first)
+    msgs = [None] * len(blocks)
+    for hop in range(2):
+        for i, (lo, hi, ch) in enumerate(blocks):
+            x = sl[hop][lo * 256:hi * 256]
+            msgs[i] = orc.compress(ch, hop, x, mu[lo:hi]) if hop == 0 else orc.dar_hop(ch, hop, msgs[i], x, mu[lo:hi])
+    want = np.concatenate([np.concatenate([m, np.zeros((-len(m)) % 256, np.uint8)]) for m in msgs])
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    wire = None
+    for hop in range(2):
+        wire = B.dq_dar_hop_pipelined(ctx, wire, to_dev(sl[hop], dev), gch, hop, block_sg, s1, s2, mu=mu_t)
+        s1.synchronize()
+    assert np.array_equal(host(wire), want)
+
+
+def test_mx_replay_rejects_means(dev):
+    n = 2
+    grads = [torch.zeros(2 * 256, dtype=torch.float32, device=dev) for _ in range(n)]
+    with pytest.raises(B.DqError):
+        B.Replay(B.Context(n), B.DQ_RING, B.DQ_MXFP8_E4M3, grads, 2, mu=torch.zeros(2, device=dev))

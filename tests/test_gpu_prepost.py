@@ -166,22 +166,29 @@ def test_reorder_and_restore(dev, dtype, J, nb):
     n_sg = J * nb
     x = draw(2 if dtype == "bf16" else 1, 1, n_sg * 256)
     rng = np.random.default_rng(J)
-    widths = rng.choice(np.array([2, 4, 8], np.uint8), n_sg, p=[0.4, 0.4, 0.2])
-    pos = np.concatenate([P.positions(widths[b * J:(b + 1) * J])[0] for b in range(nb)])
+    widths = rng.choice(np.array([2, 4, 8, 16], np.uint8), n_sg, p=[0.4, 0.3, 0.2, 0.1])
+    pc = [P.positions(widths[b * J:(b + 1) * J]) for b in range(nb)]
+    pos = np.concatenate([p for p, _ in pc])
+    counts = np.array([c + [0] for _, c in pc], np.int32)                  # [nb, 5] as dq_allocate writes it
     mu = (rng.standard_normal(n_sg) * 1e-4).astype(f32)
     xn = as_np(x)
     pos_t = torch.from_numpy(pos.view(np.int32)).to(dev)
-    mu_t = torch.from_numpy(mu).to(dev)
-    for m, m_t in ((mu, mu_t), (None, None)):
-        want = np.concatenate([P.reorder(xn[b * J * 256:(b + 1) * J * 256], pos[b * J:(b + 1) * J],
-                                         None if m is None else m[b * J:(b + 1) * J]) for b in range(nb)])
-        got = B.dq_reorder(x.to(dev), pos_t, J, mu=m_t)
-        assert np.array_equal(as_np(got.cpu()), want)
+    want = np.concatenate([P.reorder(xn[b * J * 256:(b + 1) * J * 256], pos[b * J:(b + 1) * J]) for b in range(nb)])
+    got = B.dq_reorder(x.to(dev), pos_t, J)
+    assert np.array_equal(as_np(got.cpu()), want)
+    # the means of the main stage: reordered, zero for the 16-bit super-groups; without counts: all kept
+    for cnt in (counts, None):
+        want_mm = np.concatenate([P.reorder_mean(mu[b * J:(b + 1) * J], pos[b * J:(b + 1) * J],
+                                                 0 if cnt is None else cnt[b][3]) for b in range(nb)])
+        got_mm = B.dq_reorder_mean(torch.from_numpy(mu).to(dev), pos_t, J,
+                                   None if cnt is None else torch.from_numpy(cnt).to(dev))
+        assert np.array_equal(host(got_mm).view(np.uint32), want_mm.view(np.uint32))
     total = (rng.standard_normal(n_sg * 256) * 1e-2).astype(f32)
-    for m, m_t in ((mu, mu_t), (None, None)):
+    for m in (want_mm, None):
         want = np.concatenate([P.restore(total[b * J * 256:(b + 1) * J * 256], pos[b * J:(b + 1) * J],
                                          None if m is None else m[b * J:(b + 1) * J], 8) for b in range(nb)])
-        got = B.dq_restore(torch.from_numpy(total).to(dev), pos_t, J, 8, mu=m_t)
+        got = B.dq_restore(torch.from_numpy(total).to(dev), pos_t, J, 8,
+                           mu_main=None if m is None else torch.from_numpy(m).to(dev))
         assert np.array_equal(host(got).view(np.uint32), want.view(np.uint32))
 
 
@@ -195,24 +202,30 @@ def test_reorder_full_bucket(dev):
     w, _ = P.allocate(F, int(math.floor(prep.code_bits(wl.budget_bits) * J)))
     pos, counts = P.positions(w)
     assert counts[0] > 0 and counts[1] > 0
-    got = B.dq_reorder(x.to(dev), torch.from_numpy(pos.view(np.int32)).to(dev), J, mu=torch.from_numpy(mu).to(dev))
-    assert np.array_equal(as_np(got.cpu()), P.reorder(as_np(x), pos, mu))
+    pos_t = torch.from_numpy(pos.view(np.int32)).to(dev)
+    got = B.dq_reorder(x.to(dev), pos_t, J)
+    assert np.array_equal(as_np(got.cpu()), P.reorder(as_np(x), pos))
+    mm = P.reorder_mean(mu, pos, 0)
+    got_mm = B.dq_reorder_mean(torch.from_numpy(mu).to(dev), pos_t, J)
+    assert np.array_equal(host(got_mm).view(np.uint32), mm.view(np.uint32))
     total = got.float()
-    back = B.dq_restore(total, torch.from_numpy(pos.view(np.int32)).to(dev), J, 1, mu=torch.from_numpy(mu).to(dev))
-    assert np.array_equal(host(back).view(np.uint32), P.restore(host(total), pos, mu, 1).view(np.uint32))
-    # restoring what was reordered returns the gradient up to the bf16 rounding of x - mu
-    err = (back.cpu().double() - x.double()).abs().max().item()
-    assert err <= 2.0 ** -8 * x.double().abs().max().item()
+    back = B.dq_restore(total, pos_t, J, 1, mu_main=got_mm)
+    assert np.array_equal(host(back).view(np.uint32), P.restore(host(total), pos, mm, 1).view(np.uint32))
+    # the permutation alone is undone exactly
+    assert torch.equal(B.dq_restore(total, pos_t, J, 1).cpu(), x.float())
 
 
 def test_rejects_bad_arguments(dev):
     x = torch.zeros(512, dtype=torch.float32, device=dev)
     pos = torch.zeros(2, dtype=torch.int32, device=dev)
     L = B.lib()
-    st = L.dq_reorder(B._ptr(x), 0, B._ptr(pos), None, 2, 1, B._ptr(x), None)         # in place
+    st = L.dq_reorder(B._ptr(x), 0, B._ptr(pos), 2, 1, B._ptr(x), None)               # in place
     assert st == B.DQ_EINVAL
-    st = L.dq_reorder(x.data_ptr() + 4, 0, B._ptr(pos), None, 2, 1, B._ptr(torch.empty_like(x)), None)
+    st = L.dq_reorder(x.data_ptr() + 4, 0, B._ptr(pos), 2, 1, B._ptr(torch.empty_like(x)), None)
     assert st == B.DQ_EALIGN
+    mu = torch.zeros(2, dtype=torch.float32, device=dev)
+    st = L.dq_reorder_mean(B._ptr(mu), B._ptr(pos), None, 2, 1, B._ptr(mu), None)     # in place
+    assert st == B.DQ_EINVAL
     st = L.dq_restore(B._ptr(x), B._ptr(pos), None, 0, 2, 1, B._ptr(torch.empty_like(x)), None)   # n = 0
     assert st == B.DQ_EINVAL
     st = L.dq_sg_stats(B._ptr(x), 7, 2, B._ptr(x), B._ptr(x), None)                  # unknown dtype
@@ -236,11 +249,12 @@ def test_whole_pipeline_is_consistent(dev):
     assert sum(c[:4]) == J and budget - 6 < int(w.sum()) <= budget
     order = np.argsort(host(F), kind="stable")
     assert np.all(np.diff(w[order]) >= 0)
-    re = [B.dq_reorder(x, pos, J, mu=mu) for x in xs]
+    re = [B.dq_reorder(x, pos, J) for x in xs]
+    mu_main = B.dq_reorder_mean(mu, pos, J, counts)
     ctx = B.Context(n, seed=11)
-    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, re, J, [[int(v) for v in c[:3]]])
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, re, J, [[int(v) for v in c[:3]]], mu=mu_main)
     rp.run()
-    out = B.dq_restore(rp.out, pos, J, n, mu=mu)
+    out = B.dq_restore(rp.out, pos, J, n, mu_main=mu_main)
     true = sum(x.double() for x in xs)
     est = out.double()
     assert float(((est - true) ** 2).sum() / (true ** 2).sum()) < 0.05

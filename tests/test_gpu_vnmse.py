@@ -58,7 +58,7 @@ def test_rounds_draw_fresh_randomness_and_average_out(dev):
     """Unbiasedness at scale: the mean of the estimates of R rounds is far closer to the truth than
     one round.  Not quite 1/R: every hop's rounding is unbiased on its own, but the intervals of
     consecutive hops are tied by the shared permutation, which leaves a bias of a few percent of
-    one round's error energy (measured: 2-7 %), plus the deterministic bf16 rounding of the reorder."""
+    one round's error energy."""
     J, n, R = 1024, 8, 16
     M = workloads.mixture_magnitudes(J, seed=6, device=dev)
     grads = [workloads.draw_mixture(M, w, seed=6) for w in range(n)]
