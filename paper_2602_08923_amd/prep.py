@@ -37,6 +37,16 @@ def squared_norms(worker_grads):
     return F
 
 
+def mean_per_super_group(worker_grads):
+    """mu_j = (1/n) sum_i mean(X_ij) in float64, returned as float32 (Section 3.1): the means that
+    tests and the benchmark hand to both the library and the oracle as an input."""
+    acc = None
+    for g in worker_grads:
+        m = g.to(torch.float64).reshape(-1, 256).mean(dim=1)
+        acc = m if acc is None else acc + m
+    return (acc / len(worker_grads)).to(torch.float32)
+
+
 def widths_for_offset(F, u):
     """q_j in {2,4,8}: 2 if z_j < 4, 4 if 4 <= z_j < 8, 8 if z_j >= 8 (Appendix A)."""
     z = K_ALLOC * torch.log2(F) + u  # F = 0 gives -inf, i.e. 2 bits

@@ -36,15 +36,17 @@ def test_config2_ring8_bf16_25mb_full(dev):
     n_sg = wl.entries // 256
     assert sum(counts) == n_sg and counts[0] > 0 and counts[1] > 0   # ~4 bits: a mix of 2- and 4-bit SGs
     seed = 2024
-    want = np.concatenate(O.ring_reduce_scatter(O.Oracle(n, seed=seed), [workloads.to_numpy(g) for g in re], counts))
+    mu = prep.mean_per_super_group(re)                                # as bench.py runs it: means subtracted
+    want = np.concatenate(O.ring_reduce_scatter(O.Oracle(n, seed=seed), [workloads.to_numpy(g) for g in re], counts,
+                                                mu=mu.numpy()))
     ctx = B.Context(n, seed=seed)
-    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [g.to(dev) for g in re], n_sg, [counts])
+    rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [g.to(dev) for g in re], n_sg, [counts], mu=mu.to(dev))
     assert rp.n_steps == 8 and [rp.step_info(i)[0] for i in range(8)] == [0, 1, 1, 1, 1, 1, 1, 2]
     rp.run()
     torch.cuda.synchronize()
     got = host(rp.out)
     assert np.array_equal(got, want)
-    true = sum(g.double() for g in re).numpy()
+    true = sum(g.double() for g in re).numpy() - n * np.repeat(mu.double().numpy(), 256)
     assert ((got - true) ** 2).sum() / (true ** 2).sum() < 0.5   # ~4 bits, x100 outliers, 7 re-quantizations
 
 
@@ -69,11 +71,12 @@ def test_config4_butterfly16_1p3b_sampled_buckets(dev):
     n_sg = d // 256
     check = (7, 93)
     worker = [torch.empty(d * nb, dtype=torch.bfloat16, device=dev) for _ in range(n)]
-    counts_all, kept = [], {}
+    counts_all, kept, mus = [], {}, []
     for b in range(nb):
         g = [workloads.draw(wl, w, b, device=dev) for w in range(n)]
         re, counts, _ = prep.prepare_bucket(g, wl.budget_bits, n)
         counts_all.append(counts)
+        mus.append(prep.mean_per_super_group(re))
         for w in range(n):
             worker[w][b * d:(b + 1) * d] = re[w]
         if b in check:
@@ -83,19 +86,20 @@ def test_config4_butterfly16_1p3b_sampled_buckets(dev):
     assert all(c[0] > 0 for c in counts_all)            # lowest budget: mostly 2-bit
     seed = 77
     ctx = B.Context(n, seed=seed)
-    rp = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_DYNAMIQ, worker, n_sg, counts_all, n_buckets=nb)
+    rp = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_DYNAMIQ, worker, n_sg, counts_all, n_buckets=nb, mu=torch.cat(mus))
     assert rp.n_steps == 5
     rp.run()
     torch.cuda.synchronize()
     orc = O.Oracle(n, seed=seed)
     for b in check:
-        want = np.concatenate(O.butterfly_reduce_scatter(orc, kept[b], counts_all[b], first_sg=b * n_sg))
+        want = np.concatenate(O.butterfly_reduce_scatter(orc, kept[b], counts_all[b], first_sg=b * n_sg,
+                                                         mu=mus[b].cpu().numpy()))
         got = host(rp.out[b * d:(b + 1) * d])
         assert np.array_equal(got, want), f"bucket {b}"
     # the unchecked buckets are estimates of their true sums too (at 3 bits per entry on i.i.d.
     # values the ternary codes are coarse: ask for clear correlation, not for a small error)
     for b in (0, 50, 99):
-        true = sum(worker[w][b * d:(b + 1) * d].double() for w in range(n))
+        true = sum(worker[w][b * d:(b + 1) * d].double() for w in range(n)) - n * mus[b].double().repeat_interleave(256)
         est = rp.out[b * d:(b + 1) * d].double()
         corr = float((est * true).sum() / torch.sqrt((est * est).sum() * (true * true).sum()))
         assert corr > 0.5, (b, corr)
@@ -123,8 +127,9 @@ def test_config5_chain64_125m_sampled_runs(dev):
         raw[w] = None
     assert counts[1] > 0 and counts[2] > 0              # 4.3125 code bits on average: 4- and 8-bit SGs
     seed = 5
+    mu = prep.mean_per_super_group(slices)
     ctx = B.Context(n, seed=seed)
-    rp = B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, slices, n_sg, [counts])
+    rp = B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, slices, n_sg, [counts], mu=mu)
     assert rp.n_steps == 64
     assert [rp.step_info(i)[0] for i in (0, 1, 62, 63)] == [0, 1, 1, 2]
     rp.run()
@@ -139,9 +144,10 @@ def test_config5_chain64_125m_sampled_runs(dev):
         cw = [int(max(0, min(s + run, edges[k + 1]) - max(s, edges[k]))) for k in range(3)]
         ch = O.make_chunk(s, cw)
         sl = [workloads.to_numpy(x[s * 256:(s + run) * 256]) for x in slices]
-        msg = orc.compress(ch, 0, sl[0])
+        m = mu[s:s + run].cpu().numpy()
+        msg = orc.compress(ch, 0, sl[0], m)
         for i in range(1, n - 1):
-            msg = orc.dar_hop(ch, i, msg, sl[i])
-        want = orc.decompress(ch, msg, sl[n - 1])
+            msg = orc.dar_hop(ch, i, msg, sl[i], m)
+        want = orc.decompress(ch, msg, sl[n - 1], m)
         got = host(rp.out[s * 256:(s + run) * 256])
         assert np.array_equal(got, want), f"run at super-group {s}"

@@ -109,3 +109,18 @@ def test_variable_bitwidth_is_the_main_driver(dev):
     alloc = A.vnmse(A.simulated_allreduce(grads, bits, seed=5)[0], truth)
     assert flat < 0.8 * flat_uniform                    # non-uniform levels (paper: about 45 % lower)
     assert alloc < flat / 3                             # variable bitwidth (paper: 3.5-5.1 x lower)
+
+
+def test_mean_subtraction_costs_no_accuracy_at_many_workers(dev):
+    """Zero-mean data, 256 workers, W = {2,4,8,16}: the tiny super-group means (about sigma/256) are
+    far below half an ulp of a bf16 entry.  Taking them off in fp32 inside the kernels changes the
+    error by a few percent at most; rounding x - mu back to bf16 before the main stage made all
+    workers err together and tripled it."""
+    J, n = 2048, 256
+    M = workloads.mixture_magnitudes(J, seed=8, device=dev)
+    grads = [workloads.draw_mixture(M, w, seed=8) for w in range(n)]
+    truth = A.true_sum(grads)
+    kw = dict(topology=B.DQ_BUTTERFLY, seed=3, max_width=16)
+    with_mean = A.vnmse(A.simulated_allreduce(grads, 8.5, subtract_mean=True, **kw)[0], truth)
+    without = A.vnmse(A.simulated_allreduce(grads, 8.5, subtract_mean=False, **kw)[0], truth)
+    assert with_mean < 1.1 * without and with_mean < 1e-4, (with_mean, without)
