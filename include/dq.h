@@ -100,6 +100,15 @@ dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_d
 dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
                         const float *mu_or_null, const dq_chunk *chunk, float *out, void *hip_stream);
 
+/* The sink's decompress with the restore of Section 3.4's last paragraph fused in: super-group j of
+ * the chunk is written to out_base + origin[j] * 256 (origin: device, one u32 per super-group of the
+ * chunk, distinct values) and, if mu_back_or_null is given, fp32(n_workers * mu_back[j]) is added to
+ * each of its entries after the decode (and the local addition): what dq_decompress followed by
+ * dq_restore computes, without the pass in between.  local_or_null must not be out_base. */
+dq_status dq_decompress_restore(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
+                                const float *mu_or_null, const dq_chunk *chunk, const uint32_t *origin,
+                                const float *mu_back_or_null, float *out_base, void *hip_stream);
+
 /* ---- OCP Microscaling comparison codec (blocks of 32, E8M0 shared scale, elements
  * E4M3 / E3M2 / E2M1, round-to-nearest-even, saturating; the formats the paper compares
  * against in Section 5 "Baseline compression schemes").  n_entries must be a multiple of
@@ -143,6 +152,11 @@ typedef struct {
                           the same for every worker: taken off each worker's gradient where it enters a
                           kernel, never off an fp32 buffer of sums; `out` is then the sum of the
                           mean-subtracted entries.  DQ_DYNAMIQ only; must stay valid like scratch. */
+  const uint32_t *origin; /* device, NULL or [n_buckets][n_sg_bucket]: origin[p] = the place inside its bucket
+                          that reordered super-group p came from (dq_reorder_mean writes it).  Then the last
+                          launch of the schedule writes every super-group straight to that place of `out` and
+                          adds n_workers * mu back: `out` ends in the ORIGINAL order, unnormalized -- the
+                          restore fused into the final decompress.  DQ_DYNAMIQ only. */
 } dq_replay_desc;
 
 /* Device scratch the replay needs (job tables, packed messages, fp32 keep-buffers). */
@@ -211,9 +225,13 @@ dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, uint32_
  * mu_main[pos[j]] = mu[j], except that the 16-bit super-groups of a bucket -- its last
  * counts[5b + 3] places, `counts` being what dq_allocate wrote -- get zero: a value sent as raw
  * bf16 gains nothing from the subtraction, and rounding x - mu back to bf16 would make all
- * workers err the same way.  counts_or_null NULL: no 16-bit class.  mu_main must not be mu. */
-dq_status dq_reorder_mean(const float *mu, const uint32_t *pos, const uint32_t *counts_or_null,
-                          uint32_t n_sg_per_bucket, uint32_t n_buckets, float *mu_main, void *hip_stream);
+ * workers err the same way.  counts_or_null NULL: no 16-bit class.  mu_main must not be mu.
+ * origin_or_null, if given, receives the inverse of the positions, origin[pos[j]] = j (per bucket):
+ * what dq_decompress_restore and dq_replay_desc.origin take.  Either output may be NULL, not both;
+ * without mu_main, mu is not read. */
+dq_status dq_reorder_mean(const float *mu_or_null, const uint32_t *pos, const uint32_t *counts_or_null,
+                          uint32_t n_sg_per_bucket, uint32_t n_buckets, float *mu_main_or_null,
+                          uint32_t *origin_or_null, void *hip_stream);
 
 /* Section 3.4, last paragraph: out[super-group j] = sum[super-group pos[j]] + n_workers *
  * mu_main[pos[j]] (fp32: one product per super-group, one addition per entry; `sum` is the main

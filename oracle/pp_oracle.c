@@ -153,11 +153,16 @@ void ppo_reorder_mean(const float *mu, const uint32_t *pos, uint64_t J, uint32_t
  * unnormalized by adding back the mean value".  The main stage returns the SUM over the
  * n workers of the mean-subtracted entries, so what is added back is n times the mean the
  * main stage subtracted (mu_main, in reordered order): one fp32 multiplication per
- * super-group, one fp32 addition per entry.  mu_main may be NULL. */
+ * super-group, one fp32 addition per entry.  mu_main NULL: nothing was subtracted, nothing is
+ * added (the entries are copied as they are, a zero keeps its sign). */
 void ppo_restore(const float *sum, const uint32_t *pos, const float *mu_main, uint32_t n, uint64_t J, float *out) {
   for (uint64_t j = 0; j < J; ++j) {
-    const float back = mu_main ? (float)n * mu_main[pos[j]] : 0.0f;
-    for (int k = 0; k < PPO_SG; ++k)
-      out[j * PPO_SG + k] = sum[(uint64_t)pos[j] * PPO_SG + k] + back;
+    const float *src = sum + (uint64_t)pos[j] * PPO_SG;
+    if (!mu_main) {
+      memcpy(out + j * PPO_SG, src, PPO_SG * sizeof(float));
+      continue;
+    }
+    const float back = (float)n * mu_main[pos[j]];
+    for (int k = 0; k < PPO_SG; ++k) out[j * PPO_SG + k] = src[k] + back;
   }
 }

@@ -26,13 +26,15 @@ def true_sum(worker_grads):
 
 def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.DQ_DYNAMIQ, seed=0, round=0,
                         all_gather=True, subtract_mean=True, n_sg_bucket=None, g4=1.3, g8=1.02, max_width=8,
-                        independent_rounding=False, uniform_width=None):
+                        independent_rounding=False, uniform_width=None, fused_restore=True):
     """Returns (sum estimate in the original order, float32; info dict).
     worker_grads: one tensor per simulated worker (same length, float32 or bfloat16, a whole
     number of buckets of n_sg_bucket super-groups; default: one bucket).  MX codecs skip the
     statistics, allocation and reorder (they have none) and ignore budget_bits.
     max_width: 8 for W = {2,4,8}, 16 for W = {2,4,8,16}.  uniform_width (2, 4 or 8): no allocation,
-    every super-group at that width (the baseline the variable allocation is compared with)."""
+    every super-group at that width (the baseline the variable allocation is compared with).
+    fused_restore: the replay's last launch writes the original order with the means added back
+    (dq_replay_desc.origin); False: a separate dq_restore pass does."""
     n = len(worker_grads)
     entries = worker_grads[0].numel()
     n_sg = entries // 256
@@ -65,10 +67,10 @@ def simulated_allreduce(worker_grads, budget_bits, topology=B.DQ_RING, codec=B.D
         by_width = [row] * nb
         if uniform_width == 16:
             mu = None                                    # uncompressed super-groups are not normalized
-    mu_main = None if mu is None else B.dq_reorder_mean(mu, pos, J, counts)
+    mu_main, origin = B.dq_reorder_mean(mu, pos, J, counts, with_origin=True)
     reordered = [B.dq_reorder(g, pos, J) for g in worker_grads]
     rp = B.Replay(ctx, topology, B.DQ_DYNAMIQ, reordered, J, by_width, n_buckets=nb, all_gather=all_gather,
-                  mu=mu_main)
+                  mu=mu_main, origin=origin if fused_restore else None)
     rp.run()
-    out = B.dq_restore(rp.out, pos, J, n, mu_main=mu_main)
+    out = rp.out if fused_restore else B.dq_restore(rp.out, pos, J, n, mu_main=mu_main)
     return out, {"sg_by_width": by_width, "replay_steps": rp.n_steps}

@@ -19,6 +19,7 @@ DQ_RING, DQ_BUTTERFLY, DQ_CHAIN = 0, 1, 2
 
 EXPORTS = [
     "dq_create", "dq_destroy", "dq_set_round", "dq_packed_bytes", "dq_compress", "dq_dar_hop", "dq_decompress",
+    "dq_decompress_restore",
     "dq_mx_packed_bytes", "dq_mx_compress", "dq_mx_dar_hop", "dq_mx_decompress",
     "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_run_steps",
     "dq_replay_step_info",
@@ -44,7 +45,7 @@ class Chunk(C.Structure):
 class ReplayDesc(C.Structure):
     _fields_ = [("topology", C.c_int), ("codec", C.c_int), ("dtype", C.c_int), ("n_buckets", C.c_uint32),
                 ("n_sg_bucket", C.c_uint64), ("n_sg_by_width", C.POINTER(C.c_uint32)), ("first_sg", C.c_uint64),
-                ("all_gather", C.c_uint32), ("mu", C.c_void_p)]
+                ("all_gather", C.c_uint32), ("mu", C.c_void_p), ("origin", C.c_void_p)]
 
 
 _lib = None
@@ -68,6 +69,7 @@ def lib():
         L.dq_compress.argtypes = [vp, vp, i, vp, C.POINTER(Chunk), u32, vp, vp]
         L.dq_dar_hop.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), u32, vp, vp]
         L.dq_decompress.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), vp, vp]
+        L.dq_decompress_restore.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), vp, vp, vp, vp]
         L.dq_status_str.argtypes = [i]
         L.dq_status_str.restype = C.c_char_p
         L.dq_last_hip_error.restype = C.c_char_p
@@ -90,7 +92,7 @@ def lib():
         L.dq_stats_combine.argtypes = [vp, vp, u32, u64, vp, vp, vp]
         L.dq_allocate.argtypes = [vp, u32, u32, u64, u32, vp, vp, vp, vp]
         L.dq_reorder.argtypes = [vp, i, vp, u32, u32, vp, vp]
-        L.dq_reorder_mean.argtypes = [vp, vp, vp, u32, u32, vp, vp]
+        L.dq_reorder_mean.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
         L.dq_restore.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp]
         L.dq_pipelined_wire_bytes.argtypes = [C.POINTER(Chunk), u32]
         L.dq_pipelined_wire_bytes.restype = C.c_size_t
@@ -206,6 +208,21 @@ class Context:
         return out
 
 
+    def dq_decompress_restore(self, packed_in, chunk, origin, out_base, local=None, mu=None, mu_back=None):
+        """Decompress (+ local - mu) with every super-group written to out_base[origin[j]] and
+        n_workers * mu_back[j] added: the restore fused into the sink's kernel."""
+        if packed_in.numel() < dq_packed_bytes(chunk) or (local is not None and local.numel() != _entries(chunk)):
+            raise DqError("buffers do not match the chunk")
+        if origin.dtype != torch.int32 or origin.numel() != sum(chunk.n_sg):
+            raise DqError("origin is int32, one per super-group of the chunk")
+        if out_base.dtype != torch.float32 or (origin.numel() and out_base.numel() < (int(origin.max()) + 1) * 256):
+            raise DqError("out_base is float32 and holds every destination super-group")
+        _check(lib().dq_decompress_restore(self.h, _ptr(packed_in), _ptr(local), 0 if local is None else _dtype(local),
+                                           _ptr(_mean(mu, chunk)), C.byref(chunk), _ptr(origin),
+                                           _ptr(_mean(mu_back, chunk)), _ptr(out_base), _stream()))
+        return out_base
+
+
 # ---- MX comparison codec -------------------------------------------------------------
 
 def dq_mx_packed_bytes(fmt, n_entries):
@@ -246,10 +263,15 @@ class Replay:
     """dq_replay: a prepared ring / butterfly / chain schedule over N simulated workers."""
 
     def __init__(self, ctx, topology, codec, worker_grads, n_sg_bucket, n_sg_by_width=None, n_buckets=1, first_sg=0,
-                 all_gather=False, mu=None):
-        """mu: None, or the float32 means of all n_buckets * n_sg_bucket super-groups in reordered order."""
+                 all_gather=False, mu=None, origin=None):
+        """mu: None, or the float32 means of all n_buckets * n_sg_bucket super-groups in reordered order.
+        origin: None, or int32 [n_buckets * n_sg_bucket] (from dq_reorder_mean): the result is then written
+        in the original order with the means added back."""
         self.ctx = ctx
         self.mu = mu
+        self.origin = origin
+        if origin is not None and (origin.dtype != torch.int32 or origin.numel() != n_buckets * n_sg_bucket):
+            raise DqError("origin is int32, one per super-group")
         if mu is not None and (mu.dtype != torch.float32 or mu.numel() != n_buckets * n_sg_bucket):
             raise DqError("mu is float32, one per super-group")
         self.grads = list(worker_grads)
@@ -262,7 +284,7 @@ class Replay:
                     flat[4 * b + k] = int(n_sg_by_width[b][k])
         self._widths = flat
         desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg,
-                          1 if all_gather else 0, _ptr(mu))
+                          1 if all_gather else 0, _ptr(mu), _ptr(origin))
         self.desc = desc
         entries = n_sg_bucket * 256 * n_buckets
         for g in self.grads:
@@ -352,18 +374,25 @@ def dq_reorder(x, pos, n_sg_per_bucket, out=None):
     return out
 
 
-def dq_reorder_mean(mu, pos, n_sg_per_bucket, counts=None, out=None):
+def dq_reorder_mean(mu, pos, n_sg_per_bucket, counts=None, out=None, with_origin=False):
     """The means the main stage subtracts, in reordered order (zero for 16-bit super-groups).
-    counts: what dq_allocate returned (int32 [n_buckets, 5]) or None (no 16-bit class)."""
+    counts: what dq_allocate returned (int32 [n_buckets, 5]) or None (no 16-bit class).
+    mu None: only the origins.  with_origin: also return origin (int32, origin[pos[j]] = j per bucket)."""
     nb = pos.numel() // n_sg_per_bucket
-    if mu.dtype != torch.float32 or mu.numel() != pos.numel() or pos.numel() % n_sg_per_bucket or pos.dtype != torch.int32:
-        raise DqError("mu is float32, one per position; positions are int32, a whole number of buckets")
+    if pos.numel() % n_sg_per_bucket or pos.dtype != torch.int32:
+        raise DqError("positions are int32, a whole number of buckets")
+    if mu is not None and (mu.dtype != torch.float32 or mu.numel() != pos.numel()):
+        raise DqError("mu is float32, one per position")
     if counts is not None and (counts.dtype != torch.int32 or counts.numel() != 5 * nb):
         raise DqError("counts is int32 [n_buckets, 5]")
-    if out is None:
+    if mu is None and not with_origin:
+        raise DqError("nothing to compute")
+    if out is None and mu is not None:
         out = torch.empty_like(mu)
-    _check(lib().dq_reorder_mean(_ptr(mu), _ptr(pos), _ptr(counts), n_sg_per_bucket, nb, _ptr(out), _stream()))
-    return out
+    origin = torch.empty_like(pos) if with_origin else None
+    _check(lib().dq_reorder_mean(_ptr(mu), _ptr(pos), _ptr(counts), n_sg_per_bucket, nb,
+                                 _ptr(out) if mu is not None else None, _ptr(origin), _stream()))
+    return (out, origin) if with_origin else out
 
 
 def dq_restore(total, pos, n_sg_per_bucket, n_workers, mu_main=None, out=None):

@@ -276,7 +276,7 @@ dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const floa
   if (chunk_sgs(chunk) == 0) return DQ_OK;  // nothing to do
   if (!local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
   if (!aligned16(local) || !aligned16(packed_out) || !aligned4(mu_or_null)) return DQ_EALIGN;
-  dq::Job j{nullptr, local, mu_or_null, packed_out, chunk->first_sg, {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, rank};
+  const dq::Job j = dq::make_job(nullptr, local, mu_or_null, packed_out, chunk->first_sg, chunk->n_sg, rank);
   return hip_ok(dq::launch_one(dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream))
              ? DQ_OK
              : DQ_EHIP;
@@ -289,8 +289,7 @@ dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_d
   if (chunk_sgs(chunk) == 0) return DQ_OK;
   if (!packed_in || !local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
   if (!aligned16(packed_in) || !aligned16(local) || !aligned16(packed_out) || !aligned4(mu_or_null)) return DQ_EALIGN;
-  dq::Job j{(const uint8_t *)packed_in, local, mu_or_null, packed_out, chunk->first_sg,
-            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, rank};
+  const dq::Job j = dq::make_job((const uint8_t *)packed_in, local, mu_or_null, packed_out, chunk->first_sg, chunk->n_sg, rank);
   return hip_ok(dq::launch_one(dq::kDar, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream)) ? DQ_OK
                                                                                                           : DQ_EHIP;
 }
@@ -303,8 +302,30 @@ dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or
   if (!packed_in || !out) return DQ_EINVAL;
   if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
   if (!aligned16(packed_in) || !aligned16(out) || !aligned16(local_or_null) || !aligned4(mu_or_null)) return DQ_EALIGN;
-  dq::Job j{(const uint8_t *)packed_in, local_or_null, local_or_null ? mu_or_null : nullptr, out, chunk->first_sg,
-            {chunk->n_sg[0], chunk->n_sg[1], chunk->n_sg[2], chunk->n_sg[3]}, 0};
+  const dq::Job j = dq::make_job((const uint8_t *)packed_in, local_or_null, local_or_null ? mu_or_null : nullptr, out,
+                                 chunk->first_sg, chunk->n_sg, 0);
+  return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->grid_blocks,
+                               (hipStream_t)hip_stream))
+             ? DQ_OK
+             : DQ_EHIP;
+}
+
+dq_status dq_decompress_restore(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
+                                const float *mu_or_null, const dq_chunk *chunk, const uint32_t *origin,
+                                const float *mu_back_or_null, float *out_base, void *hip_stream) {
+  dq_status st = check_chunk(ctx, chunk, 0);
+  if (st != DQ_OK) return st;
+  if (chunk_sgs(chunk) == 0) return DQ_OK;
+  if (!packed_in || !out_base || !origin) return DQ_EINVAL;
+  if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
+  if (local_or_null == (const void *)out_base) return DQ_EINVAL;  // scattered stores: no in-place accumulation
+  if (!aligned16(packed_in) || !aligned16(out_base) || !aligned16(local_or_null) || !aligned4(mu_or_null) ||
+      !aligned4(origin) || !aligned4(mu_back_or_null))
+    return DQ_EALIGN;
+  dq::Job j = dq::make_job((const uint8_t *)packed_in, local_or_null, local_or_null ? mu_or_null : nullptr, out_base,
+                           chunk->first_sg, chunk->n_sg, 0);
+  j.dest = origin;
+  j.back = mu_back_or_null;
   return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->grid_blocks,
                                (hipStream_t)hip_stream))
              ? DQ_OK
@@ -393,10 +414,10 @@ dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *loc
     // the kernels do not write the padding at the end of a packed block: clear the last 16 bytes first,
     // or a block would carry bytes of the one that used this half before
     if (bytes >= 16 && !hip_ok(hipMemsetAsync(stg + bytes - 16, 0, 16, cs))) return DQ_EHIP;
-    dq::Job j{wire_in ? static_cast<const uint8_t *>(wire_in) + wire_off : nullptr,
-              static_cast<const uint8_t *>(local) + b * (uint64_t)block_sg * 256 * es,
-              mu_or_null ? mu_or_null + b * (uint64_t)block_sg : nullptr, stg, blk.first_sg,
-              {blk.n_sg[0], blk.n_sg[1], blk.n_sg[2], blk.n_sg[3]}, rank};
+    const dq::Job j = dq::make_job(wire_in ? static_cast<const uint8_t *>(wire_in) + wire_off : nullptr,
+                                   static_cast<const uint8_t *>(local) + b * (uint64_t)block_sg * 256 * es,
+                                   mu_or_null ? mu_or_null + b * (uint64_t)block_sg : nullptr, stg, blk.first_sg,
+                                   blk.n_sg, rank);
     if (!hip_ok(dq::launch_one(wire_in ? dq::kDar : dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, cs)))
       return DQ_EHIP;
     if (!hip_ok(hipEventRecord(ctx->stage_filled[slot], cs)) || !hip_ok(hipStreamWaitEvent(xs, ctx->stage_filled[slot], 0)) ||

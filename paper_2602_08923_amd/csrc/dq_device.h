@@ -22,10 +22,23 @@ struct Job {
   const void *local;   // local slice, may be nullptr for decompress
   const float *mu;     // one mean per super-group of the chunk, taken off the local entries, or nullptr
   void *out;           // packed (compress, DAR) or fp32 (decompress)
+  const uint32_t *dest; // decompress: per super-group of the chunk, the super-group index in `out` it is written to
+                        // (nullptr: the chunk's own order, from out[0])
+  const float *back;    // decompress: per super-group, the mean added back n_workers times, or nullptr
   uint64_t first_sg;   // global index of the chunk's first super-group
   uint32_t n_sg[4];    // super-groups at 2, 4, 8 and 16 bits
   uint32_t rank;       // worker doing the compression (feeds the random streams)
 };
+
+inline Job make_job(const uint8_t *in, const void *local, const float *mu, void *out, uint64_t first_sg,
+                    const uint32_t n_sg[4], uint32_t rank) {
+  Job j;
+  j.in = in; j.local = local; j.mu = mu; j.out = out; j.dest = nullptr; j.back = nullptr;
+  j.first_sg = first_sg;
+  for (int w = 0; w < 4; ++w) j.n_sg[w] = n_sg[w];
+  j.rank = rank;
+  return j;
+}
 
 // Fixed part of the table blob (dword offsets).  The tables whose size does not depend on the
 // level sets sit at constant places, so the kernels address them with immediate offsets.

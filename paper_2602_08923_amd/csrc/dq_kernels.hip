@@ -421,8 +421,16 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
 // LDS area so that every store instruction covers 1 KB of contiguous memory: lane l parks its 4
 // float4 at slots 4l..4l+3 (slot index xor-ed with bits 2-3 of l so that the 16 lanes of a pass hit
 // different banks); store round r then reads slot r*64 + lane = float4 number r*64 + lane of the tile.
-__device__ __forceinline__ void store_tile_f32(const float (&v)[16], uint32_t xpose, float *outp, uint32_t last_row) {
+__device__ __forceinline__ void store_tile_f32(const Job &job, const Params &P, float (&v)[16], uint32_t xpose,
+                                               size_t first_entry, uint32_t last_row) {
   const uint32_t lane = threadIdx.x & 63u;
+  const size_t sg0 = first_entry / kSG;  // the tile's first super-group inside the chunk
+  if (job.back) {
+    // Section 3.4, last paragraph: the mean comes back, n times (the sum of n workers' entries lost it n times)
+    const float back = (float)P.n_workers * gld<float>(job.back + sg0 + min(lane >> 4, last_row));
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = v[k] + back;
+  }
   __builtin_amdgcn_wave_barrier();
 #pragma unroll
   for (uint32_t i = 0; i < 4; ++i)
@@ -430,12 +438,15 @@ __device__ __forceinline__ void store_tile_f32(const float (&v)[16], uint32_t xp
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  float *out = static_cast<float *>(job.out);
 #pragma unroll
   for (uint32_t r = 0; r < (uint32_t)kWaveSGs; ++r) {
     if (r > last_row) break;
     const uint32_t slot = r * 64 + lane, w = slot >> 2, c = slot & 3u;
     const f32x4 o = lds_ldf4(xpose + w * 64 + ((c ^ ((w >> 2) & 3u)) * 16));
-    gst<f32x4>(reinterpret_cast<float4 *>(outp) + slot, o);
+    // row r is one super-group, 1 KB: at its place in the chunk, or where job.dest sends it
+    const size_t sg = job.dest ? (size_t)gld<uint32_t>(job.dest + sg0 + r) : sg0 + r;
+    gst<f32x4>(reinterpret_cast<float4 *>(out + sg * kSG) + lane, o);
   }
   __builtin_amdgcn_wave_barrier();
 }
@@ -517,7 +528,7 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
       else v[per * j + k] = t[k] * sfg;
     }
   }
-  store_tile_f32(v, xpose, static_cast<float *>(job.out) + tb.first_entry, tb.last_row);
+  store_tile_f32(job, P, v, xpose, tb.first_entry, tb.last_row);
 }
 
 // One wave tile of uncompressed (16-bit) super-groups: the packed values are raw bf16
@@ -532,7 +543,7 @@ __device__ __forceinline__ uint32_t bf16_rne_pair(float lo, float hi) {
 }
 
 template <Kind KIND, typename LT>
-__device__ __forceinline__ void tile16(const Job &job, uint32_t xpose, const TilePos pos) {
+__device__ __forceinline__ void tile16(const Job &job, const Params &P, uint32_t xpose, const TilePos pos) {
   constexpr bool kHasLocal = !__is_same(LT, NoLocal);
   const TileBase<16> tb(job, pos);
   const uint32_t lane = threadIdx.x & 63u;
@@ -586,7 +597,7 @@ __device__ __forceinline__ void tile16(const Job &job, uint32_t xpose, const Til
     }
   }
   if constexpr (KIND == kDecompress) {
-    store_tile_f32(v, xpose, static_cast<float *>(job.out) + tb.first_entry, tb.last_row);
+    store_tile_f32(job, P, v, xpose, tb.first_entry, tb.last_row);
   } else if (row <= tb.last_row) {
     uint8_t *dst = static_cast<uint8_t *>(job.out) + tb.code_off + lg * 32;
 #pragma unroll
@@ -641,7 +652,7 @@ __device__ __forceinline__ void run_range(const Job &job, const Params &P, uint3
     else if (p.wi == 2) run_tiles<8, KIND, LT>(job, P, lds0, stage, p, len);
     else {
       TilePos q = p;
-      for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<KIND, LT>(job, 0u, q);
+      for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<KIND, LT>(job, P, 0u, q);
     }
     j += len;
   }
@@ -707,7 +718,7 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
       if (p.wi == 0) tile_da<2, LT>(job, P, lds0, xpose, p);
       else if (p.wi == 1) tile_da<4, LT>(job, P, lds0, xpose, p);
       else if (p.wi == 2) tile_da<8, LT>(job, P, lds0, xpose, p);
-      else tile16<kDecompress, LT>(job, xpose, p);
+      else tile16<kDecompress, LT>(job, P, xpose, p);
     }
   } else if (block_draws) {
     run_range<KIND, LT>(job, P, lds0, park0 + (w_lo - b_lo) * 128, w_lo, w_hi - w_lo);

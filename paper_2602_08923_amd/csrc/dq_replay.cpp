@@ -17,6 +17,8 @@ struct HostJob {
   const uint8_t *in;
   const void *local;
   const float *mu;
+  const uint32_t *dest = nullptr;
+  const float *back = nullptr;
   void *out;
   uint64_t first_sg;
   uint32_t n_sg[4];
@@ -81,7 +83,8 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
   if (n < 2 || d->n_buckets < 1 || d->n_sg_bucket < 1) return DQ_EINVAL;
   if (!mx && !d->n_sg_by_width) return DQ_EINVAL;
   if (mx && d->mu) return DQ_EINVAL;  // the MX codec has no normalization
-  if (reinterpret_cast<uintptr_t>(d->mu) & 3u) return DQ_EALIGN;
+  if (mx && d->origin) return DQ_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(d->mu) & 3u) || (reinterpret_cast<uintptr_t>(d->origin) & 3u)) return DQ_EALIGN;
   if (d->topology == DQ_CHAIN) {
     if (d->n_buckets != 1) return DQ_EINVAL;
   } else if (d->topology == DQ_RING || d->topology == DQ_BUTTERFLY) {
@@ -127,8 +130,24 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
   // raw: `local` is a worker's own gradient (its means are still to be taken off), not an fp32
   // buffer of sums that already had them taken off
   auto mk = [&](const ChunkInfo &x, const uint8_t *in, const void *local, bool raw, void *o, uint32_t rank) {
-    const float *mu = (raw && d->mu) ? d->mu + (x.first_sg - d->first_sg) : nullptr;
-    HostJob j{in, local, mu, o, x.first_sg, {x.n_sg[0], x.n_sg[1], x.n_sg[2], x.n_sg[3]}, rank};
+    HostJob j;
+    j.in = in;
+    j.local = local;
+    j.mu = (raw && d->mu) ? d->mu + (x.first_sg - d->first_sg) : nullptr;
+    j.out = o;
+    j.first_sg = x.first_sg;
+    memcpy(j.n_sg, x.n_sg, sizeof(j.n_sg));
+    j.rank = rank;
+    return j;
+  };
+  // The launch that writes the final result: with d->origin every super-group goes straight to its
+  // original place in its bucket and gets its mean back (the restore, fused into the last kernel).
+  auto finish = [&](HostJob j, const ChunkInfo &x, uint32_t b) {
+    if (d->origin) {
+      j.out = out + (uint64_t)b * bucket_entries;
+      j.dest = d->origin + (x.first_sg - d->first_sg);
+      j.back = d->mu ? d->mu + (x.first_sg - d->first_sg) : nullptr;
+    }
     return j;
   };
 
@@ -159,7 +178,9 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
           const void *local = d->topology == DQ_CHAIN ? grad_ptr(w, 0, 0) : grad_ptr(w, b, c);
           const uint8_t *in = t == 0 ? nullptr : msg[(t - 1) & 1] + slot[i];
           void *o = t == n - 1 ? (void *)out_ptr(b, c) : (void *)(msg[t & 1] + slot[i]);
-          L.jobs.push_back(mk(ci[i], in, local, true, o, w));
+          HostJob j = mk(ci[i], in, local, true, o, w);
+          if (t == n - 1 && !d->all_gather) j = finish(j, ci[i], b);
+          L.jobs.push_back(j);
         }
       st.launches.push_back(std::move(L));
       plan->steps.push_back(std::move(st));
@@ -236,7 +257,9 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
       for (uint32_t w = 0; w < n; ++w) {
         const ChunkInfo &x = ci[(size_t)b * n + w];
         const void *local = Lg == 1 ? grad_ptr(w, b, w) : (const void *)acc_ptr(w, b, w);
-        fin.jobs.push_back(mk(x, msg_ptr(Lg, b, w, w), local, Lg == 1, out_ptr(b, w), w));
+        HostJob j = mk(x, msg_ptr(Lg, b, w, w), local, Lg == 1, out_ptr(b, w), w);
+        if (!d->all_gather) j = finish(j, x, b);
+        fin.jobs.push_back(j);
       }
     st.launches.push_back(std::move(fin));
     plan->steps.push_back(std::move(st));
@@ -267,7 +290,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
         const size_t i = (size_t)b * n_chunks + c;
         const uint32_t sink = d->topology == DQ_CHAIN ? n - 1 : (d->topology == DQ_RING ? (c + n - 1) % n : c);
         comp.jobs.push_back(mk(ci[i], nullptr, out_ptr(b, c), false, ag + slot[i], sink));
-        dec.jobs.push_back(mk(ci[i], ag + slot[i], nullptr, false, out_ptr(b, c), sink));
+        dec.jobs.push_back(finish(mk(ci[i], ag + slot[i], nullptr, false, out_ptr(b, c), sink), ci[i], b));
       }
     sc.launches.push_back(std::move(comp));
     sd.launches.push_back(std::move(dec));
@@ -349,7 +372,9 @@ dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *
         std::vector<dq::Job> t(L.jobs.size());
         for (size_t i = 0; i < t.size(); ++i) {
           const HostJob &j = L.jobs[i];
-          t[i] = dq::Job{j.in, j.local, j.mu, j.out, j.first_sg, {j.n_sg[0], j.n_sg[1], j.n_sg[2], j.n_sg[3]}, j.rank};
+          t[i] = dq::make_job(j.in, j.local, j.mu, j.out, j.first_sg, j.n_sg, j.rank);
+          t[i].dest = j.dest;
+          t[i].back = j.back;
         }
         e = hipMemcpy(r->scratch + L.table_off, t.data(), t.size() * sizeof(dq::Job), hipMemcpyHostToDevice);
       }

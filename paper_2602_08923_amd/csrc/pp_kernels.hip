@@ -494,15 +494,18 @@ __global__ void __launch_bounds__(kThreads) k_reorder(const void *x_all, const u
 }
 
 // The means the main stage subtracts, in reordered order; zero for the 16-bit super-groups (the
-// last counts[5b + 3] places of bucket b).  One thread per super-group.
+// last counts[5b + 3] places of bucket b); and the inverse of the positions.  One thread per super-group.
 __global__ void __launch_bounds__(kThreads) k_reorder_mean(const float *mu_all, const uint32_t *pos_all, const uint32_t *counts,
-                                                           uint32_t J, float *mu_main) {
+                                                           uint32_t J, float *mu_main, uint32_t *origin) {
   const uint64_t bucket_first = (uint64_t)blockIdx.y * J;
   const uint32_t n16 = counts ? gld<uint32_t>(counts + 5ull * blockIdx.y + 3) : 0u;
   for (uint32_t j = blockIdx.x * kThreads + threadIdx.x; j < J; j += gridDim.x * kThreads) {
     const uint32_t p = gld<uint32_t>(pos_all + bucket_first + j);
-    const float m = gld<float>(mu_all + bucket_first + j);
-    gst<float>(mu_main + bucket_first + p, (p < J - n16) ? m : 0.0f);
+    if (mu_main) {
+      const float m = gld<float>(mu_all + bucket_first + j);
+      gst<float>(mu_main + bucket_first + p, (p < J - n16) ? m : 0.0f);
+    }
+    if (origin) gst<uint32_t>(origin + bucket_first + p, j);
   }
 }
 
@@ -532,8 +535,8 @@ __global__ void __launch_bounds__(kThreads) k_restore(const float *sum_all, cons
     for (int i = 0; i < kUnroll; ++i) {
       const uint32_t c = base + i * kThreads;
       if (c < n_pieces) {
-        f32x4 o;
-        o.x = d[i].x + back[i]; o.y = d[i].y + back[i]; o.z = d[i].z + back[i]; o.w = d[i].w + back[i];
+        f32x4 o = d[i];
+        if (mu) { o.x = d[i].x + back[i]; o.y = d[i].y + back[i]; o.z = d[i].z + back[i]; o.w = d[i].w + back[i]; }
         gst<f32x4>(out + (uint64_t)c * 16, o);
       }
     }
@@ -611,15 +614,20 @@ dq_status dq_reorder(const void *x, dq_dtype dtype, const uint32_t *pos, uint32_
   return launched();
 }
 
-dq_status dq_reorder_mean(const float *mu, const uint32_t *pos, const uint32_t *counts_or_null, uint32_t n_sg_per_bucket,
-                          uint32_t n_buckets, float *mu_main, void *hip_stream) {
+dq_status dq_reorder_mean(const float *mu_or_null, const uint32_t *pos, const uint32_t *counts_or_null,
+                          uint32_t n_sg_per_bucket, uint32_t n_buckets, float *mu_main_or_null, uint32_t *origin_or_null,
+                          void *hip_stream) {
   if (n_sg_per_bucket == 0 || n_buckets == 0) return DQ_OK;
-  if (!mu || !pos || !mu_main || mu == mu_main) return DQ_EINVAL;
+  if (!pos || (!mu_main_or_null && !origin_or_null) || (mu_main_or_null && (!mu_or_null || mu_or_null == mu_main_or_null)) ||
+      origin_or_null == pos)
+    return DQ_EINVAL;
   if (n_sg_per_bucket > (1u << 24) || n_buckets > 65535u) return DQ_EUNSUPPORTED;
-  if (!aligned(mu, 4) || !aligned(pos, 4) || !aligned(counts_or_null, 4) || !aligned(mu_main, 4)) return DQ_EALIGN;
+  if (!aligned(mu_or_null, 4) || !aligned(pos, 4) || !aligned(counts_or_null, 4) || !aligned(mu_main_or_null, 4) ||
+      !aligned(origin_or_null, 4))
+    return DQ_EALIGN;
   const uint32_t blocks = stream_blocks(kThreads, n_sg_per_bucket, n_buckets);
-  hipLaunchKernelGGL(k_reorder_mean, dim3(blocks, n_buckets), dim3(kThreads), 0, (hipStream_t)hip_stream, mu, pos,
-                     counts_or_null, n_sg_per_bucket, mu_main);
+  hipLaunchKernelGGL(k_reorder_mean, dim3(blocks, n_buckets), dim3(kThreads), 0, (hipStream_t)hip_stream, mu_or_null, pos,
+                     counts_or_null, n_sg_per_bucket, mu_main_or_null, origin_or_null);
   return launched();
 }
 

@@ -628,3 +628,64 @@ def test_mx_replay_rejects_means(dev):
     grads = [torch.zeros(2 * 256, dtype=torch.float32, device=dev) for _ in range(n)]
     with pytest.raises(B.DqError):
         B.Replay(B.Context(n), B.DQ_RING, B.DQ_MXFP8_E4M3, grads, 2, mu=torch.zeros(2, device=dev))
+
+
+# ----------------------------------------------------------------------------- restore fused into the last kernel
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_sg", [[5, 7, 3, 0], [1, 2, 1, 6], [0, 0, 1, 0], [9, 0, 4, 1]])
+def test_decompress_restore_is_decompress_then_restore(dev, dtype, n_sg):
+    from oracle import pp_oracle as P
+    n, first = 8, 77
+    total = sum(n_sg)
+    rng = np.random.default_rng(total + 1)
+    a, c = make_local(rng, total * 256, dtype), make_local(rng, total * 256, dtype)
+    mu = (rng.standard_normal(total) * 2e-4).astype(np.float32)
+    origin = rng.permutation(total).astype(np.uint32)          # reordered place p came from origin[p]
+    pos = np.argsort(origin).astype(np.uint32)                 # pos[j] = place of original super-group j
+    orc, ctx = O.Oracle(n, seed=3), B.Context(n, seed=3)
+    och, gch = O.make_chunk(first, n_sg), B.make_chunk(first, n_sg)
+    msg = orc.compress(och, 2, a, mu)
+    msg_t = torch.from_numpy(msg).to(dev)
+    mu_t, origin_t = torch.from_numpy(mu).to(dev), torch.from_numpy(origin.view(np.int32)).to(dev)
+    for local, back in ((c, mu), (None, mu), (c, None), (None, None)):
+        plain = orc.decompress(och, msg, local, mu if local is not None else None)
+        want = P.restore(plain, pos, back, n)
+        out = torch.full((total * 256,), float("nan"), dtype=torch.float32, device=dev)
+        ctx.dq_decompress_restore(msg_t, gch, origin_t, out, local=None if local is None else to_dev(local, dev),
+                                  mu=mu_t if local is not None else None, mu_back=None if back is None else mu_t)
+        assert np.array_equal(host(out).view(np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.parametrize("topology,n,all_gather", [("ring", 4, True), ("ring", 3, False), ("butterfly", 2, False),
+                                                   ("butterfly", 8, True), ("butterfly", 4, False)])
+def test_replay_writes_the_restored_result(dev, topology, n, all_gather):
+    """dq_replay_desc.origin: the schedule's last launch scatters to the original order and adds n * mu."""
+    from oracle import pp_oracle as P
+    J, buckets = 4 * n, 2
+    rng = np.random.default_rng(10 * n + all_gather)
+    d = J * 256
+    grads = [make_local(rng, d * buckets, "bf16") for _ in range(n)]     # already reordered
+    widths = [np.sort(rng.choice(np.array([2, 4, 8, 16], np.uint8), J)) for _ in range(buckets)]
+    counts = [[int((w == b).sum()) for b in (2, 4, 8, 16)] for w in widths]
+    mu = (rng.standard_normal(J * buckets) * 2e-4).astype(np.float32)
+    for b in range(buckets):
+        mu[b * J + J - counts[b][3]:(b + 1) * J] = 0                      # 16-bit super-groups are not normalized
+    origin = np.concatenate([rng.permutation(J) for _ in range(buckets)]).astype(np.uint32)
+    orc, ctx = O.Oracle(n, seed=19), B.Context(n, seed=19)
+    fn = O.ring_reduce_scatter if topology == "ring" else O.butterfly_reduce_scatter
+    want = []
+    for b in range(buckets):
+        m = mu[b * J:(b + 1) * J]
+        rs = fn(orc, [g[b * d:(b + 1) * d] for g in grads], counts[b], first_sg=b * J, mu=m)
+        if all_gather:
+            rs = O.all_gather(orc, rs, counts[b], topology, first_sg=b * J)
+        pos = np.argsort(origin[b * J:(b + 1) * J]).astype(np.uint32)
+        want.append(P.restore(np.concatenate(rs), pos, m, n))
+    topo = B.DQ_RING if topology == "ring" else B.DQ_BUTTERFLY
+    rp = B.Replay(ctx, topo, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in grads], J, counts, n_buckets=buckets,
+                  all_gather=all_gather, mu=torch.from_numpy(mu).to(dev),
+                  origin=torch.from_numpy(origin.view(np.int32)).to(dev))
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out).view(np.uint32), np.concatenate(want).view(np.uint32))

@@ -183,6 +183,12 @@ def test_reorder_and_restore(dev, dtype, J, nb):
         got_mm = B.dq_reorder_mean(torch.from_numpy(mu).to(dev), pos_t, J,
                                    None if cnt is None else torch.from_numpy(cnt).to(dev))
         assert np.array_equal(host(got_mm).view(np.uint32), want_mm.view(np.uint32))
+    # the inverse of the positions, alone and together with the means
+    inv = np.concatenate([np.argsort(pos[b * J:(b + 1) * J]) for b in range(nb)]).astype(np.int32)
+    _, origin = B.dq_reorder_mean(None, pos_t, J, with_origin=True)
+    assert np.array_equal(host(origin), inv)
+    mm2, origin2 = B.dq_reorder_mean(torch.from_numpy(mu).to(dev), pos_t, J, with_origin=True)
+    assert np.array_equal(host(origin2), inv) and np.array_equal(host(mm2).view(np.uint32), want_mm.view(np.uint32))
     total = (rng.standard_normal(n_sg * 256) * 1e-2).astype(f32)
     for m in (want_mm, None):
         want = np.concatenate([P.restore(total[b * J * 256:(b + 1) * J * 256], pos[b * J:(b + 1) * J],
@@ -224,7 +230,9 @@ def test_rejects_bad_arguments(dev):
     st = L.dq_reorder(x.data_ptr() + 4, 0, B._ptr(pos), 2, 1, B._ptr(torch.empty_like(x)), None)
     assert st == B.DQ_EALIGN
     mu = torch.zeros(2, dtype=torch.float32, device=dev)
-    st = L.dq_reorder_mean(B._ptr(mu), B._ptr(pos), None, 2, 1, B._ptr(mu), None)     # in place
+    st = L.dq_reorder_mean(B._ptr(mu), B._ptr(pos), None, 2, 1, B._ptr(mu), None, None)     # in place
+    assert st == B.DQ_EINVAL
+    st = L.dq_reorder_mean(B._ptr(mu), B._ptr(pos), None, 2, 1, None, None, None)           # no output asked for
     assert st == B.DQ_EINVAL
     st = L.dq_restore(B._ptr(x), B._ptr(pos), None, 0, 2, 1, B._ptr(torch.empty_like(x)), None)   # n = 0
     assert st == B.DQ_EINVAL

@@ -325,6 +325,17 @@ def test_restore_inverts_reorder_and_adds_n_mu():
     assert np.array_equal(P.restore(total, pos, None, n), sum(xs) - n * np.repeat(kept, 256))
 
 
+def test_restore_without_means_is_the_permutation_alone():
+    """Nothing subtracted, nothing added: every bit pattern survives, the sign of a zero included
+    (x + 0.0 would turn -0.0 into +0.0)."""
+    bits = np.arange(3 * 256, dtype=np.uint32) * np.uint32(0x00A3C0F1) | np.uint32(0x80000000)
+    bits[:4] = [0x80000000, 0x00000000, 0x80000001, 0x7F7FFFFF]
+    pos = np.array([2, 0, 1], np.uint32)
+    out = P.restore(bits.view(f32), pos, None, 5)
+    for j in range(3):
+        assert np.array_equal(out[j * 256:(j + 1) * 256].view(np.uint32), bits[pos[j] * 256:(pos[j] + 1) * 256])
+
+
 def test_pipeline_on_real_shapes():
     """statistics -> combine -> allocate -> positions on a bucket with the survey's structure."""
     rng = np.random.default_rng(10)
