@@ -165,8 +165,9 @@ class Context:
         _check(lib().dq_create(C.byref(cfg), C.byref(self.h)))
 
     def close(self):
-        if getattr(self, "h", None):
-            lib().dq_destroy(self.h)
+        # _lib is read directly: at interpreter exit module functions may already be gone
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.dq_destroy(self.h)
             self.h = None
 
     __del__ = close
@@ -318,8 +319,8 @@ class Replay:
         return kind.value, a.value, b.value
 
     def close(self):
-        if getattr(self, "h", None):
-            lib().dq_replay_destroy(self.h)
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.dq_replay_destroy(self.h)
             self.h = None
 
     __del__ = close

@@ -54,7 +54,7 @@ def main():
         budget = int(math.floor(prep.code_bits(args.bits) * J))
         widths, pos, counts = B.dq_allocate(F, J, budget, max_width=args.max_width)
         by_width = [[int(v) for v in counts.cpu().tolist()[0][:4]]]
-        mu_main = B.dq_reorder_mean(mu, pos, J, counts)
+        mu_main, origin = B.dq_reorder_mean(mu, pos, J, counts, with_origin=True)
     resident = []
     for w in range(n):                                   # pass 2: the resident (reordered) gradients
         g = workloads.draw_mixture(M, w, seed=args.seed)
@@ -63,13 +63,15 @@ def main():
     t1 = time.perf_counter()
     ctx = B.Context(n, seed=1234 + args.seed)
     codec = B.DQ_DYNAMIQ if dynamiq else B.DQ_MXFP8_E4M3
-    rp = B.Replay(ctx, topo, codec, resident, J, by_width, all_gather=True, mu=mu_main if dynamiq else None)
+    # the schedule's last launch writes the original order with the means added back (the restore, fused)
+    rp = B.Replay(ctx, topo, codec, resident, J, by_width, all_gather=True, mu=mu_main if dynamiq else None,
+                  origin=origin if dynamiq else None)
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     rp.run()
     torch.cuda.synchronize()
     t3 = time.perf_counter()
-    out = B.dq_restore(rp.out, pos, J, n, mu_main=mu_main) if dynamiq else rp.out
+    out = rp.out
     err = A.vnmse(out, truth)
     print(json.dumps({
         "workers": n, "super_groups_per_worker": J, "entries_per_worker": entries, "topology": args.topology,
