@@ -7,7 +7,7 @@
  *
  * Conventions shared by every call
  *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned
- *     (DQ_EALIGN otherwise).  Descriptor structs (dq_config, dq_chunk, dq_replay_desc
+ *     (DQ_EALIGN otherwise).  Descriptor structs (dq_config, dq_chunk, dq_local, dq_replay_desc
  *     and the arrays they point to) are HOST memory, read during the call only.
  *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
  *     and return without synchronising; the library allocates device memory only in
@@ -75,39 +75,51 @@ dq_status dq_set_round(dq_ctx *ctx, uint32_t round);
 /* Bytes of the packed form of a chunk (pure; layout above). */
 size_t dq_packed_bytes(const dq_chunk *chunk);
 
-/* The three calls below take `mu_or_null`: NULL, or one fp32 mean per super-group of the chunk
- * (device, 4-byte aligned, in the chunk's order).  Section 3.1: every worker subtracts mu_j from
- * each entry of super-group j before it is quantized; here that is one fp32 subtraction on the
- * widened local entry, done where the entry enters the main stage, for every width (callers pass
- * zero for the 16-bit super-groups: see dq_reorder_mean).  Pass NULL when `local` is not a
- * worker's own gradient but a buffer of sums whose means are already off. */
+/* A worker's own entries as the calls below read them (host struct, read during the call).
+ *   data      device, 16-byte aligned, `dtype` entries.
+ *   mu        NULL, or one fp32 mean per super-group of the chunk (device, 4-byte aligned, in the
+ *             chunk's order).  Section 3.1: every worker subtracts mu_j from each entry of
+ *             super-group j before it is quantized; here that is one fp32 subtraction on the widened
+ *             entry, done where the entry enters the main stage, for every width (callers pass zero
+ *             for the 16-bit super-groups: see dq_reorder_mean).  NULL when `data` is not a
+ *             gradient but a buffer of sums whose means are already off.
+ *   sg_index  NULL: `data` holds the chunk's super-groups back to back in the chunk's order (a
+ *             reordered tensor, Section 3.5).  Else one u32 per super-group of the chunk (device):
+ *             super-group j of the chunk is data[256 * sg_index[j] ...], i.e. `data` is the
+ *             ORIGINAL tensor and the reorder is done by addressing -- whole super-groups (512 B or
+ *             1 KB) are gathered, no reorder pass.  The result is the same bytes either way. */
+typedef struct {
+  const void *data;
+  dq_dtype dtype;
+  const float *mu;
+  const uint32_t *sg_index;
+} dq_local;
 
 /* Leaf node of the aggregation topology (Section 3.4 "Fused kernels", kernel 1 of Section 4):
- * quantize the local chunk (minus its means).  local: chunk entries, contiguous, `dtype`.  rank:
- * the worker doing the compression (0..n_workers-1).  packed_out: dq_packed_bytes(chunk) bytes. */
-dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const float *mu_or_null, const dq_chunk *chunk,
-                      uint32_t rank, void *packed_out, void *hip_stream);
+ * quantize the local chunk (minus its means).  rank: the worker doing the compression
+ * (0..n_workers-1).  packed_out: dq_packed_bytes(chunk) bytes. */
+dq_status dq_compress(dq_ctx *ctx, const dq_local *local, const dq_chunk *chunk, uint32_t rank, void *packed_out,
+                      void *hip_stream);
 
 /* Internal node (kernel 3 of Section 4): decode the received partial sum, add the local
  * slice (minus its means), re-quantize; intermediates never leave registers.  packed_out may
  * alias packed_in. */
-dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const float *mu_or_null,
-                     const dq_chunk *chunk, uint32_t rank, void *packed_out, void *hip_stream);
+dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const dq_local *local, const dq_chunk *chunk, uint32_t rank,
+                     void *packed_out, void *hip_stream);
 
 /* Sink of the reduce-scatter, non-last parents of a butterfly node, all-gather receivers
  * (kernels 2 and 4 of Section 4): out = decode(packed_in) [+ (local - mu)].  local_or_null may be
- * NULL (then dtype and mu_or_null are ignored); out (fp32, one per entry) may alias an fp32 local. */
-dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
-                        const float *mu_or_null, const dq_chunk *chunk, float *out, void *hip_stream);
+ * NULL; out (fp32, one per entry, the chunk's order) may alias an fp32 local->data without sg_index. */
+dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const dq_local *local_or_null, const dq_chunk *chunk,
+                        float *out, void *hip_stream);
 
 /* The sink's decompress with the restore of Section 3.4's last paragraph fused in: super-group j of
  * the chunk is written to out_base + origin[j] * 256 (origin: device, one u32 per super-group of the
  * chunk, distinct values) and, if mu_back_or_null is given, fp32(n_workers * mu_back[j]) is added to
  * each of its entries after the decode (and the local addition): what dq_decompress followed by
- * dq_restore computes, without the pass in between.  local_or_null must not be out_base. */
-dq_status dq_decompress_restore(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
-                                const float *mu_or_null, const dq_chunk *chunk, const uint32_t *origin,
-                                const float *mu_back_or_null, float *out_base, void *hip_stream);
+ * dq_restore computes, without the pass in between.  local_or_null->data must not be out_base. */
+dq_status dq_decompress_restore(dq_ctx *ctx, const void *packed_in, const dq_local *local_or_null, const dq_chunk *chunk,
+                                const uint32_t *origin, const float *mu_back_or_null, float *out_base, void *hip_stream);
 
 /* ---- OCP Microscaling comparison codec (blocks of 32, E8M0 shared scale, elements
  * E4M3 / E3M2 / E2M1, round-to-nearest-even, saturating; the formats the paper compares
@@ -157,6 +169,9 @@ typedef struct {
                           launch of the schedule writes every super-group straight to that place of `out` and
                           adds n_workers * mu back: `out` ends in the ORIGINAL order, unnormalized -- the
                           restore fused into the final decompress.  DQ_DYNAMIQ only. */
+  uint32_t inputs_in_original_order; /* 1 (needs origin; ring and butterfly): worker_grads hold the ORIGINAL
+                          tensors and every kernel that reads a worker's gradient gathers its super-groups
+                          through origin (dq_local.sg_index): no reorder pass at all.  0: reordered inputs. */
 } dq_replay_desc;
 
 /* Device scratch the replay needs (job tables, packed messages, fp32 keep-buffers). */
@@ -247,16 +262,16 @@ dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_main
  * at a multiple of 256 bytes: dq_pipelined_wire_bytes in all.  Block i is (re-)encoded on
  * compute_stream into one half of `stage` (dq_pipelined_stage_bytes, two blocks) and copied from
  * there to its place in wire_out on copy_stream -- a device-to-device copy standing in for the
- * network -- while block i+1 is being encoded.  wire_in NULL: the first hop (compress).  mu_or_null:
- * as for dq_dar_hop, one mean per super-group of the whole chunk.  The two
+ * network -- while block i+1 is being encoded.  wire_in NULL: the first hop (compress).  `local`
+ * describes the whole chunk (means and indices per super-group of the whole chunk).  The two
  * streams must differ; when the call returns, compute_stream has been made to wait for the last
  * copies, so synchronising it is enough.  Events are created inside the context at the first call;
  * one pipelined call at a time per context. */
 size_t dq_pipelined_wire_bytes(const dq_chunk *chunk, uint32_t block_sg);
 size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg);
-dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *local, dq_dtype dtype,
-                               const float *mu_or_null, const dq_chunk *chunk, uint32_t rank, uint32_t block_sg,
-                               void *stage, void *wire_out, void *compute_stream, void *copy_stream);
+dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
+                               uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
+                               void *copy_stream);
 
 const char *dq_status_str(dq_status s);
 /* Last HIP error string seen by this library on the calling thread (for DQ_EHIP). */

@@ -45,7 +45,13 @@ class Chunk(C.Structure):
 class ReplayDesc(C.Structure):
     _fields_ = [("topology", C.c_int), ("codec", C.c_int), ("dtype", C.c_int), ("n_buckets", C.c_uint32),
                 ("n_sg_bucket", C.c_uint64), ("n_sg_by_width", C.POINTER(C.c_uint32)), ("first_sg", C.c_uint64),
-                ("all_gather", C.c_uint32), ("mu", C.c_void_p), ("origin", C.c_void_p)]
+                ("all_gather", C.c_uint32), ("mu", C.c_void_p), ("origin", C.c_void_p),
+                ("inputs_in_original_order", C.c_uint32)]
+
+
+class Local(C.Structure):
+    """dq_local: a worker's own entries, their means, and where each super-group of the chunk lives."""
+    _fields_ = [("data", C.c_void_p), ("dtype", C.c_int), ("mu", C.c_void_p), ("sg_index", C.c_void_p)]
 
 
 _lib = None
@@ -66,10 +72,10 @@ def lib():
         L.dq_set_round.argtypes = [vp, u32]
         L.dq_packed_bytes.argtypes = [C.POINTER(Chunk)]
         L.dq_packed_bytes.restype = C.c_size_t
-        L.dq_compress.argtypes = [vp, vp, i, vp, C.POINTER(Chunk), u32, vp, vp]
-        L.dq_dar_hop.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), u32, vp, vp]
-        L.dq_decompress.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), vp, vp]
-        L.dq_decompress_restore.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), vp, vp, vp, vp]
+        L.dq_compress.argtypes = [vp, C.POINTER(Local), C.POINTER(Chunk), u32, vp, vp]
+        L.dq_dar_hop.argtypes = [vp, vp, C.POINTER(Local), C.POINTER(Chunk), u32, vp, vp]
+        L.dq_decompress.argtypes = [vp, vp, C.POINTER(Local), C.POINTER(Chunk), vp, vp]
+        L.dq_decompress_restore.argtypes = [vp, vp, C.POINTER(Local), C.POINTER(Chunk), vp, vp, vp, vp]
         L.dq_status_str.argtypes = [i]
         L.dq_status_str.restype = C.c_char_p
         L.dq_last_hip_error.restype = C.c_char_p
@@ -98,7 +104,7 @@ def lib():
         L.dq_pipelined_wire_bytes.restype = C.c_size_t
         L.dq_pipelined_stage_bytes.argtypes = [C.POINTER(Chunk), u32]
         L.dq_pipelined_stage_bytes.restype = C.c_size_t
-        L.dq_dar_hop_pipelined.argtypes = [vp, vp, vp, i, vp, C.POINTER(Chunk), u32, u32, vp, vp, vp, vp]
+        L.dq_dar_hop_pipelined.argtypes = [vp, vp, C.POINTER(Local), C.POINTER(Chunk), u32, u32, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -155,6 +161,23 @@ def _mean(mu, chunk):
     return mu
 
 
+def _local(local, chunk, mu=None, sg_index=None):
+    """dq_local for a tensor of the chunk's entries (sg_index None) or for the original tensor whose
+    super-groups sg_index (int32, one per super-group of the chunk) picks; None stays None."""
+    if local is None:
+        return None
+    if sg_index is None:
+        if local.numel() != _entries(chunk):
+            raise DqError("local slice does not match the chunk")
+    else:
+        if sg_index.dtype != torch.int32 or sg_index.numel() != sum(chunk.n_sg) or local.numel() % 256:
+            raise DqError("sg_index is int32, one per super-group of the chunk")
+        if sg_index.numel() and not 0 <= int(sg_index.min()) <= int(sg_index.max()) < local.numel() // 256:
+            raise DqError("sg_index points outside the tensor")
+    d, m, x = _ptr(local), _ptr(_mean(mu, chunk)), _ptr(sg_index)
+    return C.byref(Local(d, _dtype(local), m, x))
+
+
 class Context:
     """dq_ctx: level tables on the device + PRNG key (seed, round) + worker count."""
 
@@ -175,51 +198,48 @@ class Context:
     def set_round(self, r):
         _check(lib().dq_set_round(self.h, r))
 
-    def dq_compress(self, local, chunk, rank, packed_out=None, mu=None):
-        if local.numel() != _entries(chunk):
-            raise DqError("local slice does not match the chunk")
+    def dq_compress(self, local, chunk, rank, packed_out=None, mu=None, sg_index=None):
+        loc = _local(local, chunk, mu, sg_index)
         if packed_out is None:
             packed_out = torch.zeros(dq_packed_bytes(chunk), dtype=torch.uint8, device=local.device)
         if packed_out.numel() < dq_packed_bytes(chunk):
             raise DqError("packed_out too small")
-        _check(lib().dq_compress(self.h, _ptr(local), _dtype(local), _ptr(_mean(mu, chunk)), C.byref(chunk), rank,
-                                 _ptr(packed_out), _stream()))
+        _check(lib().dq_compress(self.h, loc, C.byref(chunk), rank, _ptr(packed_out), _stream()))
         return packed_out
 
-    def dq_dar_hop(self, packed_in, local, chunk, rank, packed_out=None, mu=None):
-        if local.numel() != _entries(chunk) or packed_in.numel() < dq_packed_bytes(chunk):
+    def dq_dar_hop(self, packed_in, local, chunk, rank, packed_out=None, mu=None, sg_index=None):
+        loc = _local(local, chunk, mu, sg_index)
+        if packed_in.numel() < dq_packed_bytes(chunk):
             raise DqError("buffers do not match the chunk")
         if packed_out is None:
             packed_out = torch.zeros(dq_packed_bytes(chunk), dtype=torch.uint8, device=local.device)
         if packed_out.numel() < dq_packed_bytes(chunk):
             raise DqError("packed_out too small")
-        _check(lib().dq_dar_hop(self.h, _ptr(packed_in), _ptr(local), _dtype(local), _ptr(_mean(mu, chunk)),
-                                C.byref(chunk), rank, _ptr(packed_out), _stream()))
+        _check(lib().dq_dar_hop(self.h, _ptr(packed_in), loc, C.byref(chunk), rank, _ptr(packed_out), _stream()))
         return packed_out
 
-    def dq_decompress(self, packed_in, chunk, local=None, out=None, mu=None):
-        if packed_in.numel() < dq_packed_bytes(chunk) or (local is not None and local.numel() != _entries(chunk)):
+    def dq_decompress(self, packed_in, chunk, local=None, out=None, mu=None, sg_index=None):
+        loc = _local(local, chunk, mu, sg_index)
+        if packed_in.numel() < dq_packed_bytes(chunk):
             raise DqError("buffers do not match the chunk")
         if out is None:
             out = torch.empty(_entries(chunk), dtype=torch.float32, device=packed_in.device)
         if out.numel() != _entries(chunk) or out.dtype != torch.float32:
             raise DqError("out must be float32 with one element per entry")
-        _check(lib().dq_decompress(self.h, _ptr(packed_in), _ptr(local), 0 if local is None else _dtype(local),
-                                   _ptr(_mean(mu, chunk)), C.byref(chunk), _ptr(out), _stream()))
+        _check(lib().dq_decompress(self.h, _ptr(packed_in), loc, C.byref(chunk), _ptr(out), _stream()))
         return out
 
-
-    def dq_decompress_restore(self, packed_in, chunk, origin, out_base, local=None, mu=None, mu_back=None):
+    def dq_decompress_restore(self, packed_in, chunk, origin, out_base, local=None, mu=None, mu_back=None, sg_index=None):
         """Decompress (+ local - mu) with every super-group written to out_base[origin[j]] and
         n_workers * mu_back[j] added: the restore fused into the sink's kernel."""
-        if packed_in.numel() < dq_packed_bytes(chunk) or (local is not None and local.numel() != _entries(chunk)):
+        loc = _local(local, chunk, mu, sg_index)
+        if packed_in.numel() < dq_packed_bytes(chunk):
             raise DqError("buffers do not match the chunk")
         if origin.dtype != torch.int32 or origin.numel() != sum(chunk.n_sg):
             raise DqError("origin is int32, one per super-group of the chunk")
         if out_base.dtype != torch.float32 or (origin.numel() and out_base.numel() < (int(origin.max()) + 1) * 256):
             raise DqError("out_base is float32 and holds every destination super-group")
-        _check(lib().dq_decompress_restore(self.h, _ptr(packed_in), _ptr(local), 0 if local is None else _dtype(local),
-                                           _ptr(_mean(mu, chunk)), C.byref(chunk), _ptr(origin),
+        _check(lib().dq_decompress_restore(self.h, _ptr(packed_in), loc, C.byref(chunk), _ptr(origin),
                                            _ptr(_mean(mu_back, chunk)), _ptr(out_base), _stream()))
         return out_base
 
@@ -264,10 +284,11 @@ class Replay:
     """dq_replay: a prepared ring / butterfly / chain schedule over N simulated workers."""
 
     def __init__(self, ctx, topology, codec, worker_grads, n_sg_bucket, n_sg_by_width=None, n_buckets=1, first_sg=0,
-                 all_gather=False, mu=None, origin=None):
+                 all_gather=False, mu=None, origin=None, inputs_in_original_order=False):
         """mu: None, or the float32 means of all n_buckets * n_sg_bucket super-groups in reordered order.
         origin: None, or int32 [n_buckets * n_sg_bucket] (from dq_reorder_mean): the result is then written
-        in the original order with the means added back."""
+        in the original order with the means added back.  inputs_in_original_order (needs origin): the
+        worker gradients are the original tensors; the kernels gather their super-groups through origin."""
         self.ctx = ctx
         self.mu = mu
         self.origin = origin
@@ -285,7 +306,7 @@ class Replay:
                     flat[4 * b + k] = int(n_sg_by_width[b][k])
         self._widths = flat
         desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg,
-                          1 if all_gather else 0, _ptr(mu), _ptr(origin))
+                          1 if all_gather else 0, _ptr(mu), _ptr(origin), 1 if inputs_in_original_order else 0)
         self.desc = desc
         entries = n_sg_bucket * 256 * n_buckets
         for g in self.grads:
@@ -418,7 +439,7 @@ def dq_pipelined_stage_bytes(chunk, block_sg):
 
 
 def dq_dar_hop_pipelined(ctx, wire_in, local, chunk, rank, block_sg, compute_stream, copy_stream, stage=None,
-                         wire_out=None, mu=None):
+                         wire_out=None, mu=None, sg_index=None):
     """One hop of a chunk in blocks of block_sg super-groups: block i is encoded on compute_stream
     while block i-1 travels (a device copy) on copy_stream.  wire_in None: the first hop."""
     dev = local.device
@@ -427,7 +448,7 @@ def dq_dar_hop_pipelined(ctx, wire_in, local, chunk, rank, block_sg, compute_str
         stage = torch.zeros(dq_pipelined_stage_bytes(chunk, block_sg), dtype=torch.uint8, device=dev)
     if wire_out is None:
         wire_out = torch.zeros(dq_pipelined_wire_bytes(chunk, block_sg), dtype=torch.uint8, device=dev)
-    _check(lib().dq_dar_hop_pipelined(ctx.h, _ptr(wire_in), _ptr(local), _dtype(local), _ptr(_mean(mu, chunk)),
+    _check(lib().dq_dar_hop_pipelined(ctx.h, _ptr(wire_in), _local(local, chunk, mu, sg_index),
                                       C.byref(chunk), rank, block_sg,
                                       _ptr(stage), _ptr(wire_out), C.c_void_p(compute_stream.cuda_stream),
                                       C.c_void_p(copy_stream.cuda_stream)))

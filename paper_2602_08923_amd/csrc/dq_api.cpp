@@ -269,67 +269,69 @@ size_t dq_packed_bytes(const dq_chunk *ch) {
   return (sz + 15) & ~(size_t)15;
 }
 
-dq_status dq_compress(dq_ctx *ctx, const void *local, dq_dtype dtype, const float *mu_or_null, const dq_chunk *chunk,
-                      uint32_t rank, void *packed_out, void *hip_stream) {
+// Checks a local operand and fills the job's local fields from it.
+static dq_status take_local(const dq_local *l, dq::Job *j) {
+  if (!l->data || (l->dtype != DQ_F32 && l->dtype != DQ_BF16)) return DQ_EINVAL;
+  if (!aligned16(l->data) || !aligned4(l->mu) || !aligned4(l->sg_index)) return DQ_EALIGN;
+  j->local = l->data;
+  j->mu = l->mu;
+  j->src = l->sg_index;
+  return DQ_OK;
+}
+
+dq_status dq_compress(dq_ctx *ctx, const dq_local *local, const dq_chunk *chunk, uint32_t rank, void *packed_out,
+                      void *hip_stream) {
   dq_status st = check_chunk(ctx, chunk, rank);
   if (st != DQ_OK) return st;
   if (chunk_sgs(chunk) == 0) return DQ_OK;  // nothing to do
-  if (!local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
-  if (!aligned16(local) || !aligned16(packed_out) || !aligned4(mu_or_null)) return DQ_EALIGN;
-  const dq::Job j = dq::make_job(nullptr, local, mu_or_null, packed_out, chunk->first_sg, chunk->n_sg, rank);
-  return hip_ok(dq::launch_one(dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream))
-             ? DQ_OK
-             : DQ_EHIP;
+  if (!local || !packed_out) return DQ_EINVAL;
+  if (!aligned16(packed_out)) return DQ_EALIGN;
+  dq::Job j = dq::make_job(nullptr, nullptr, nullptr, packed_out, chunk->first_sg, chunk->n_sg, rank);
+  if ((st = take_local(local, &j)) != DQ_OK) return st;
+  return dq::hip_status(dq::launch_one(dq::kCompress, local->dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream));
 }
 
-dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const void *local, dq_dtype dtype, const float *mu_or_null,
-                     const dq_chunk *chunk, uint32_t rank, void *packed_out, void *hip_stream) {
+dq_status dq_dar_hop(dq_ctx *ctx, const void *packed_in, const dq_local *local, const dq_chunk *chunk, uint32_t rank,
+                     void *packed_out, void *hip_stream) {
   dq_status st = check_chunk(ctx, chunk, rank);
   if (st != DQ_OK) return st;
   if (chunk_sgs(chunk) == 0) return DQ_OK;
-  if (!packed_in || !local || !packed_out || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
-  if (!aligned16(packed_in) || !aligned16(local) || !aligned16(packed_out) || !aligned4(mu_or_null)) return DQ_EALIGN;
-  const dq::Job j = dq::make_job((const uint8_t *)packed_in, local, mu_or_null, packed_out, chunk->first_sg, chunk->n_sg, rank);
-  return hip_ok(dq::launch_one(dq::kDar, dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream)) ? DQ_OK
-                                                                                                          : DQ_EHIP;
+  if (!packed_in || !local || !packed_out) return DQ_EINVAL;
+  if (!aligned16(packed_in) || !aligned16(packed_out)) return DQ_EALIGN;
+  dq::Job j = dq::make_job((const uint8_t *)packed_in, nullptr, nullptr, packed_out, chunk->first_sg, chunk->n_sg, rank);
+  if ((st = take_local(local, &j)) != DQ_OK) return st;
+  return dq::hip_status(dq::launch_one(dq::kDar, local->dtype, true, j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream));
 }
 
-dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
-                        const float *mu_or_null, const dq_chunk *chunk, float *out, void *hip_stream) {
+dq_status dq_decompress(dq_ctx *ctx, const void *packed_in, const dq_local *local_or_null, const dq_chunk *chunk,
+                        float *out, void *hip_stream) {
   dq_status st = check_chunk(ctx, chunk, 0);
   if (st != DQ_OK) return st;
   if (chunk_sgs(chunk) == 0) return DQ_OK;
   if (!packed_in || !out) return DQ_EINVAL;
-  if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
-  if (!aligned16(packed_in) || !aligned16(out) || !aligned16(local_or_null) || !aligned4(mu_or_null)) return DQ_EALIGN;
-  const dq::Job j = dq::make_job((const uint8_t *)packed_in, local_or_null, local_or_null ? mu_or_null : nullptr, out,
-                                 chunk->first_sg, chunk->n_sg, 0);
-  return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->grid_blocks,
-                               (hipStream_t)hip_stream))
-             ? DQ_OK
-             : DQ_EHIP;
+  if (!aligned16(packed_in) || !aligned16(out)) return DQ_EALIGN;
+  dq::Job j = dq::make_job((const uint8_t *)packed_in, nullptr, nullptr, out, chunk->first_sg, chunk->n_sg, 0);
+  if (local_or_null && (st = take_local(local_or_null, &j)) != DQ_OK) return st;
+  // a gathered local cannot be accumulated in place: other super-groups' inputs would be overwritten
+  if (local_or_null && local_or_null->sg_index && local_or_null->data == (const void *)out) return DQ_EINVAL;
+  return dq::hip_status(dq::launch_one(dq::kDecompress, local_or_null ? local_or_null->dtype : DQ_F32, local_or_null != nullptr,
+                                       j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream));
 }
 
-dq_status dq_decompress_restore(dq_ctx *ctx, const void *packed_in, const void *local_or_null, dq_dtype dtype,
-                                const float *mu_or_null, const dq_chunk *chunk, const uint32_t *origin,
-                                const float *mu_back_or_null, float *out_base, void *hip_stream) {
+dq_status dq_decompress_restore(dq_ctx *ctx, const void *packed_in, const dq_local *local_or_null, const dq_chunk *chunk,
+                                const uint32_t *origin, const float *mu_back_or_null, float *out_base, void *hip_stream) {
   dq_status st = check_chunk(ctx, chunk, 0);
   if (st != DQ_OK) return st;
   if (chunk_sgs(chunk) == 0) return DQ_OK;
   if (!packed_in || !out_base || !origin) return DQ_EINVAL;
-  if (local_or_null && dtype != DQ_F32 && dtype != DQ_BF16) return DQ_EINVAL;
-  if (local_or_null == (const void *)out_base) return DQ_EINVAL;  // scattered stores: no in-place accumulation
-  if (!aligned16(packed_in) || !aligned16(out_base) || !aligned16(local_or_null) || !aligned4(mu_or_null) ||
-      !aligned4(origin) || !aligned4(mu_back_or_null))
-    return DQ_EALIGN;
-  dq::Job j = dq::make_job((const uint8_t *)packed_in, local_or_null, local_or_null ? mu_or_null : nullptr, out_base,
-                           chunk->first_sg, chunk->n_sg, 0);
+  if (!aligned16(packed_in) || !aligned16(out_base) || !aligned4(origin) || !aligned4(mu_back_or_null)) return DQ_EALIGN;
+  dq::Job j = dq::make_job((const uint8_t *)packed_in, nullptr, nullptr, out_base, chunk->first_sg, chunk->n_sg, 0);
+  if (local_or_null && (st = take_local(local_or_null, &j)) != DQ_OK) return st;
+  if (local_or_null && local_or_null->data == (const void *)out_base) return DQ_EINVAL;  // scattered stores: not in place
   j.dest = origin;
   j.back = mu_back_or_null;
-  return hip_ok(dq::launch_one(dq::kDecompress, dtype, local_or_null != nullptr, j, ctx->params, ctx->grid_blocks,
-                               (hipStream_t)hip_stream))
-             ? DQ_OK
-             : DQ_EHIP;
+  return dq::hip_status(dq::launch_one(dq::kDecompress, local_or_null ? local_or_null->dtype : DQ_F32, local_or_null != nullptr,
+                                       j, ctx->params, ctx->grid_blocks, (hipStream_t)hip_stream));
 }
 
 }  // extern "C"
@@ -381,17 +383,19 @@ size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg) {
   return 2 * biggest;
 }
 
-dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *local, dq_dtype dtype,
-                               const float *mu_or_null, const dq_chunk *chunk, uint32_t rank, uint32_t block_sg,
-                               void *stage, void *wire_out, void *compute_stream, void *copy_stream) {
+dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
+                               uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
+                               void *copy_stream) {
   dq_status st = check_chunk(ctx, chunk, rank);
   if (st != DQ_OK) return st;
   const uint64_t n = chunk_sgs(chunk);
   if (n == 0) return DQ_OK;
-  if (!local || !stage || !wire_out || block_sg == 0 || (dtype != DQ_F32 && dtype != DQ_BF16)) return DQ_EINVAL;
+  if (!local || !stage || !wire_out || block_sg == 0) return DQ_EINVAL;
   if (compute_stream == copy_stream) return DQ_EINVAL;  // the overlap needs two streams
-  if (!aligned16(wire_in) || !aligned16(local) || !aligned16(stage) || !aligned16(wire_out) || !aligned4(mu_or_null))
-    return DQ_EALIGN;
+  if (!aligned16(wire_in) || !aligned16(stage) || !aligned16(wire_out)) return DQ_EALIGN;
+  dq::Job whole = dq::make_job(nullptr, nullptr, nullptr, nullptr, chunk->first_sg, chunk->n_sg, rank);
+  if ((st = take_local(local, &whole)) != DQ_OK) return st;
+  const dq_dtype dtype = local->dtype;
   hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
   if (!ctx->have_events) {
     for (int i = 0; i < 2; ++i)
@@ -414,10 +418,12 @@ dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const void *loc
     // the kernels do not write the padding at the end of a packed block: clear the last 16 bytes first,
     // or a block would carry bytes of the one that used this half before
     if (bytes >= 16 && !hip_ok(hipMemsetAsync(stg + bytes - 16, 0, 16, cs))) return DQ_EHIP;
-    const dq::Job j = dq::make_job(wire_in ? static_cast<const uint8_t *>(wire_in) + wire_off : nullptr,
-                                   static_cast<const uint8_t *>(local) + b * (uint64_t)block_sg * 256 * es,
-                                   mu_or_null ? mu_or_null + b * (uint64_t)block_sg : nullptr, stg, blk.first_sg,
-                                   blk.n_sg, rank);
+    // block b of the chunk: its slice of a contiguous local, or its slice of the indices into a gathered one
+    const uint64_t sg_first = b * (uint64_t)block_sg;
+    dq::Job j = dq::make_job(wire_in ? static_cast<const uint8_t *>(wire_in) + wire_off : nullptr,
+                             whole.src ? whole.local : static_cast<const uint8_t *>(whole.local) + sg_first * 256 * es,
+                             whole.mu ? whole.mu + sg_first : nullptr, stg, blk.first_sg, blk.n_sg, rank);
+    j.src = whole.src ? whole.src + sg_first : nullptr;
     if (!hip_ok(dq::launch_one(wire_in ? dq::kDar : dq::kCompress, dtype, true, j, ctx->params, ctx->grid_blocks, cs)))
       return DQ_EHIP;
     if (!hip_ok(hipEventRecord(ctx->stage_filled[slot], cs)) || !hip_ok(hipStreamWaitEvent(xs, ctx->stage_filled[slot], 0)) ||

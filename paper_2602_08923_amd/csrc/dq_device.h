@@ -21,6 +21,8 @@ struct Job {
   const uint8_t *in;   // packed partial sum (DAR, decompress) or nullptr (compress)
   const void *local;   // local slice, may be nullptr for decompress
   const float *mu;     // one mean per super-group of the chunk, taken off the local entries, or nullptr
+  const uint32_t *src; // per super-group of the chunk: which super-group of `local` holds its entries
+                       // (nullptr: `local` holds the chunk's super-groups in chunk order)
   void *out;           // packed (compress, DAR) or fp32 (decompress)
   const uint32_t *dest; // decompress: per super-group of the chunk, the super-group index in `out` it is written to
                         // (nullptr: the chunk's own order, from out[0])
@@ -33,7 +35,7 @@ struct Job {
 inline Job make_job(const uint8_t *in, const void *local, const float *mu, void *out, uint64_t first_sg,
                     const uint32_t n_sg[4], uint32_t rank) {
   Job j;
-  j.in = in; j.local = local; j.mu = mu; j.out = out; j.dest = nullptr; j.back = nullptr;
+  j.in = in; j.local = local; j.mu = mu; j.src = nullptr; j.out = out; j.dest = nullptr; j.back = nullptr;
   j.first_sg = first_sg;
   for (int w = 0; w < 4; ++w) j.n_sg[w] = n_sg[w];
   j.rank = rank;

@@ -205,6 +205,46 @@ __device__ __forceinline__ float c255_over_sf(uint32_t sfb, uint32_t rec0) {
 __device__ __forceinline__ float local_mean(const Job &job, size_t first_entry, uint32_t row) {
   return job.mu ? gld<float>(job.mu + (first_entry / kSG) + row) : 0.0f;
 }
+// A lane's 16 local entries (group g of the super-group in row `row` of the tile) as raw 128-bit words.
+// Without job.src they sit in the chunk's own order: a wave-uniform base plus a small lane offset.
+// With job.src the super-group lives at index src[...] of `local` (the reorder of Section 3.5 done by
+// addressing: the kernel gathers whole super-groups, 512 B or 1 KB each, from the original tensor).
+template <typename LT>
+__device__ __forceinline__ void load_local(const Job &job, size_t first_entry, uint32_t row, uint32_t g,
+                                           uint4 (&loc)[sizeof(LT) == 4 ? 4 : 2]) {
+  constexpr int kWords = sizeof(LT) == 4 ? 4 : 2;  // 128-bit words per group
+  const LT *base = static_cast<const LT *>(job.local);
+  if (job.src) {
+    const size_t sg = gld<uint32_t>(job.src + first_entry / kSG + row);
+    const uint4 *p = reinterpret_cast<const uint4 *>(base + sg * kSG) + g * kWords;
+#pragma unroll
+    for (int i = 0; i < kWords; ++i) loc[i] = gld16(p + i);
+  } else {
+    const uint4 *p = reinterpret_cast<const uint4 *>(base + first_entry) + (row * 16 + g) * kWords;
+#pragma unroll
+    for (int i = 0; i < kWords; ++i) loc[i] = gld16(p + i);
+  }
+}
+template <typename LT>
+__device__ __forceinline__ void widen_local(const uint4 (&loc)[sizeof(LT) == 4 ? 4 : 2], float (&v)[16]) {
+  if constexpr (sizeof(LT) == 4) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[4 * i] = u2f(loc[i].x); v[4 * i + 1] = u2f(loc[i].y);
+      v[4 * i + 2] = u2f(loc[i].z); v[4 * i + 3] = u2f(loc[i].w);
+    }
+  } else {  // bf16 widens exactly
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t w[4] = {loc[i].x, loc[i].y, loc[i].z, loc[i].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[8 * i + 2 * j] = u2f(w[j] << 16);
+        v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
+      }
+    }
+  }
+}
 __device__ __forceinline__ void subtract_mean(const Job &job, float mu, float (&v)[16]) {
   if (job.mu) {
 #pragma unroll
@@ -228,17 +268,7 @@ __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePo
   const uint32_t rowc = min(lane >> 4, tb.last_row);  // idle rows redo the last SG and store nothing
   const uint32_t lg = rowc * 16 + (lane & 15u);       // group index inside the tile
   Fetch<B, KIND, LT> f;
-  if constexpr (sizeof(LT) == 4) {  // fp32: 4 x 128 bit
-    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) f.loc[i] = gld16(p + i);
-  } else {  // bf16: 2 x 128 bit
-    const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
-    f.loc[0] = gld16(p);
-    f.loc[1] = gld16(p + 1);
-  }
-  f.mu = local_mean(job, tb.first_entry, rowc);
-  if constexpr (KIND == kDar) {
+  if constexpr (KIND == kDar) {  // the incoming words first: with job.src the local loads wait for an index
     const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
     if constexpr (B == 2) {
       f.cw[0] = gld<uint32_t>(cp);
@@ -252,6 +282,8 @@ __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePo
     f.rg_in = gld<uint8_t>(job.in + tb.gs_off + lg);
     f.sf_in = gld<uint16_t>(job.in + tb.sf_off + rowc * 2);
   }
+  f.mu = local_mean(job, tb.first_entry, rowc);
+  load_local<LT>(job, tb.first_entry, rowc, lane & 15u, f.loc);
   return f;
 }
 
@@ -274,23 +306,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const uint32_t rec0 = lds0 + kOffRec * 4;
 
   float v[16];
-  if constexpr (sizeof(LT) == 4) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[4 * i] = u2f(f.loc[i].x); v[4 * i + 1] = u2f(f.loc[i].y);
-      v[4 * i + 2] = u2f(f.loc[i].z); v[4 * i + 3] = u2f(f.loc[i].w);
-    }
-  } else {  // bf16 widens exactly
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const uint32_t w[4] = {f.loc[i].x, f.loc[i].y, f.loc[i].z, f.loc[i].w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        v[8 * i + 2 * j] = u2f(w[j] << 16);
-        v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
-      }
-    }
-  }
+  widen_local<LT>(f.loc, v);
   subtract_mean(job, f.mu, v);
 
   if constexpr (KIND == kDar) {
@@ -467,31 +483,7 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
   const uint32_t rec0 = lds0 + kOffRec * 4;
   const uint32_t dec0 = dec_addr<B>(P, lds0);
 
-  float v[16];
-  if constexpr (kHasLocal) {
-    if constexpr (sizeof(LT) == 4) {
-      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint4 x = gld16(p + i);
-        v[4 * i] = u2f(x.x); v[4 * i + 1] = u2f(x.y); v[4 * i + 2] = u2f(x.z); v[4 * i + 3] = u2f(x.w);
-      }
-    } else {
-      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const uint4 x = gld16(p + i);
-        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          v[8 * i + 2 * j] = u2f(w[j] << 16);
-          v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
-        }
-      }
-    }
-  }
-  float mu = 0.0f;
-  if constexpr (kHasLocal) mu = local_mean(job, tb.first_entry, rowc);
+  // the incoming words first: with job.src the local loads wait for an index
   uint32_t cw[W::words];
   const uint8_t *cp = job.in + tb.code_off + lg * (2 * B);
   if constexpr (B == 2) {
@@ -505,6 +497,14 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
   }
   const uint32_t rg_in = gld<uint8_t>(job.in + tb.gs_off + lg);
   const uint32_t sf_in = gld<uint16_t>(job.in + tb.sf_off + rowc * 2);
+  float v[16];
+  float mu = 0.0f;
+  if constexpr (kHasLocal) {
+    uint4 loc[sizeof(LT) == 4 ? 4 : 2];
+    mu = local_mean(job, tb.first_entry, rowc);
+    load_local<LT>(job, tb.first_entry, rowc, lane & 15u, loc);
+    widen_local<LT>(loc, v);
+  }
   const float sfg = (float)rg_in * sf_over_255(sf_in, rec0);
   // after every load of the tile has been issued: the branch would otherwise hold the later loads back
   if constexpr (kHasLocal) subtract_mean(job, mu, v);
@@ -550,38 +550,21 @@ __device__ __forceinline__ void tile16(const Job &job, const Params &P, uint32_t
   const uint32_t row = lane >> 4;
   const uint32_t rowc = min(row, tb.last_row);
   const uint32_t lg = rowc * 16 + (lane & 15u);
-  float v[16];
-#pragma unroll
-  for (int k = 0; k < 16; ++k) v[k] = 0.0f;
-  if constexpr (kHasLocal) {
-    if constexpr (sizeof(LT) == 4) {
-      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const float *>(job.local) + tb.first_entry) + lg * 4;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint4 x = gld16(p + i);
-        v[4 * i] = u2f(x.x); v[4 * i + 1] = u2f(x.y); v[4 * i + 2] = u2f(x.z); v[4 * i + 3] = u2f(x.w);
-      }
-    } else {
-      const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(job.local) + tb.first_entry) + lg * 2;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const uint4 x = gld16(p + i);
-        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          v[8 * i + 2 * j] = u2f(w[j] << 16);
-          v[8 * i + 2 * j + 1] = u2f(w[j] & 0xFFFF0000u);
-        }
-      }
-    }
-  }
-  float mu = 0.0f;
-  if constexpr (kHasLocal) mu = local_mean(job, tb.first_entry, rowc);
   uint4 in[2];
-  if constexpr (KIND != kCompress) {
+  if constexpr (KIND != kCompress) {  // the incoming words first: with job.src the local loads wait for an index
     const uint4 *p = reinterpret_cast<const uint4 *>(job.in + tb.code_off) + lg * 2;
     in[0] = gld16(p);
     in[1] = gld16(p + 1);
+  }
+  float v[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) v[k] = 0.0f;
+  float mu = 0.0f;
+  if constexpr (kHasLocal) {
+    uint4 loc[sizeof(LT) == 4 ? 4 : 2];
+    mu = local_mean(job, tb.first_entry, rowc);
+    load_local<LT>(job, tb.first_entry, rowc, lane & 15u, loc);
+    widen_local<LT>(loc, v);
   }
   if constexpr (kHasLocal) subtract_mean(job, mu, v);  // after every load of the tile has been issued
   if constexpr (KIND != kCompress) {

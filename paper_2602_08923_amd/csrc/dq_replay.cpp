@@ -17,6 +17,7 @@ struct HostJob {
   const uint8_t *in;
   const void *local;
   const float *mu;
+  const uint32_t *src = nullptr;
   const uint32_t *dest = nullptr;
   const float *back = nullptr;
   void *out;
@@ -84,6 +85,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
   if (!mx && !d->n_sg_by_width) return DQ_EINVAL;
   if (mx && d->mu) return DQ_EINVAL;  // the MX codec has no normalization
   if (mx && d->origin) return DQ_EINVAL;
+  if (d->inputs_in_original_order && (!d->origin || d->topology == DQ_CHAIN)) return DQ_EINVAL;
   if ((reinterpret_cast<uintptr_t>(d->mu) & 3u) || (reinterpret_cast<uintptr_t>(d->origin) & 3u)) return DQ_EALIGN;
   if (d->topology == DQ_CHAIN) {
     if (d->n_buckets != 1) return DQ_EINVAL;
@@ -134,6 +136,13 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
     j.in = in;
     j.local = local;
     j.mu = (raw && d->mu) ? d->mu + (x.first_sg - d->first_sg) : nullptr;
+    if (raw && d->inputs_in_original_order) {
+      // `local` points at the chunk's place in a reordered bucket: step back to the bucket's start (the chunk
+      // begins (first_sg - first of the bucket) super-groups in) and let the kernel gather through origin
+      const uint64_t in_bucket = (x.first_sg - d->first_sg) % d->n_sg_bucket;
+      j.local = static_cast<const uint8_t *>(local) - in_bucket * 256 * es;
+      j.src = d->origin + (x.first_sg - d->first_sg);
+    }
     j.out = o;
     j.first_sg = x.first_sg;
     memcpy(j.n_sg, x.n_sg, sizeof(j.n_sg));
@@ -373,6 +382,7 @@ dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *
         for (size_t i = 0; i < t.size(); ++i) {
           const HostJob &j = L.jobs[i];
           t[i] = dq::make_job(j.in, j.local, j.mu, j.out, j.first_sg, j.n_sg, j.rank);
+          t[i].src = j.src;
           t[i].dest = j.dest;
           t[i].back = j.back;
         }

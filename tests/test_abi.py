@@ -53,7 +53,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert L.dq_create(ctypes.byref(cfg), ctypes.byref(h)) == B.DQ_EINVAL
     cfg = B.Config(1.0, 1.02, 0, 0, 4, 0, 0)   # degenerate level set
     assert L.dq_create(ctypes.byref(cfg), ctypes.byref(h)) == B.DQ_EINVAL
-    assert L.dq_compress(None, None, 0, None, None, 0, None, None) == B.DQ_EINVAL
+    assert L.dq_compress(None, None, None, 0, None, None) == B.DQ_EINVAL
     assert L.dq_reorder_mean(None, None, None, 4, 1, None, None, None) == B.DQ_EINVAL
     assert L.dq_mx_compress(1, None, 0, 256, None, None) == B.DQ_EINVAL
     assert L.dq_replay_n_steps(None) == 0

@@ -689,3 +689,100 @@ def test_replay_writes_the_restored_result(dev, topology, n, all_gather):
     rp.run()
     torch.cuda.synchronize()
     assert np.array_equal(host(rp.out).view(np.uint32), np.concatenate(want).view(np.uint32))
+
+
+# ----------------------------------------------------------------------------- reorder done by addressing
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_sg", [[5, 7, 3, 0], [1, 2, 1, 6], [0, 0, 1, 0], [9, 0, 4, 1]])
+def test_gathered_local_equals_reordered_local(dev, dtype, n_sg):
+    """dq_local.sg_index: the kernels read super-group j of the chunk at index sg_index[j] of the original tensor."""
+    n, first = 8, 500
+    total = sum(n_sg)
+    extra = 5                                                   # the tensor is larger than the chunk
+    rng = np.random.default_rng(total + 7)
+    orig = [make_local(rng, (total + extra) * 256, dtype) for _ in range(3)]
+    idx = rng.permutation(total + extra)[:total].astype(np.int32)
+    mu = (rng.standard_normal(total) * 2e-4).astype(np.float32)
+
+    def gathered(x):
+        return np.ascontiguousarray(x.reshape(-1, 256)[idx].reshape(-1))
+
+    idx_t, mu_t = torch.from_numpy(idx).to(dev), torch.from_numpy(mu).to(dev)
+    orc, ctx = O.Oracle(n, seed=23), B.Context(n, seed=23)
+    och, gch = O.make_chunk(first, n_sg), B.make_chunk(first, n_sg)
+    w1 = orc.compress(och, 1, gathered(orig[0]), mu)
+    g1 = ctx.dq_compress(to_dev(orig[0], dev), gch, 1, mu=mu_t, sg_index=idx_t)
+    assert np.array_equal(host(g1), w1)
+    w2 = orc.dar_hop(och, 2, w1, gathered(orig[1]), mu)
+    g2 = ctx.dq_dar_hop(g1, to_dev(orig[1], dev), gch, 2, mu=mu_t, sg_index=idx_t)
+    assert np.array_equal(host(g2), w2)
+    want = orc.decompress(och, w2, gathered(orig[2]), mu)
+    got = ctx.dq_decompress(g2, gch, local=to_dev(orig[2], dev), mu=mu_t, sg_index=idx_t)
+    assert np.array_equal(host(got).view(np.uint32), want.view(np.uint32))
+    with pytest.raises(B.DqError):
+        ctx.dq_compress(to_dev(orig[0], dev), gch, 1, sg_index=idx_t + 10 ** 6)      # outside the tensor
+
+
+@pytest.mark.parametrize("topology,n,all_gather", [("ring", 4, True), ("ring", 3, False), ("butterfly", 2, False),
+                                                   ("butterfly", 8, True), ("butterfly", 4, False)])
+def test_replay_on_original_tensors(dev, topology, n, all_gather):
+    """inputs_in_original_order: no reorder pass; gather on the way in, scatter and n * mu on the way out."""
+    from oracle import pp_oracle as P
+    J, buckets = 4 * n, 2
+    rng = np.random.default_rng(100 * n + all_gather)
+    d = J * 256
+    orig = [make_local(rng, d * buckets, "bf16") for _ in range(n)]
+    widths = [rng.choice(np.array([2, 4, 8, 16], np.uint8), J) for _ in range(buckets)]
+    pc = [P.positions(w) for w in widths]
+    pos = np.concatenate([p for p, _ in pc])
+    counts = [c for _, c in pc]
+    mu = (rng.standard_normal(J * buckets) * 2e-4).astype(np.float32)
+    mu_main = np.concatenate([P.reorder_mean(mu[b * J:(b + 1) * J], pos[b * J:(b + 1) * J], counts[b][3]) for b in range(buckets)])
+    origin = np.concatenate([np.argsort(pos[b * J:(b + 1) * J]) for b in range(buckets)]).astype(np.int32)
+    orc, ctx = O.Oracle(n, seed=29), B.Context(n, seed=29)
+    fn = O.ring_reduce_scatter if topology == "ring" else O.butterfly_reduce_scatter
+    want = []
+    for b in range(buckets):
+        pb = pos[b * J:(b + 1) * J]
+        re = [P.reorder(g[b * d:(b + 1) * d], pb) for g in orig]
+        rs = fn(orc, re, counts[b], first_sg=b * J, mu=mu_main[b * J:(b + 1) * J])
+        if all_gather:
+            rs = O.all_gather(orc, rs, counts[b], topology, first_sg=b * J)
+        want.append(P.restore(np.concatenate(rs), pb, mu_main[b * J:(b + 1) * J], n))
+    topo = B.DQ_RING if topology == "ring" else B.DQ_BUTTERFLY
+    rp = B.Replay(ctx, topo, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in orig], J, counts, n_buckets=buckets,
+                  all_gather=all_gather, mu=torch.from_numpy(mu_main).to(dev), origin=torch.from_numpy(origin).to(dev),
+                  inputs_in_original_order=True)
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out).view(np.uint32), np.concatenate(want).view(np.uint32))
+    with pytest.raises(B.DqError):                                                  # needs origin
+        B.Replay(ctx, topo, B.DQ_DYNAMIQ, [to_dev(g, dev) for g in orig], J, counts, n_buckets=buckets,
+                 inputs_in_original_order=True)
+
+
+def test_pipelined_hops_on_a_gathered_local(dev):
+    n, n_sg, first, block_sg = 4, [6, 9, 4, 3], 40, 5
+    total = sum(n_sg)
+    rng = np.random.default_rng(33)
+    orig = [make_local(rng, (total + 3) * 256, "bf16") for _ in range(2)]
+    idx = rng.permutation(total + 3)[:total].astype(np.int32)
+    mu = (rng.standard_normal(total) * 2e-4).astype(np.float32)
+    orc, ctx = O.Oracle(n, seed=15), B.Context(n, seed=15)
+    gch = B.make_chunk(first, n_sg)
+    blocks = block_chunks(n_sg, block_sg, first)
+    msgs = [None] * len(blocks)
+    for hop in range(2):
+        g = orig[hop].reshape(-1, 256)[idx].reshape(-1)
+        for i, (lo, hi, ch) in enumerate(blocks):
+            x = np.ascontiguousarray(g[lo * 256:hi * 256])
+            msgs[i] = orc.compress(ch, hop, x, mu[lo:hi]) if hop == 0 else orc.dar_hop(ch, hop, msgs[i], x, mu[lo:hi])
+    want = np.concatenate([np.concatenate([m, np.zeros((-len(m)) % 256, np.uint8)]) for m in msgs])
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    wire = None
+    for hop in range(2):
+        wire = B.dq_dar_hop_pipelined(ctx, wire, to_dev(orig[hop], dev), gch, hop, block_sg, s1, s2,
+                                      mu=torch.from_numpy(mu).to(dev), sg_index=torch.from_numpy(idx).to(dev))
+        s1.synchronize()
+    assert np.array_equal(host(wire), want)

@@ -126,11 +126,12 @@ def test_mean_subtraction_costs_no_accuracy_at_many_workers(dev):
     assert with_mean < 1.1 * without and with_mean < 1e-4, (with_mean, without)
 
 
-def test_fused_restore_equals_the_separate_pass(dev):
+def test_fused_reorder_and_restore_equal_the_separate_passes(dev):
     J, n = 1024, 8
     M = workloads.mixture_magnitudes(J, seed=4, device=dev)
     grads = [workloads.draw_mixture(M, w, seed=4) for w in range(n)]
     for kw in (dict(topology=B.DQ_RING), dict(topology=B.DQ_BUTTERFLY, max_width=16), dict(all_gather=False)):
-        a, _ = A.simulated_allreduce(grads, 6.0, seed=1, fused_restore=True, **kw)
-        b, _ = A.simulated_allreduce(grads, 6.0, seed=1, fused_restore=False, **kw)
-        assert torch.equal(a, b)
+        a, _ = A.simulated_allreduce(grads, 6.0, seed=1, **kw)                            # gather + scatter
+        b, _ = A.simulated_allreduce(grads, 6.0, seed=1, fused_restore=False, **kw)       # both passes separate
+        c, _ = A.simulated_allreduce(grads, 6.0, seed=1, fused_reorder=False, **kw)       # reorder pass, fused restore
+        assert torch.equal(a, b) and torch.equal(a, c)
