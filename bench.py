@@ -239,12 +239,31 @@ def main():
         t_stats, t_comb, t_alloc, t_mean = timed(f_stats), timed(f_combine), timed(f_alloc), timed(f_mean)
         t_reo, t_res = timed(f_reorder), timed(f_restore)
         c = state["counts"].cpu().numpy()[0]
+        # the same reduce-scatter from the ORIGINAL tensors: reorder pass + replay + restore pass against
+        # one replay whose kernels gather on the way in and scatter (with n * mu) on the way out
+        mm, origin = B.dq_reorder_mean(state["mu"], state["pos"], n_sg, state["counts"], with_origin=True)
+        gpu_counts = [[int(v) for v in c[:4]]]
+        re_all = [B.dq_reorder(raw[w], state["pos"], n_sg) for w in range(n)]
+        rp_sep = B.Replay(ctx, topo, codec, re_all, n_sg, gpu_counts, mu=mm)
+        rp_fused = B.Replay(ctx, topo, codec, raw, n_sg, gpu_counts, mu=mm, origin=origin, inputs_in_original_order=True)
+
+        def f_three_passes():
+            for w in range(n):
+                B.dq_reorder(raw[w], state["pos"], n_sg, out=re_all[w])
+            rp_sep.run()
+            B.dq_restore(rp_sep.out, state["pos"], n_sg, n, mu_main=mm, out=final)
+
+        t_three, t_fused = timed(f_three_passes), timed(rp_fused.run)
+        same = bool(torch.equal(final, rp_fused.out))
+        del re_all, rp_sep, rp_fused
         prepost = {
             "stats_us": round(t_stats, 1), "stats_GBps": round(n * entries * dtype_bytes / t_stats / 1e3, 1),
             "combine_us": round(t_comb, 1), "allocate_us": round(t_alloc, 1), "reorder_mean_us": round(t_mean, 1),
             "reorder_us": round(t_reo, 1), "reorder_GBps": round(n * entries * 2 * dtype_bytes / t_reo / 1e3, 1),
             "restore_us": round(t_res, 1), "restore_GBps": round(entries * 8 / t_res / 1e3, 1),
             "sg_by_width_2_4_8_gpu_allocation": [int(c[0]), int(c[1]), int(c[2])],   # W = {2,4,8}: c[3] (16-bit) is 0
+            "reorder_replay_restore_us": {"three_passes": round(t_three, 1), "fused_into_the_replay": round(t_fused, 1),
+                                          "same_bits": same},
             "note": "all workers per figure (stats and reorder: one launch per worker); GB/s = bytes read + written",
         }
         del raw, re_out, final

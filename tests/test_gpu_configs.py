@@ -32,7 +32,7 @@ def test_config2_ring8_bf16_25mb_full(dev):
     wl = workloads.CONFIGS[2]
     n = wl.n_workers
     grads = [workloads.draw(wl, w, 0, device="cpu") for w in range(n)]
-    re, counts, _ = prep.prepare_bucket(grads, wl.budget_bits, n)
+    re, counts, perm = prep.prepare_bucket(grads, wl.budget_bits, n)
     n_sg = wl.entries // 256
     assert sum(counts) == n_sg and counts[0] > 0 and counts[1] > 0   # ~4 bits: a mix of 2- and 4-bit SGs
     seed = 2024
@@ -48,6 +48,17 @@ def test_config2_ring8_bf16_25mb_full(dev):
     assert np.array_equal(got, want)
     true = sum(g.double() for g in re).numpy() - n * np.repeat(mu.double().numpy(), 256)
     assert ((got - true) ** 2).sum() / (true ** 2).sum() < 0.5   # ~4 bits, x100 outliers, 7 re-quantizations
+    # the same bucket from the ORIGINAL tensors: super-groups gathered on the way in, scattered to
+    # their original places with n * mu added on the way out -- restore(want) by definition
+    from oracle import pp_oracle as P
+    origin = perm.to(torch.int32).contiguous()                       # reordered[k] = original[perm[k]]
+    pos = np.empty(n_sg, np.uint32)
+    pos[perm.numpy()] = np.arange(n_sg, dtype=np.uint32)
+    rg = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [g.to(dev) for g in grads], n_sg, [counts], mu=mu.to(dev),
+                  origin=origin.to(dev), inputs_in_original_order=True)
+    rg.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rg.out).view(np.uint32), P.restore(want, pos, mu.numpy(), n).view(np.uint32))
 
 
 @pytest.mark.parametrize("fmt", [B.DQ_MXFP8_E4M3, B.DQ_MXFP6_E3M2, B.DQ_MXFP4_E2M1])
