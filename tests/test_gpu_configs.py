@@ -162,3 +162,51 @@ def test_config5_chain64_125m_sampled_runs(dev):
         want = orc.decompress(ch, msg, sl[n - 1], m)
         got = host(rp.out[s * 256:(s + run) * 256])
         assert np.array_equal(got, want), f"run at super-group {s}"
+
+
+def test_one_chunk_beyond_four_gibibytes(dev):
+    """A single chunk of 20.5 M super-groups (5.2 G entries): the local slice (10.5 GB), the 8-bit
+    codes (4.5 GB), the entry index and the fp32 result (21 GB) all pass 2^32 inside one job, so every
+    64-bit offset of the kernels is exercised.  Compress, a DAR hop and decompress-accumulate run at
+    full size; the oracle recomputes runs of super-groups around each 2^32 crossing, the width
+    boundaries and the ragged end."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * 2 ** 30:
+        pytest.skip("needs 60 GB of free device memory")
+    n = 8
+    counts = [1_000_003, 2_000_001, 17_500_002]                  # not multiples of a tile: ragged segment ends
+    n_sg = sum(counts)
+    entries = n_sg * 256
+    local = torch.empty(entries, dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20260208)
+    step = 1 << 28
+    for lo in range(0, entries, step):                           # sigma varies slowly along the tensor
+        hi = min(entries, lo + step)
+        x = torch.randn(hi - lo, generator=gen, device=dev) * (1e-3 * (1 + lo / entries))
+        local[lo:hi] = x.to(torch.bfloat16)
+        del x
+    mu = (torch.randn(n_sg, generator=gen, device=dev) * 1e-5).contiguous()
+    first = 3
+    seed = 99
+    ctx = B.Context(n, seed=seed)
+    gch = B.make_chunk(first, counts)
+    p1 = ctx.dq_compress(local, gch, 2, mu=mu)
+    p2 = ctx.dq_dar_hop(p1, local, gch, 5, mu=mu)
+    out = ctx.dq_decompress(p2, gch, local=local, mu=mu)
+    torch.cuda.synchronize()
+    edges = np.cumsum([0] + counts)
+    run = 96
+    code8_cross = int(edges[2]) + (2 ** 32 - 64 * counts[0] - 128 * counts[1]) // 256   # 8-bit code bytes pass 2^32 here
+    starts = [0, int(edges[1]) - 50, int(edges[2]) - 47, 2 ** 22 - 40, 2 ** 23 - 48, 2 ** 24 - 50, code8_cross - 45,
+              n_sg - run]
+    assert all(0 <= s <= n_sg - run for s in starts) and code8_cross < n_sg
+    orc = O.Oracle(n, seed=seed)
+    for s in starts:
+        cw = [int(max(0, min(s + run, edges[k + 1]) - max(s, edges[k]))) for k in range(3)]
+        ch = O.make_chunk(first + s, cw)
+        sl = workloads.to_numpy(local[s * 256:(s + run) * 256].cpu())
+        m = mu[s:s + run].cpu().numpy()
+        msg = orc.dar_hop(ch, 5, orc.compress(ch, 2, sl, m), sl, m)
+        want = orc.decompress(ch, msg, sl, m)
+        assert np.array_equal(host(out[s * 256:(s + run) * 256]).view(np.uint32), want.view(np.uint32)), f"run at super-group {s}"
