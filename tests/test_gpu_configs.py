@@ -210,3 +210,27 @@ def test_one_chunk_beyond_four_gibibytes(dev):
         msg = orc.dar_hop(ch, 5, orc.compress(ch, 2, sl, m), sl, m)
         want = orc.decompress(ch, msg, sl, m)
         assert np.array_equal(host(out[s * 256:(s + run) * 256]).view(np.uint32), want.view(np.uint32)), f"run at super-group {s}"
+
+
+def test_mx_beyond_four_gibibytes(dev):
+    """The MX codec on 5.2 G entries in one call (codes, local bytes, entry index and result pass 2^32)."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * 2 ** 30:
+        pytest.skip("needs 60 GB of free device memory")
+    fmt = B.DQ_MXFP8_E4M3
+    entries = (2 ** 32 + 2 ** 30 + 7 * 256)
+    local = torch.empty(entries, dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    step = 1 << 28
+    for lo in range(0, entries, step):
+        hi = min(entries, lo + step)
+        local[lo:hi] = (torch.randn(hi - lo, generator=gen, device=dev) * 1e-3).to(torch.bfloat16)
+    p2 = B.dq_mx_dar_hop(fmt, B.dq_mx_compress(fmt, local), local)
+    out = B.dq_mx_decompress(fmt, p2, entries, local=local)
+    torch.cuda.synchronize()
+    run = 4096
+    for s in (0, 2 ** 30 - 2048, 2 ** 31 - 2048, 2 ** 32 - 2048, entries - run):
+        sl = workloads.to_numpy(local[s:s + run].cpu())
+        want = O.mx_decompress(fmt, O.mx_dar_hop(fmt, O.mx_compress(fmt, sl), sl), run, sl)
+        assert np.array_equal(host(out[s:s + run]).view(np.uint32), want.view(np.uint32)), f"run at entry {s}"
