@@ -27,12 +27,12 @@ sys.path.insert(0, ROOT)
 # 2^30 bytes on the same box: FETCH_SIZE counts half the bytes read (x2.0), WRITE_SIZE all of
 # them (x1.0).  Key: (workload, codec).  The summary with the commands sits in profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    (2, 0): int((16268.0 * 2.0 + 6228.2 * 1.0) * 1024),
+    (2, 0): int((16260.5 * 2.0 + 6238.4 * 1.0) * 1024),
 }
 # Vector-ALU wave instructions per DAR launch, from `rocprofv3 --pmc SQ_INSTS_VALU` on the same
 # command (profiles/); one wave instruction is 64 lane operations.
 MEASURED_VALU_WAVE_INSTR = {
-    (2, 0): 5_913_642,
+    (2, 0): 5_818_511,
 }
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: lane operations per second the vector ALUs can issue
 VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12

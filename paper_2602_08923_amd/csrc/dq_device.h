@@ -74,7 +74,8 @@ enum Kind { kCompress = 0, kDar = 1, kDecompress = 2 };
 // kernel launchers (dq_kernels.hip); grid_blocks = thread blocks the GPU keeps resident at once
 hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t grid_blocks,
                       hipStream_t stream);
-hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, const Job *jobs_dev, uint32_t n_jobs,
+// gather: some job of the batch has a `src` (jobs without one still take the contiguous path)
+hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, bool gather, const Job *jobs_dev, uint32_t n_jobs,
                         uint32_t max_tiles_per_job, uint64_t total_tiles, const Params &p, uint32_t grid_blocks,
                         hipStream_t stream);
 

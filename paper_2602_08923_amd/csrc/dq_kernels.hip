@@ -209,21 +209,33 @@ __device__ __forceinline__ float local_mean(const Job &job, size_t first_entry, 
 // Without job.src they sit in the chunk's own order: a wave-uniform base plus a small lane offset.
 // With job.src the super-group lives at index src[...] of `local` (the reorder of Section 3.5 done by
 // addressing: the kernel gathers whole super-groups, 512 B or 1 KB each, from the original tensor).
+// Kernels are built twice: the plain local types know no job.src at all (the compiler would otherwise
+// merge the two paths' loads and pay a 64-bit per-lane address on both), the Gathered<> types look at it.
+template <typename T>
+struct Gathered { T x; };  // same size as T: sizeof(LT) keeps telling fp32 from bf16
+template <typename LT>
+struct IsGathered { static constexpr bool value = false; };
+template <typename T>
+struct IsGathered<Gathered<T>> { static constexpr bool value = true; };
+
 template <typename LT>
 __device__ __forceinline__ void load_local(const Job &job, size_t first_entry, uint32_t row, uint32_t g,
                                            uint4 (&loc)[sizeof(LT) == 4 ? 4 : 2]) {
   constexpr int kWords = sizeof(LT) == 4 ? 4 : 2;  // 128-bit words per group
-  const LT *base = static_cast<const LT *>(job.local);
-  if (job.src) {
-    const size_t sg = gld<uint32_t>(job.src + first_entry / kSG + row);
-    const uint4 *p = reinterpret_cast<const uint4 *>(base + sg * kSG) + g * kWords;
+  constexpr size_t kSgWords = kSG * sizeof(LT) / 16;
+  const uint4 *base = static_cast<const uint4 *>(job.local);
+  if constexpr (IsGathered<LT>::value) {
+    if (job.src) {
+      const size_t sg = gld<uint32_t>(job.src + first_entry / kSG + row);
+      const uint4 *p = base + sg * kSgWords + g * kWords;
 #pragma unroll
-    for (int i = 0; i < kWords; ++i) loc[i] = gld16(p + i);
-  } else {
-    const uint4 *p = reinterpret_cast<const uint4 *>(base + first_entry) + (row * 16 + g) * kWords;
-#pragma unroll
-    for (int i = 0; i < kWords; ++i) loc[i] = gld16(p + i);
+      for (int i = 0; i < kWords; ++i) loc[i] = gld16(p + i);
+      return;
+    }
   }
+  const uint4 *p = base + (first_entry / kSG) * kSgWords + (row * 16 + g) * kWords;
+#pragma unroll
+  for (int i = 0; i < kWords; ++i) loc[i] = gld16(p + i);
 }
 template <typename LT>
 __device__ __forceinline__ void widen_local(const uint4 (&loc)[sizeof(LT) == 4 ? 4 : 2], float (&v)[16]) {
@@ -771,35 +783,38 @@ hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, uint64
 
 }  // namespace
 
+// LT for a local of `dtype`, gathered through job.src or not
+#define DQ_DISPATCH_LOCAL(CALL, KINDV)                                                        \
+  (gather ? (f32 ? CALL<KINDV, Gathered<float>> ARGS : CALL<KINDV, Gathered<uint16_t>> ARGS) \
+          : (f32 ? CALL<KINDV, float> ARGS : CALL<KINDV, uint16_t> ARGS))
+
 hipError_t launch_one(Kind kind, dq_dtype dtype, bool has_local, const Job &job, const Params &p, uint32_t grid_blocks,
                       hipStream_t s) {
-  const bool f32 = dtype == DQ_F32;
+  const bool f32 = dtype == DQ_F32, gather = job.src != nullptr;
+#define ARGS (job, p, grid_blocks, s)
   switch (kind) {
-    case kCompress:
-      return f32 ? go_one<kCompress, float>(job, p, grid_blocks, s) : go_one<kCompress, uint16_t>(job, p, grid_blocks, s);
-    case kDar:
-      return f32 ? go_one<kDar, float>(job, p, grid_blocks, s) : go_one<kDar, uint16_t>(job, p, grid_blocks, s);
+    case kCompress: return DQ_DISPATCH_LOCAL(go_one, kCompress);
+    case kDar: return DQ_DISPATCH_LOCAL(go_one, kDar);
     default:
       if (!has_local) return go_one<kDecompress, NoLocal>(job, p, grid_blocks, s);
-      return f32 ? go_one<kDecompress, float>(job, p, grid_blocks, s) : go_one<kDecompress, uint16_t>(job, p, grid_blocks, s);
+      return DQ_DISPATCH_LOCAL(go_one, kDecompress);
   }
+#undef ARGS
 }
 
-hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, const Job *jobs, uint32_t n_jobs,
+hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, bool gather, const Job *jobs, uint32_t n_jobs,
                         uint32_t max_tiles, uint64_t total_tiles, const Params &p, uint32_t grid_blocks, hipStream_t s) {
   const bool f32 = dtype == DQ_F32;
+#define ARGS (jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s)
   switch (kind) {
-    case kCompress:
-      return f32 ? go_batch<kCompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s)
-                 : go_batch<kCompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
-    case kDar:
-      return f32 ? go_batch<kDar, float>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s)
-                 : go_batch<kDar, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
+    case kCompress: return DQ_DISPATCH_LOCAL(go_batch, kCompress);
+    case kDar: return DQ_DISPATCH_LOCAL(go_batch, kDar);
     default:
       if (!has_local) return go_batch<kDecompress, NoLocal>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
-      return f32 ? go_batch<kDecompress, float>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s)
-                 : go_batch<kDecompress, uint16_t>(jobs, n_jobs, max_tiles, total_tiles, p, grid_blocks, s);
+      return DQ_DISPATCH_LOCAL(go_batch, kDecompress);
   }
+#undef ARGS
 }
+#undef DQ_DISPATCH_LOCAL
 
 }  // namespace dq

@@ -30,6 +30,7 @@ struct Launch {
   dq::Kind kind;
   dq_dtype dtype;  // dtype of `local`
   bool has_local = true;  // false: decompress without accumulation
+  bool gather = false;    // some job reads its local super-groups through an index
   std::vector<HostJob> jobs;  // freed once the table is on the device
   uint32_t n_jobs = 0;
   size_t table_off = 0;  // byte offset of this launch's job table in scratch
@@ -315,6 +316,7 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
       L.n_jobs = (uint32_t)L.jobs.size();
       off += L.jobs.size() * (mx ? sizeof(dq::MxJob) : sizeof(dq::Job));
       for (const HostJob &j : L.jobs) {
+        if (j.src) L.gather = true;
         const uint32_t tiles = (j.n_sg[0] + 3) / 4 + (j.n_sg[1] + 3) / 4 + (j.n_sg[2] + 3) / 4 + (j.n_sg[3] + 3) / 4;
         const uint64_t e = ((uint64_t)j.n_sg[0] + j.n_sg[1] + j.n_sg[2] + j.n_sg[3]) * 256;
         if (tiles > L.max_tiles) L.max_tiles = tiles;
@@ -427,7 +429,7 @@ static dq_status run_step(dq_replay *plan, size_t i, hipStream_t s) {
                               reinterpret_cast<const dq::MxJob *>(plan->scratch + L.table_off),
                               L.n_jobs, L.max_entries, plan->ctx->n_cu, s);
     else
-      e = dq::launch_batch(L.kind, L.dtype, L.has_local, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
+      e = dq::launch_batch(L.kind, L.dtype, L.has_local, L.gather, reinterpret_cast<const dq::Job *>(plan->scratch + L.table_off),
                            L.n_jobs, L.max_tiles, L.total_tiles, plan->ctx->params, plan->ctx->grid_blocks, s);
     if (e != hipSuccess) return dq::hip_status(e);
   }
