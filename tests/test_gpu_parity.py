@@ -786,3 +786,32 @@ def test_pipelined_hops_on_a_gathered_local(dev):
                                       mu=torch.from_numpy(mu).to(dev), sg_index=torch.from_numpy(idx).to(dev))
         s1.synchronize()
     assert np.array_equal(host(wire), want)
+
+
+@pytest.mark.parametrize("all_gather", [False, True])
+def test_chain_replay_writes_the_restored_result(dev, all_gather):
+    from oracle import pp_oracle as P
+    n, n_sg = 5, [6, 9, 4, 3]
+    total = sum(n_sg)
+    rng = np.random.default_rng(55 + all_gather)
+    sl = [make_local(rng, total * 256, "bf16") for _ in range(n)]
+    mu = (rng.standard_normal(total) * 2e-4).astype(np.float32)
+    mu[total - n_sg[3]:] = 0
+    origin = rng.permutation(total).astype(np.int32)
+    orc, ctx = O.Oracle(n, seed=8), B.Context(n, seed=8)
+    och = O.make_chunk(9, n_sg)
+    msg = orc.compress(och, 0, sl[0], mu)
+    for i in range(1, n - 1):
+        msg = orc.dar_hop(och, i, msg, sl[i], mu)
+    res = orc.decompress(och, msg, sl[n - 1], mu)
+    if all_gather:
+        res = orc.decompress(och, orc.compress(och, n - 1, res))
+    want = P.restore(res, np.argsort(origin).astype(np.uint32), mu, n)
+    rc = B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, [to_dev(s, dev) for s in sl], total, [n_sg], first_sg=9,
+                  all_gather=all_gather, mu=torch.from_numpy(mu).to(dev), origin=torch.from_numpy(origin).to(dev))
+    rc.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rc.out).view(np.uint32), want.view(np.uint32))
+    with pytest.raises(B.DqError):          # a chain's slices are chunks, not buckets: no gathered inputs
+        B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, [to_dev(s, dev) for s in sl], total, [n_sg], first_sg=9,
+                 origin=torch.from_numpy(origin).to(dev), inputs_in_original_order=True)
