@@ -18,6 +18,10 @@
 // drawn by ONE wave-wide Philox call (each lane a different counter) and parked in LDS; a block
 // with few tiles draws for all its waves at once.  A chunk may end in a run of 16-bit
 // super-groups (raw bf16 values, Section 3.2): those tiles only add and round.
+// Three options ride on the job: per-super-group means taken off the local entries in fp32 where
+// they enter (Section 3.1), the local super-groups gathered from the original tensor through an
+// index (the reorder of Section 3.5 done by addressing), and, for decompress, every super-group
+// stored to its original place with the mean added back (the restore of Section 3.4, fused in).
 //
 // All arithmetic that decides a code is IEEE binary32 with explicit fused multiply-adds
 // only where written (this file is compiled with -ffp-contract=off and correctly rounded
@@ -348,8 +352,8 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const uint64_t gi = (tb.G0 + rowc) * 16 + g;  // global group index
   // stream 0: one byte per entry, private to the worker
   const U4 gam = philox4x32_10((uint32_t)gi, (uint32_t)(gi >> 32), P.round, job.rank & 0xFFFFu, P.key0, P.key1);
-  // parked per-SG draws: word 0 of the shared stream -> cyclic shift; byte g of the private
-  // stream -> this group's scale dither
+  // parked per-SG draws: word 0 of the shared stream -> the offset c of the permutation
+  // pi = (stride * rank + c + g) mod n; byte g of the private stream -> this group's scale dither
   const uint32_t perm_w0 = lds_ld1(stage + rowc * 32);
   const uint32_t sc_word = lds_ld1(stage + rowc * 32 + 16 + (g >> 2) * 4);
   const uint32_t scale_byte = (sc_word >> (8 * (g & 3u))) & 0xFFu;

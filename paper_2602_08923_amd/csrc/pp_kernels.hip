@@ -1,8 +1,8 @@
 // Steps before and after the main all-reduce stage, for gfx950: per-super-group statistics
 // (Section 3.1), their combination over workers with the bf16 exchange format (Sections 3.1,
-// 3.5), the three-width bit allocation with tied thresholds (Section 3.2, Appendix A), the
-// mean-subtracting reorder into increasing width order (Sections 3.1, 3.5) and the final
-// restore (Section 3.4, last paragraph).  All of them stream each entry once; the allocation
+// 3.5), the bit allocation with tied thresholds (Section 3.2, Appendix A), the reorder into
+// increasing width order (Section 3.5), the means the main stage subtracts in that order
+// (Section 3.1) and the final restore (Section 3.4, last paragraph).  All of them stream each entry once; the allocation
 // works on 4 bytes per super-group.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
