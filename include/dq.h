@@ -182,7 +182,8 @@ size_t dq_replay_scratch_bytes(const dq_ctx *ctx, const dq_replay_desc *desc);
 dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *const *worker_grads, void *scratch,
                            size_t scratch_bytes, float *out, dq_replay **plan);
 uint32_t dq_replay_n_steps(const dq_replay *plan);
-/* Enqueue every step of the schedule.  step_ms: NULL, or a host array of n_steps floats that
+/* Enqueue every step of the schedule: kernel launches only (no allocation, no memset, no
+ * synchronisation unless step_ms is given), so a caller may capture the call in a HIP graph.  step_ms: NULL, or a host array of n_steps floats that
  * receives each step's duration measured with HIP events on `hip_stream` (this variant
  * synchronises the stream before returning). */
 dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream);

@@ -815,3 +815,36 @@ def test_chain_replay_writes_the_restored_result(dev, all_gather):
     with pytest.raises(B.DqError):          # a chain's slices are chunks, not buckets: no gathered inputs
         B.Replay(ctx, B.DQ_CHAIN, B.DQ_DYNAMIQ, [to_dev(s, dev) for s in sl], total, [n_sg], first_sg=9,
                  origin=torch.from_numpy(origin).to(dev), inputs_in_original_order=True)
+
+
+def test_replay_can_be_captured_in_a_graph(dev):
+    """The replay only launches kernels (no allocation, no memset, no synchronisation), so a caller may
+    capture it in a HIP graph; every replay of the graph, with eager work between, gives the eager bytes."""
+    n, J = 8, 64
+    counts = [[10, 30, 20, 4]]
+    rng = np.random.default_rng(91)
+    grads = [to_dev(make_local(rng, J * 256, "bf16"), dev) for _ in range(n)]
+    mu = torch.from_numpy((rng.standard_normal(J) * 2e-4).astype(np.float32)).to(dev)
+    origin = torch.from_numpy(rng.permutation(J).astype(np.int32)).to(dev)
+    ctx = B.Context(n, seed=4)
+    rp = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_DYNAMIQ, grads, J, counts, all_gather=True, mu=mu, origin=origin,
+                  inputs_in_original_order=True)
+    rp.run()
+    torch.cuda.synchronize()
+    ref = rp.out.clone()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        rp.run()                                        # warm the capture stream
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        rp.run_steps(0, rp.n_steps)
+    torch.cuda.synchronize()
+    for i in range(4):
+        rp.out.fill_(float(i))                          # eager work between the replays
+        scratch_probe = (grads[i] * 2).sum()            # a library reduction too
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(rp.out, ref), f"graph replay {i}"
+        assert torch.isfinite(scratch_probe)
