@@ -417,7 +417,7 @@ dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local 
     if (b >= 2 && !hip_ok(hipStreamWaitEvent(cs, ctx->stage_free[slot], 0))) return DQ_EHIP;
     // the kernels do not write the padding at the end of a packed block: clear the last 16 bytes first,
     // or a block would carry bytes of the one that used this half before
-    if (bytes >= 16 && !hip_ok(hipMemsetAsync(stg + bytes - 16, 0, 16, cs))) return DQ_EHIP;
+    if (bytes >= 16 && !hip_ok(dq::clear16(stg + bytes - 16, cs))) return DQ_EHIP;
     // block b of the chunk: its slice of a contiguous local, or its slice of the indices into a gathered one
     const uint64_t sg_first = b * (uint64_t)block_sg;
     dq::Job j = dq::make_job(wire_in ? static_cast<const uint8_t *>(wire_in) + wire_off : nullptr,

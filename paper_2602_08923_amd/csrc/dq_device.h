@@ -79,6 +79,9 @@ hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, bool gather, 
                         uint32_t max_tiles_per_job, uint64_t total_tiles, const Params &p, uint32_t grid_blocks,
                         hipStream_t stream);
 
+// 16 zero bytes at a 16-byte aligned device address, written by a kernel
+hipError_t clear16(void *p, hipStream_t stream);
+
 // DQ_OK, or DQ_EHIP after recording the error's text for dq_last_hip_error (dq_api.cpp)
 dq_status hip_status(hipError_t e);
 

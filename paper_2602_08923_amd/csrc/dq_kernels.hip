@@ -743,6 +743,12 @@ __global__ __launch_bounds__(kBlockThreads) void k_batch(const Job *jobs, Params
   run_job<KIND, LT>(job, P);
 }
 
+// 16 zero bytes at p (16-byte aligned): a fill kernel instead of a memset node, so that callers may
+// capture the launches around it in a graph
+__global__ void k_clear16(uint4 *p) {
+  if (threadIdx.x == 0) *p = uint4{0u, 0u, 0u, 0u};
+}
+
 uint32_t job_tiles(const Job &j) {
   return (j.n_sg[0] + kWaveSGs - 1) / kWaveSGs + (j.n_sg[1] + kWaveSGs - 1) / kWaveSGs +
          (j.n_sg[2] + kWaveSGs - 1) / kWaveSGs + (j.n_sg[3] + kWaveSGs - 1) / kWaveSGs;
@@ -820,5 +826,10 @@ hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, bool gather, 
 #undef ARGS
 }
 #undef DQ_DISPATCH_LOCAL
+
+hipError_t clear16(void *p, hipStream_t s) {
+  hipLaunchKernelGGL(k_clear16, dim3(1), dim3(64), 0, s, static_cast<uint4 *>(p));
+  return hipGetLastError();
+}
 
 }  // namespace dq
