@@ -55,6 +55,17 @@ def algorithmic_bytes_per_entry(codec, counts_total, n_sg_total, dtype_bytes, ki
     return packed + dtype_bytes + 4.0  # decompress-accumulate: packed + local in, fp32 out
 
 
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -314,7 +325,7 @@ def main():
             "sample": f"{hops} DAR hops over {sample_sg} super-groups ({sample_sg * 256} entries) of worker slices 1-2, "
                       f"{t_cpu:.1f} s single-threaded C oracle",
             "ns_per_entry_hop": round(t_cpu / cpu_entries * 1e9, 2),
-            "host_cpus_visible": os.cpu_count(),
+            "host_cpus_visible": os.cpu_count(), "host_cpu_model": _cpu_model(),
         }
 
     out = {
