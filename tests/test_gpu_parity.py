@@ -724,15 +724,16 @@ def test_gathered_local_equals_reordered_local(dev, dtype, n_sg):
         ctx.dq_compress(to_dev(orig[0], dev), gch, 1, sg_index=idx_t + 10 ** 6)      # outside the tensor
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("topology,n,all_gather", [("ring", 4, True), ("ring", 3, False), ("butterfly", 2, False),
                                                    ("butterfly", 8, True), ("butterfly", 4, False)])
-def test_replay_on_original_tensors(dev, topology, n, all_gather):
+def test_replay_on_original_tensors(dev, topology, n, all_gather, dtype):
     """inputs_in_original_order: no reorder pass; gather on the way in, scatter and n * mu on the way out."""
     from oracle import pp_oracle as P
     J, buckets = 4 * n, 2
     rng = np.random.default_rng(100 * n + all_gather)
     d = J * 256
-    orig = [make_local(rng, d * buckets, "bf16") for _ in range(n)]
+    orig = [make_local(rng, d * buckets, dtype) for _ in range(n)]
     widths = [rng.choice(np.array([2, 4, 8, 16], np.uint8), J) for _ in range(buckets)]
     pc = [P.positions(w) for w in widths]
     pos = np.concatenate([p for p, _ in pc])
