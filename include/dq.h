@@ -3,11 +3,13 @@
  * all-reduce (arxiv 2602.08923): first-hop compress, the fused
  * decompress-accumulate-recompress (DAR) hop, decompress(+accumulate), a driver that
  * replays ring / butterfly reduce-scatter hops for N simulated workers inside one
- * GPU's HBM, and the same three calls for the OCP-MX comparison codec.
+ * GPU's HBM, the same three calls for the OCP-MX comparison codec, and the steps on either
+ * side of the main stage (statistics, bit allocation, reorder, restore).
  *
  * Conventions shared by every call
  *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned
- *     (DQ_EALIGN otherwise).  Descriptor structs (dq_config, dq_chunk, dq_local, dq_replay_desc
+ *     (per-super-group arrays -- means, indices, statistics, positions -- 4-byte aligned;
+ *     DQ_EALIGN otherwise).  Descriptor structs (dq_config, dq_chunk, dq_local, dq_replay_desc
  *     and the arrays they point to) are HOST memory, read during the call only.
  *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
  *     and return without synchronising; the library allocates device memory only in
@@ -20,13 +22,15 @@
  *
  * Data model (paper Section 5 "configuration", Section 3.5): entries come in groups of
  * 16 sharing a u8 scale and super-groups (SG) of 256 = 16 groups sharing a bf16 scale and
- * a code width of 2, 4 or 8 bits.  A chunk is a run of SGs already reordered by increasing
- * width.  Packed chunk layout (structure of arrays, each array 16-byte aligned, SG order):
+ * a code width of 2, 4 or 8 bits (or 16: raw bf16).  A chunk is a run of SGs in increasing
+ * width order (its entries either reordered that way or picked from the original tensor
+ * through an index, see dq_local).  Packed chunk layout (structure of arrays, each array 16-byte aligned, SG order):
  *   [2-bit codes, 64 B per SG][4-bit codes, 128 B per SG][8-bit codes, 256 B per SG]
  *   [16-bit values, 512 B per SG: raw bf16, "16 bits corresponds to uncompressed values", Section 3.2]
  *   [group scales, 16 u8 per coded SG][SG scales, one u16 bf16 pattern per coded SG], rounded up
- *   to 16 B (the kernels never write those padding bytes); the coded SGs are those at 2, 4 and 8 bits.  A 16-bit SG has no scales and uses no
- *   random numbers: compress rounds to bf16 (nearest even), a DAR hop adds in fp32 and rounds back.
+ *   to 16 B (the kernels never write those padding bytes); the coded SGs are those at 2, 4 and
+ *   8 bits.  A 16-bit SG has no scales and uses no random numbers: compress rounds to bf16
+ *   (nearest even), a DAR hop adds in fp32 and rounds back.
  * Entry k of an SG sits at bit offset k*b of the SG's code block (little-endian);
  * code = sign << (b-1) | level index.
  */
