@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--topology", choices=["ring", "butterfly"], default="ring")
     ap.add_argument("--codec", choices=["dynamiq", "mxfp8"], default="dynamiq")
     ap.add_argument("--max-width", type=int, default=16, choices=[8, 16], help="W = {2,4,8} or {2,4,8,16} (the paper's setting here)")
+    ap.add_argument("--g4", type=float, default=1.3, help="1 + 2 eps^2 of the 4-bit level set")
+    ap.add_argument("--g8", type=float, default=1.02, help="1 + 2 eps^2 of the 8-bit level set")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     n, J = args.workers, args.sg
@@ -63,7 +65,7 @@ def main():
         resident.append(g)                               # original order: the kernels gather through `origin`
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ctx = B.Context(n, seed=1234 + args.seed)
+    ctx = B.Context(n, seed=1234 + args.seed, g4=args.g4, g8=args.g8)
     codec = B.DQ_DYNAMIQ if dynamiq else B.DQ_MXFP8_E4M3
     # the schedule's last launch writes the original order with the means added back (the restore, fused)
     rp = B.Replay(ctx, topo, codec, resident, J, by_width, all_gather=True, mu=mu_main if dynamiq else None,
@@ -77,7 +79,7 @@ def main():
     err = A.vnmse(out, truth)
     print(json.dumps({
         "workers": n, "super_groups_per_worker": J, "entries_per_worker": entries, "topology": args.topology,
-        "codec": args.codec, "budget_bits": args.bits if dynamiq else 8.25, "sg_by_width_2_4_8_16": by_width[0] if by_width else None,
+        "codec": args.codec, "budget_bits": args.bits if dynamiq else 8.25, "g4": args.g4, "g8": args.g8, "sg_by_width_2_4_8_16": by_width[0] if by_width else None,
         "vNMSE": err, "gradient_GB_resident": round(n * entries * 2 / 1e9, 2),
         "scratch_GB": round(rp.scratch.numel() / 1e9, 2), "replay_steps": rp.n_steps,
         "seconds": {"generate_stats": round(t1 - t0, 2), "build_schedule": round(t2 - t1, 2),
