@@ -135,3 +135,25 @@ def test_fused_reorder_and_restore_equal_the_separate_passes(dev):
         b, _ = A.simulated_allreduce(grads, 6.0, seed=1, fused_restore=False, **kw)       # both passes separate
         c, _ = A.simulated_allreduce(grads, 6.0, seed=1, fused_reorder=False, **kw)       # reorder pass, fused restore
         assert torch.equal(a, b) and torch.equal(a, c)
+
+
+def test_command_line_studies_run(dev):
+    """The large-scale run and the parametric study at toy sizes: they finish and report sane errors."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def run(*args):
+        out = subprocess.run([sys.executable, "-m"] + list(args), cwd=root, capture_output=True, text=True, timeout=300)
+        assert out.returncode == 0, out.stderr[-2000:]
+        return json.loads(out.stdout[out.stdout.index("{"):])
+
+    d = run("paper_2602_08923_amd.large_scale", "--workers", "16", "--sg", "256", "--bits", "8.5", "--topology", "butterfly")
+    assert d["workers"] == 16 and 0 < d["vNMSE"] < 1e-3 and sum(d["sg_by_width_2_4_8_16"]) == 256
+    d = run("paper_2602_08923_amd.large_scale", "--workers", "8", "--sg", "256", "--codec", "mxfp8", "--topology", "ring")
+    assert 0 < d["vNMSE"] < 0.1
+    d = run("paper_2602_08923_amd.ablation", "--workers", "4", "--sg", "512")
+    rows = list(d["vNMSE"].values())[0]
+    assert rows["+ correlated rounding"] < rows["+ variable bitwidth allocation"] < rows["+ non-uniform levels"]
