@@ -569,3 +569,112 @@ def test_groups_of_a_worker_are_spread_over_the_intervals():
         ups = code.reshape(16, 16)[:, 1]  # entry 1 of every group (entry 0 is the group maximum)
         want = [1 if (slot + g) % 16 < 8 else 0 for g in range(16)]
         assert list(ups) == want and sum(want) == 8
+
+
+# ----------------------------------------------------------------- the fused hop (Section 3.4 "Fused kernels"; Section 4, kernel 3)
+
+def _hop_case(dtype, n_sg, seed):
+    """A chunk, an incoming message from worker 1, a local slice of `dtype` and per-SG means."""
+    rng = np.random.default_rng(seed)
+    total = sum(n_sg)
+    ch = O.make_chunk(2 ** 32 + 7, n_sg)
+    first = (rng.standard_normal(total * 256) * np.repeat(10.0 ** rng.uniform(-4, -1, total * 16), 16)).astype(np.float32)
+    local = (rng.standard_normal(total * 256) * np.repeat(10.0 ** rng.uniform(-4, -1, total * 16), 16)).astype(np.float32)
+    local[40:56] = 0.0  # a silent group: the decoded value alone survives
+    if dtype == np.uint16:
+        local = (local.view(np.uint32) >> 16).astype(np.uint16)
+    mu = (rng.standard_normal(total) * 1e-4).astype(np.float32)
+    return ch, first, local, mu
+
+
+def _widen(a):
+    return a if a.dtype == np.float32 else (a.astype(np.uint32) << 16).view(np.float32)
+
+
+HOP_SHAPES = [[3, 0, 0], [0, 3, 0], [0, 0, 3], [2, 3, 1], [1, 2, 1, 2]]
+
+
+@pytest.mark.parametrize("n_sg", HOP_SHAPES)
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+@pytest.mark.parametrize("with_mu", [False, True])
+def test_dar_hop_is_decompress_accumulate_then_compress(n_sg, dtype, with_mu):
+    """The fused kernel is by definition decompress -> accumulate -> recompress with nothing
+    materialised in between: its bytes equal compress(rank, decompress(packed, local, mu)).
+    The fp32 array in the middle holds exactly the values the hop keeps in registers."""
+    n = 8
+    orc = O.Oracle(n, seed=31, round=5)
+    ch, first, local, mu = _hop_case(dtype, n_sg, 40 + len(n_sg) + sum(n_sg))
+    m = mu if with_mu else None
+    packed = orc.compress(ch, 1, first)
+    for rank in (2, 7):
+        mid = orc.decompress(ch, packed, local, m)
+        want = orc.compress(ch, rank, mid)           # no means: mid is a sum, its means are already off
+        got = orc.dar_hop(ch, rank, packed, local, m)
+        assert np.array_equal(got, want)
+        packed = got                                  # the next hop re-encodes what this one sent
+
+
+@pytest.mark.parametrize("n_sg", HOP_SHAPES[:4])
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+@pytest.mark.parametrize("with_mu", [False, True])
+def test_dar_hop_composed_by_hand_from_the_core_functions(n_sg, dtype, with_mu):
+    """The same bytes from the pieces: unpack the documented layout, decode_sg_core with the
+    mean-subtracted local super-group, the random numbers of THIS worker and of the
+    super-group's global index (draw_sg(first_sg + j, rank)), encode_sg_core, pack.  Drawing
+    with the sender's rank, with a chunk-relative index or skipping the mean gives other bytes."""
+    n = 8
+    sender, rank = 1, 5
+    orc = O.Oracle(n, seed=77, round=2)
+    ch, first, local, mu = _hop_case(dtype, n_sg, 60 + sum(n_sg))
+    packed = orc.compress(ch, sender, first)
+    got = orc.dar_hop(ch, rank, packed, local, mu if with_mu else None)
+    total = sum(n_sg)
+    code_off = np.cumsum([0] + [n_sg[w] * 32 * O.BITS[w] for w in range(3)])
+    gs_off = int(code_off[3])
+    sf_off = gs_off + 16 * total
+
+    def compose(draw_rank, index_base, use_mu):
+        out = np.zeros(got.size, np.uint8)
+        wide = _widen(local)
+        j = 0
+        for wi in range(3):
+            b = O.BITS[wi]
+            for pos in range(n_sg[wi]):
+                blk = packed[code_off[wi] + pos * 32 * b: code_off[wi] + (pos + 1) * 32 * b]
+                bits = np.unpackbits(blk, bitorder="little").reshape(256, b)
+                code_in = (bits * (1 << np.arange(b))).sum(axis=1).astype(np.uint8)
+                rG_in = packed[gs_off + 16 * j: gs_off + 16 * (j + 1)]
+                sf_in = int(packed[sf_off + 2 * j]) | (int(packed[sf_off + 2 * j + 1]) << 8)
+                loc = wide[j * 256:(j + 1) * 256]
+                if use_mu:
+                    loc = loc - mu[j]                                   # one fp32 subtraction per entry
+                v = orc.decode_sg_core(wi, code_in, rG_in, sf_in, loc)  # decode + accumulate
+                gamma, sb, slot = orc.draw_sg(index_base + j, draw_rank)
+                code, rG, sf = orc.encode_sg_core(wi, v, gamma, sb, slot)
+                cb = np.unpackbits(code.reshape(256, 1), axis=1, bitorder="little")[:, :b]
+                out[code_off[wi] + pos * 32 * b: code_off[wi] + (pos + 1) * 32 * b] = np.packbits(cb.ravel(), bitorder="little")
+                out[gs_off + 16 * j: gs_off + 16 * (j + 1)] = rG
+                out[sf_off + 2 * j], out[sf_off + 2 * j + 1] = sf & 0xFF, sf >> 8
+                j += 1
+        return out
+
+    assert np.array_equal(got, compose(rank, ch.first_sg, with_mu))
+    # negative controls: each plausible mistake changes the bytes
+    assert not np.array_equal(got, compose(sender, ch.first_sg, with_mu))     # the sender's rank
+    assert not np.array_equal(got, compose(rank, 0, with_mu))                 # chunk-relative index
+    assert not np.array_equal(got, compose(rank, ch.first_sg, not with_mu))   # mean skipped / applied
+
+
+def test_dar_hop_with_zero_message_is_compress_and_in_place():
+    """Decoding an all-zero message adds nothing: the hop then equals the leaf's compress of the
+    local slice with the hop's rank; and writing over the incoming buffer changes nothing."""
+    orc = O.Oracle(4, seed=3)
+    ch, _, local, mu = _hop_case(np.uint16, [1, 2, 1, 1], 9)
+    zero = orc.compress(ch, 0, np.zeros(5 * 256, np.float32))
+    assert not zero.any()
+    assert np.array_equal(orc.dar_hop(ch, 3, zero, local, mu), orc.compress(ch, 3, local, mu))
+    packed = orc.compress(ch, 1, _widen(local)[::-1].copy())
+    want = orc.dar_hop(ch, 2, packed, local, mu)
+    buf = packed.copy()
+    O.lib().dqo_dar_hop(orc.h, O.C.byref(ch), 2, O._p(buf), O._p(local), O.BF16, O._p(mu), O._p(buf))
+    assert np.array_equal(buf, want)
