@@ -52,7 +52,6 @@ typedef struct {
   float T[3][128]; /* levels, T[wi][0..R] */
   float D[3][128]; /* gaps   D[wi][r] = T[r+1]-T[r], r < R */
   float inv_n, s_n;
-  uint32_t stride; /* multiplier of the worker index in the permutation, see dqo_perm_stride */
 } dqo_ctx;
 
 static const int DQO_BITS[3] = {2, 4, 8};
@@ -86,8 +85,6 @@ int dqo_levels(int wi, double g, float *T, float *D) {
   return 0;
 }
 
-uint32_t dqo_perm_stride(uint32_t n);
-
 dqo_ctx *dqo_create(const dqo_config *cfg) {
   if (cfg->n_workers < 1 || cfg->n_workers > 8192) return NULL;
   dqo_ctx *c = (dqo_ctx *)calloc(1, sizeof(dqo_ctx));
@@ -101,7 +98,6 @@ dqo_ctx *dqo_create(const dqo_config *cfg) {
   /* independent rounding is the case n = 1 of the same formula: one interval, u = (byte + 1/2)/256 */
   c->inv_n = cfg->independent ? 1.0f : 1.0f / (float)cfg->n_workers;
   c->s_n = c->inv_n * (1.0f / 256.0f);
-  c->stride = dqo_perm_stride(cfg->n_workers);
   return c;
 }
 void dqo_destroy(dqo_ctx *c) { free(c); }
@@ -149,26 +145,44 @@ static uint8_t word_byte(const uint32_t w[4], int k) { return (uint8_t)(w[k >> 2
  *   scale_byte[16] one byte per group: stream SCALE, counter = sg, private to the worker
  *               (the scale rounding must be independent of the entry rounding, Section 3.3).
  *   slot        pi_rank for the super-group's first group: stream PERM, counter = sg,
- *               NOT keyed by the worker, so all workers derive the same permutation
- *               without communicating.  The permutation is affine,
- *               pi_i = (m*i + c + g) mod n for group g of the super-group, with
- *               c = floor(word0 * n / 2^32) drawn and m = dqo_perm_stride(n) fixed:
- *               every group sees a permutation, one worker per interval, a worker's
- *               16 groups are spread over the intervals, and workers with consecutive
- *               indices -- the consecutive hops of a ring -- get intervals about
- *               n/phi apart, so that the rounding direction of an entry does not
- *               persist from hop to hop (with m = 1 consecutive hops would round the
- *               same way for long runs and the errors of a long ring would add up
- *               coherently). */
+ *               NOT keyed by the worker, so all workers derive the same random permutation
+ *               of 0..n-1 without communicating (dqo_perm_slot below); group g of the
+ *               super-group uses (slot + g) mod n, so that a worker's 16 groups are spread
+ *               over the n intervals. */
 
-/* The stride m: the first integer at or above floor(n / phi) that is coprime to n
- * (phi the golden ratio; floor(n/phi) = floor(n * 0x9E3779B9 / 2^32)), at least 1. */
-static uint32_t pp_gcd(uint32_t a, uint32_t b) { while (b) { uint32_t t = a % b; a = b; b = t; } return a; }
-uint32_t dqo_perm_stride(uint32_t n) {
-  uint32_t m = (uint32_t)(((uint64_t)n * 0x9E3779B9ull) >> 32);
-  if (m < 1) m = 1;
-  while (pp_gcd(m, n) != 1) ++m;
-  return m;
+/* The shared random permutation pi of 0..n-1 (Section 3.3), evaluated at one worker index
+ * without building the permutation.  With k = ceil(log2 n) and the four words w0..w3 of the
+ * PERM draw, three rounds of
+ *     y <- reverse_k( ((w_t | 1) * y + (w_t >> 16)) mod 2^k )          t = 0, 1, 2
+ * map the k-bit integers one-to-one onto themselves: multiplying by an odd number and adding
+ * a constant are bijections mod 2^k (they carry information from low bits to high bits), and
+ * reversing the order of the k bits is a bijection that swaps the two directions.  For n
+ * below 2^k the walk is repeated until it lands below n ("cycle walking": following a
+ * permutation of 0..2^k-1 from a point below n until it returns below n is a permutation of
+ * 0..n-1).  A final rotation by floor(w3 * n / 2^32) makes every worker's slot uniform on
+ * 0..n-1 whatever the rounds do.  The multipliers use bits 0..12 of a word and the added
+ * constants bits 16..28 (n <= 8192, so k <= 13): independent bits. */
+static uint32_t reverse_bits(uint32_t y, uint32_t k) {
+  uint32_t r = 0;
+  for (uint32_t i = 0; i < k; ++i) r |= ((y >> i) & 1u) << (k - 1 - i);
+  return r;
+}
+uint32_t dqo_perm_bits(uint32_t n) {
+  uint32_t k = 0;
+  while ((1u << k) < n) ++k;
+  return k;
+}
+static uint32_t perm_rounds(const uint32_t w[4], uint32_t k, uint32_t y) {
+  const uint32_t mask = (1u << k) - 1u;
+  for (int t = 0; t < 3; ++t) y = reverse_bits(((w[t] | 1u) * y + (w[t] >> 16)) & mask, k);
+  return y;
+}
+uint32_t dqo_perm_slot(const uint32_t w[4], uint32_t n, uint32_t rank) {
+  const uint32_t k = dqo_perm_bits(n);
+  uint32_t y = perm_rounds(w, k, rank);
+  while (y >= n) y = perm_rounds(w, k, y);
+  const uint32_t rot = (uint32_t)(((uint64_t)w[3] * n) >> 32);
+  return (y + rot) % n;
 }
 
 void dqo_draw_sg(const dqo_ctx *c, uint64_t sg, uint32_t rank, uint8_t gamma[DQO_SG],
@@ -181,9 +195,7 @@ void dqo_draw_sg(const dqo_ctx *c, uint64_t sg, uint32_t rank, uint8_t gamma[DQO
   dqo_draw(c, sg, DQO_STREAM_SCALE, rank, w);
   for (int g = 0; g < DQO_GROUPS_PER_SG; ++g) scale_byte[g] = word_byte(w, g);
   dqo_draw(c, sg, DQO_STREAM_PERM, 0xFFFFu, w);
-  uint32_t n = c->cfg.n_workers;
-  uint32_t shift = (uint32_t)(((uint64_t)w[0] * n) >> 32);
-  *slot = c->cfg.independent ? 0u : (uint32_t)(((uint64_t)c->stride * rank + shift) % n);
+  *slot = c->cfg.independent ? 0u : dqo_perm_slot(w, c->cfg.n_workers, rank);
 }
 
 /* ---------------------------------------------------------------- quantizer pieces */

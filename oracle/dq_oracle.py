@@ -59,8 +59,10 @@ def lib():
         L.dqo_levels.restype = C.c_int
         L.dqo_levels.argtypes = [C.c_int, C.c_double, C.c_void_p, C.c_void_p]
         L.dqo_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
-        L.dqo_perm_stride.restype = C.c_uint32
-        L.dqo_perm_stride.argtypes = [C.c_uint32]
+        L.dqo_perm_slot.restype = C.c_uint32
+        L.dqo_perm_slot.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32]
+        L.dqo_perm_bits.restype = C.c_uint32
+        L.dqo_perm_bits.argtypes = [C.c_uint32]
         L.dqo_draw_sg.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.dqo_entry_uniform.restype = C.c_float
         L.dqo_entry_uniform.argtypes = [C.c_void_p, C.c_uint32, C.c_uint8]
@@ -211,8 +213,14 @@ class Oracle:
         return out
 
 
-def perm_stride(n):
-    return int(lib().dqo_perm_stride(int(n)))
+def perm_slot(words, n, rank):
+    """pi_rank of the shared permutation of 0..n-1 that the four PERM words define."""
+    w = np.asarray(words, np.uint32)
+    return int(lib().dqo_perm_slot(_p(w), int(n), int(rank)))
+
+
+def perm_bits(n):
+    return int(lib().dqo_perm_bits(int(n)))
 
 
 def sq_index(T, D, x, u):

@@ -79,17 +79,25 @@ def draws(seed, rnd, n, sg, rank):
     w = call(sg, 1, rank)
     sbytes = [(w[g >> 2] >> (8 * (g & 3))) & 0xFF for g in range(16)]
     w = call(sg, 2, 0xFFFF)
-    slot = (perm_stride(n) * rank + ((w[0] * n) >> 32)) % n
-    return gamma, sbytes, slot
+    return gamma, sbytes, perm_slot(w, n, rank)
 
 
-def perm_stride(n):
-    """First integer >= floor(n / golden ratio) coprime to n (at least 1)."""
-    from math import gcd
-    m = max(1, (n * 0x9E3779B9) >> 32)
-    while gcd(m, n) != 1:
-        m += 1
-    return m
+def perm_slot(w, n, rank):
+    """The shared permutation of 0..n-1 at `rank`: three rounds of (odd multiply + add, then the
+    k bits in reverse order) on k = ceil(log2 n) bits, repeated until the value is below n,
+    then rotated by floor(w3 n / 2^32)."""
+    k = (n - 1).bit_length()
+
+    def rounds(y):
+        for t in range(3):
+            y = ((w[t] | 1) * y + (w[t] >> 16)) % (1 << k)
+            y = int(format(y, "b").zfill(k)[::-1], 2) if k else 0
+        return y
+
+    y = rounds(rank)
+    while y >= n:
+        y = rounds(y)
+    return (y + ((w[3] * n) >> 32)) % n
 
 
 def encode_sg(b, g, n, seed, rnd, sg, rank, v):

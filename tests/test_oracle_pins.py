@@ -150,30 +150,61 @@ def test_sq_unbiased_by_enumeration(wi, n):
 
 # ----------------------------------------------------------------- correlated rounding (Sections 2.4, 3.3)
 
-@pytest.mark.parametrize("n", [2, 3, 4, 7, 8, 64, 100, 8192])
+@pytest.mark.parametrize("n", [2, 3, 4, 7, 8, 64, 100, 1000, 8192])
 def test_exactly_one_uniform_per_interval(n):
     """For every super-group the slots of the n workers are a permutation of 0..n-1 and
-    u_i lies in [pi_i/n, (pi_i+1)/n): exactly one worker per interval."""
+    u_i lies in [pi_i/n, (pi_i+1)/n): exactly one worker per interval (Section 3.3)."""
     orc = O.Oracle(n, seed=1234, round=3)
-    ranks = range(n) if n <= 100 else list(range(0, n, 517)) + [n - 1]
-    for sg in (0, 1, 77, 2 ** 33 + 5):
-        slots = [orc.draw_sg(sg, r)[2] for r in ranks]
-        m = O.perm_stride(n)
-        assert math.gcd(m, n) == 1 and (n < 3 or abs(m / n - 0.6180339887) < 2.0 / n + 0.1)
-        if n <= 100:
-            assert sorted(slots) == list(range(n))
-        # affine in the worker index: slot = (m * rank + shift) mod n with one shift for all
-        shift = (slots[0] - m * ranks[0]) % n
-        assert all((s - m * r) % n == shift for s, r in zip(slots, ranks))
+    for sg in (0, 1, 77, 2 ** 33 + 5) if n <= 100 else (5,):
+        slots = [orc.draw_sg(sg, r)[2] for r in range(n)]
+        assert sorted(slots) == list(range(n))
         for s in slots[:8]:
             for byte in (0, 1, 127, 255):
                 u = float(orc.entry_uniform(s, byte))
                 assert 0.0 < u < 1.0 and math.floor(u * n) == s
-    # the shift is drawn, not fixed: it varies with the super-group and the round
-    shifts = {orc.draw_sg(sg, 0)[2] for sg in range(64)}
-    assert len(shifts) > 1 or n == 1
+    # the permutation is drawn, not fixed: it varies with the super-group and the round
+    perms = {tuple(orc.draw_sg(sg, r)[2] for r in range(min(n, 8))) for sg in range(64)}
+    assert len(perms) > 1
     other = O.Oracle(n, seed=1234, round=4)
-    assert [orc.draw_sg(sg, 0)[2] for sg in range(64)] != [other.draw_sg(sg, 0)[2] for sg in range(64)] or n <= 2
+    assert [orc.draw_sg(sg, 0)[2] for sg in range(64)] != [other.draw_sg(sg, 0)[2] for sg in range(64)]
+    # and shared: it does not depend on which worker asks (same words for every rank)
+    assert orc.draw_sg(9, 0)[2] != orc.draw_sg(9, 1)[2]
+
+
+def _perm_words(count, seed):
+    return np.random.default_rng(seed).integers(0, 1 << 32, (count, 4), dtype=np.uint64).astype(np.uint32)
+
+
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 8, 12, 16])
+def test_permutation_is_a_bijection_for_any_words(n):
+    """Whatever the four words are (also all-zero, all-one and single-bit words), the n workers
+    get the n slots once each."""
+    words = list(_perm_words(200, n)) + [np.zeros(4, np.uint32), np.full(4, 0xFFFFFFFF, np.uint32)]
+    words += [np.array([1 << i, 1 << (31 - i), 1 << ((i + 16) % 32), 0], np.uint32) for i in range(32)]
+    for w in words:
+        assert sorted(O.perm_slot(w, n, r) for r in range(n)) == list(range(n))
+    if n <= 4:  # every permutation of a small n is reachable
+        assert len({tuple(O.perm_slot(w, n, r) for r in range(n)) for w in _perm_words(3000, 1)}) == math.factorial(n)
+
+
+@pytest.mark.parametrize("n", [3, 8, 64, 100])
+def test_permutation_marginals_and_pairs_look_uniform(n):
+    """What a uniformly random permutation guarantees and an affine or fixed-stride map does not:
+    every worker's slot is uniform on 0..n-1, the difference of two workers' slots is spread over
+    all non-zero residues, and consecutive differences are not tied to each other."""
+    N = 20000
+    W = _perm_words(N, 100 + n)
+    p = np.array([[O.perm_slot(w, n, r) for r in range(3)] for w in W])
+    marg = np.bincount(p[:, 1], minlength=n)
+    chi_m = ((marg - N / n) ** 2 / (N / n)).sum() / (n - 1)
+    assert chi_m < 1.0 + 5.0 * math.sqrt(2.0 / (n - 1))          # chi-square per degree of freedom: 1 +- sqrt(2/dof)
+    d = np.bincount((p[:, 1] - p[:, 0]) % n, minlength=n)
+    assert d[0] == 0
+    rel = d[1:] / (N / (n - 1))
+    assert rel.min() > 0.7 and rel.max() < 1.3                    # a stride or a small multiplier would leave most residues empty
+    if n > 3:
+        same = np.mean((p[:, 2] - p[:, 1]) % n == (p[:, 1] - p[:, 0]) % n)
+        assert abs(same - 1.0 / (n - 2)) < 0.35 / (n - 2) + 4.0 / math.sqrt(N)   # an affine map gives 1
 
 
 def test_streams_are_private_or_shared_as_specified():

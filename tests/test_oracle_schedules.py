@@ -215,22 +215,11 @@ def test_ring_with_sixteen_bit_run_is_exact_on_bf16_friendly_values():
 
 # ----------------------------------------------------------------- the permutation and long rings
 
-def test_consecutive_hops_get_distant_rounding_intervals():
-    """pi_i = (m i + c + g) mod n with m about n/phi: neighbours on a ring never share or
-    neighbour an interval (for n >= 8), so an entry's rounding direction does not persist."""
-    for n in (8, 16, 64, 100, 1024, 8192):
-        m = O.perm_stride(n)
-        d = min(m % n, n - m % n)
-        assert d >= n // 3, (n, m)
-        orc = O.Oracle(n, seed=3)
-        s0, s1 = orc.draw_sg(5, 0)[2], orc.draw_sg(5, 1)[2]
-        assert (s1 - s0) % n == m % n
-
-
 def test_ring_error_grows_about_linearly_with_the_hops():
     """8-bit super-groups on rings of 16 and 64 workers: four times the hops, about four times
     the error.  (With neighbouring workers in neighbouring intervals -- a cyclic shift as the
-    permutation -- the same pair of rings gives a ratio near 15 and 5 times the error at 64.)"""
+    permutation -- the same pair of rings gives a ratio near 15 and 5 times the error at 64;
+    tests/test_oracle_rounding_bias.py compares the law with an ideal shuffle.)"""
     def run(n):
         rng = np.random.default_rng(7)
         J = n
