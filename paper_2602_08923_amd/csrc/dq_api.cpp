@@ -223,15 +223,7 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
   P.round = cfg->round;
   P.n_workers = cfg->n_workers;
   P.n_mask = (cfg->n_workers & (cfg->n_workers - 1)) == 0 ? cfg->n_workers - 1 : 0xFFFFFFFFu;
-  // pi_i = (stride * i + shift + g) mod n: the stride is the first integer from floor(n/phi) up that is
-  // coprime to n, so consecutive workers (consecutive ring hops) get rounding intervals far apart
-  {
-    uint32_t m = (uint32_t)(((uint64_t)cfg->n_workers * 0x9E3779B9ull) >> 32);
-    if (m < 1) m = 1;
-    auto gcd = [](uint32_t a, uint32_t b) { while (b) { const uint32_t t = a % b; a = b; b = t; } return a; };
-    while (gcd(m, cfg->n_workers) != 1) ++m;
-    P.stride = m;
-  }
+  while ((1u << P.perm_bits) < cfg->n_workers) ++P.perm_bits;  // the shared permutation mixes integers of this many bits
   P.inv_n = 1.0f / (float)cfg->n_workers;
   if (cfg->independent_rounding) {  // the case n = 1 of the same arithmetic: one interval, slot 0
     P.inv_n = 1.0f;

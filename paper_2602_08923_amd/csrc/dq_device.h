@@ -65,7 +65,7 @@ struct Params {
   uint32_t key0, key1, round;
   uint32_t n_workers;
   uint32_t n_mask;       // n-1 if n is a power of two, else 0xFFFFFFFF (meaning: use %)
-  uint32_t stride;       // multiplier of the worker index in the rounding permutation (coprime to n, about n/phi)
+  uint32_t perm_bits;    // ceil(log2 n): width of the integers the rounding permutation mixes
   float inv_n, s_n;
 };
 

@@ -352,13 +352,12 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const uint64_t gi = (tb.G0 + rowc) * 16 + g;  // global group index
   // stream 0: one byte per entry, private to the worker
   const U4 gam = philox4x32_10((uint32_t)gi, (uint32_t)(gi >> 32), P.round, job.rank & 0xFFFFu, P.key0, P.key1);
-  // parked per-SG draws: word 0 of the shared stream -> the offset c of the permutation
-  // pi = (stride * rank + c + g) mod n; byte g of the private stream -> this group's scale dither
-  const uint32_t perm_w0 = lds_ld1(stage + rowc * 32);
+  // parked per-SG draws: this worker's slot pi_rank of the shared permutation (group g of the
+  // super-group uses pi_rank + g mod n); byte g of the private stream -> this group's scale dither
+  const uint32_t slot0 = lds_ld1(stage + rowc * 32);
   const uint32_t sc_word = lds_ld1(stage + rowc * 32 + 16 + (g >> 2) * 4);
   const uint32_t scale_byte = (sc_word >> (8 * (g & 3u))) & 0xFFu;
-  const uint32_t shift = __umulhi(perm_w0, P.n_workers);
-  uint32_t slot = job.rank * P.stride + shift + g;  // below 2^27: rank, stride, shift < n <= 8192
+  uint32_t slot = slot0 + g;  // below n + 16
   slot = (P.n_mask != 0xFFFFFFFFu) ? (slot & P.n_mask) : (slot % P.n_workers);
   const float o_pi = ((float)slot + (1.0f / 512.0f)) * P.inv_n;
 
@@ -622,9 +621,30 @@ __device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint3
 // The job's tiles are split evenly over all waves of the grid row (4 * gridDim.x waves):
 // wave w takes [w*T/W, (w+1)*T/W).  The launcher sizes the grid to what the GPU holds at
 // once, so a wave lives for the whole launch and the table copy is paid once.
+// The shared random permutation pi of 0..n-1 (Section 3.3 "Correlated rounding") at one worker
+// index, from the four words of the super-group's shared draw: three rounds of
+//   y <- reverse_k(((w_t | 1) * y + (w_t >> 16)) mod 2^k),  k = ceil(log2 n)
+// (odd multiply, add and bit reversal are bijections of the k-bit integers), walked again while
+// the value is not below n, then rotated by floor(w3 * n / 2^32) so that every worker's slot is
+// uniform.  Evaluated once per super-group and job (the rank is the job's), never per entry.
+__device__ __forceinline__ uint32_t perm_slot(const U4 &d, const Params &P, uint32_t rank) {
+  const uint32_t k = P.perm_bits, mask = (1u << k) - 1u, back = (32u - k) & 31u;
+  const uint32_t w[3] = {d.x, d.y, d.z};
+  auto rounds = [&](uint32_t y) {
+#pragma unroll
+    for (int t = 0; t < 3; ++t) y = __brev(((w[t] | 1u) * y + (w[t] >> 16)) & mask) >> back;
+    return y;
+  };
+  uint32_t y = rounds(rank);
+  if (P.n_mask == 0xFFFFFFFFu)  // n is not a power of two: some k-bit values lie outside 0..n-1
+    while (y >= P.n_workers) y = rounds(y);  // ends: the walk is a cycle through `rank` < n
+  const uint32_t s = y + __umulhi(d.w, P.n_workers);
+  return s >= P.n_workers ? s - P.n_workers : s;
+}
+
 // Per-SG draws of `nb` <= 8 consecutive tiles starting at tile `t_first`, made by one wave-wide
-// Philox call and parked at `area` (128 bytes per tile: row r at [32r] the shared permutation
-// stream, at [32r+16] the worker's group-scale stream).  Lane l draws for tile l/8, row (l%8)/2.
+// Philox call and parked at `area` (128 bytes per tile: row r at [32r] this worker's slot of the
+// shared permutation, at [32r+16] the worker's group-scale stream).  Lane l draws for tile l/8, row (l%8)/2.
 __device__ __forceinline__ void park_draws(const Job &job, const Params &P, uint32_t t_first, uint32_t nb,
                                            uint32_t area) {
   const uint32_t lane = threadIdx.x & 63u;
@@ -634,7 +654,9 @@ __device__ __forceinline__ void park_draws(const Job &job, const Params &P, uint
   const uint64_t G = job.first_sg + p.seg_first + sgw;
   const uint32_t c3 = (lane & 1u) ? ((1u << 16) | (job.rank & 0xFFFFu)) : ((2u << 16) | 0xFFFFu);
   const U4 d = philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), P.round, c3, P.key0, P.key1);
-  lds_st4(area + lane * 16, u32x4{d.x, d.y, d.z, d.w});
+  // even lanes hold the shared draw: they park the slot it gives this job's worker in word 0
+  const uint32_t w0 = (lane & 1u) ? d.x : perm_slot(d, P, job.rank);
+  lds_st4(area + lane * 16, u32x4{w0, d.y, d.z, d.w});
 }
 
 // Tiles [t_first, t_first + nb) of the job, whose draws are parked from `area` on.

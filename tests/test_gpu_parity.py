@@ -57,7 +57,7 @@ CASES = [
     (64, [13, 0, 0], 7, 63),
     (1, [0, 1, 1], 0, 0),
     (100, [2, 66, 5], 999, 42),
-    (6, [3, 3, 3], 5, 5),            # floor(6/phi) = 3 shares a factor with 6: the stride search moves on to 5
+    (6, [3, 3, 3], 5, 5),            # not a power of two: the permutation walks 3-bit integers until one is below 6
     (8192, [2, 4, 1], 2 ** 40, 8191),  # the largest worker count
 ]
 

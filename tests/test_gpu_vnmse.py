@@ -55,11 +55,15 @@ def test_reduce_scatter_only_is_more_accurate_than_with_all_gather(dev):
 
 
 def test_rounds_draw_fresh_randomness_and_average_out(dev):
-    """Unbiasedness at scale: the mean of the estimates of R rounds is far closer to the truth than
-    one round.  Not quite 1/R: every hop's rounding is unbiased on its own, but the intervals of
-    consecutive hops are tied by the shared permutation, which leaves a bias of a few percent of
-    one round's error energy."""
-    J, n, R = 1024, 8, 16
+    """Unbiasedness at scale: the mean of the estimates of R rounds approaches the truth as
+    err(R) = err(1) * (1/R + beta).  beta is the multi-hop bias every shared permutation leaves
+    (worker i cannot get the interval worker i-1 has, and its input depends on how i-1 rounded):
+    tests/test_oracle_rounding_bias.py measures beta < 0.03 on the CPU for rings of 8 and 64
+    workers, for the oracle's law and for an ideal shuffle alike.  The statistical slack: the
+    estimate of err(R) over J*256 entries whose errors are correlated inside a group scatters by
+    a few percent."""
+    J, n, R = 1024, 8, 32
+    beta_bound = 0.03
     M = workloads.mixture_magnitudes(J, seed=6, device=dev)
     grads = [workloads.draw_mixture(M, w, seed=6) for w in range(n)]
     truth = A.true_sum(grads)
@@ -71,8 +75,9 @@ def test_rounds_draw_fresh_randomness_and_average_out(dev):
         acc += est.double()
     avg = A.vnmse(acc / R, truth)
     mean_single = sum(single) / R
-    assert avg < 0.2 * mean_single, (avg, mean_single)
-    assert avg - mean_single / R < 0.1 * mean_single            # the bias part
+    print(f"\nerr(1) = {mean_single:.4e}  err({R}) = {avg:.4e}  err(R)/err(1) = {avg / mean_single:.4f}  1/R = {1 / R:.4f}")
+    assert avg < mean_single * (1.0 / R + beta_bound) * 1.1, (avg, mean_single)
+    assert avg > mean_single / R * 0.8                        # and not better than independent rounds allow
     assert len({round(s, 12) for s in single}) == R           # every round differs
 
 
