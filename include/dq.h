@@ -270,13 +270,27 @@ dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_main
  * network -- while block i+1 is being encoded.  wire_in NULL: the first hop (compress).  `local`
  * describes the whole chunk (means and indices per super-group of the whole chunk).  The two
  * streams must differ; when the call returns, compute_stream has been made to wait for the last
- * copies, so synchronising it is enough.  Events are created inside the context at the first call;
- * one pipelined call at a time per context. */
+ * copies, so synchronising it is enough.  The events that order the two streams belong to the
+ * context (made in dq_create): one pipelined call at a time per context. */
 size_t dq_pipelined_wire_bytes(const dq_chunk *chunk, uint32_t block_sg);
 size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg);
 dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
                                uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
                                void *copy_stream);
+
+/* The same hop for callers that cannot allocate device memory and have no staging buffer to hand over
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the two-block
+ * stage is a static device array inside the library, DQ_STATIC_STAGE_BYTES per GPU, held until the
+ * process ends; its address on the context's GPU is looked up in dq_create.  The call allocates
+ * nothing and creates nothing (the pipeline's events are made in dq_create); results are those of
+ * dq_dar_hop_pipelined byte for byte.  DQ_EUNSUPPORTED (text in dq_last_hip_error) if
+ * dq_pipelined_stage_bytes(chunk, block_sg) exceeds DQ_STATIC_STAGE_BYTES; DQ_EINVAL if the context's
+ * device is not the current one.  Every call on a GPU shares that GPU's one array: calls that overlap
+ * in time on one GPU (other streams, other contexts, other threads) race on it. */
+#define DQ_STATIC_STAGE_BYTES (8u << 20)
+dq_status dq_dar_hop_pipelined_static(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
+                                      uint32_t rank, uint32_t block_sg, void *wire_out, void *compute_stream,
+                                      void *copy_stream);
 
 const char *dq_status_str(dq_status s);
 /* Last HIP error string seen by this library on the calling thread (for DQ_EHIP). */

@@ -25,8 +25,9 @@ EXPORTS = [
     "dq_replay_step_info",
     "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
     "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_reorder", "dq_reorder_mean", "dq_restore",
-    "dq_pipelined_wire_bytes", "dq_pipelined_stage_bytes", "dq_dar_hop_pipelined",
+    "dq_pipelined_wire_bytes", "dq_pipelined_stage_bytes", "dq_dar_hop_pipelined", "dq_dar_hop_pipelined_static",
 ]
+DQ_STATIC_STAGE_BYTES = 8 << 20
 
 
 class DqError(RuntimeError):
@@ -105,15 +106,16 @@ def lib():
         L.dq_pipelined_stage_bytes.argtypes = [C.POINTER(Chunk), u32]
         L.dq_pipelined_stage_bytes.restype = C.c_size_t
         L.dq_dar_hop_pipelined.argtypes = [vp, vp, C.POINTER(Local), C.POINTER(Chunk), u32, u32, vp, vp, vp, vp]
+        L.dq_dar_hop_pipelined_static.argtypes = [vp, vp, C.POINTER(Local), C.POINTER(Chunk), u32, u32, vp, vp, vp]
         _lib = L
     return _lib
 
 
-def _check(st):
+def _check(st, detail=False):
     if st != DQ_OK:
         L = lib()
         msg = L.dq_status_str(st).decode()
-        if st == DQ_EHIP:
+        if st == DQ_EHIP or detail:
             msg += ": " + L.dq_last_hip_error().decode()
         raise DqError(msg)
 
@@ -452,4 +454,16 @@ def dq_dar_hop_pipelined(ctx, wire_in, local, chunk, rank, block_sg, compute_str
                                       C.byref(chunk), rank, block_sg,
                                       _ptr(stage), _ptr(wire_out), C.c_void_p(compute_stream.cuda_stream),
                                       C.c_void_p(copy_stream.cuda_stream)))
+    return wire_out
+
+
+def dq_dar_hop_pipelined_static(ctx, wire_in, local, chunk, rank, block_sg, compute_stream, copy_stream, wire_out,
+                                mu=None, sg_index=None):
+    """dq_dar_hop_pipelined with the library's static staging array: allocates nothing, so the
+    caller passes wire_out (dq_pipelined_wire_bytes bytes, zero-filled once: the kernels never write
+    the padding between blocks)."""
+    _check(lib().dq_dar_hop_pipelined_static(ctx.h, _ptr(wire_in), _local(local, chunk, mu, sg_index),
+                                             C.byref(chunk), rank, block_sg, _ptr(wire_out),
+                                             C.c_void_p(compute_stream.cuda_stream),
+                                             C.c_void_p(copy_stream.cuda_stream)), detail=True)
     return wire_out

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -17,6 +18,31 @@ bool hip_ok(hipError_t e) {
   if (e == hipSuccess) return true;
   g_hip_error = hipGetErrorString(e);
   return false;
+}
+
+// Staging memory of dq_dar_hop_pipelined_static: two halves of a block pipeline.  Every GPU the
+// library runs on holds its own copy of this array until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress: the device address of the current GPU's copy
+// is resolved once per device (resolve_scratch, called from dq_create) and that pointer is what
+// kernels, copies and clears receive.
+static __device__ __align__(256) unsigned char scratch[DQ_STATIC_STAGE_BYTES];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];  // per device ordinal: address of that device's `scratch`, or null
+std::mutex g_scratch_mutex;
+
+// The address of `scratch` on `device`, which must be the current device.  nullptr for ordinals this
+// table does not cover; *err reports a failed lookup.
+void *resolve_scratch(int device, hipError_t *err) {
+  *err = hipSuccess;
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void *p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[device] = p;
+  }
+  return g_scratch_ptr[device];
 }
 
 uint32_t fbits(float f) {
@@ -85,6 +111,28 @@ void append_aligned(std::vector<uint32_t> &blob, const std::vector<uint32_t> &pa
   while (blob.size() % 4) blob.push_back(0);
   *off = (uint32_t)blob.size();
   blob.insert(blob.end(), part.begin(), part.end());
+}
+
+// The four events of the block pipeline (dq_dar_hop_pipelined*), made with the context so that
+// the pipelined calls create nothing.
+bool make_events(dq_ctx *ctx) {
+  for (int i = 0; i < 4; ++i) ctx->have_event[i] = false;
+  for (int i = 0; i < 2; ++i) {
+    if (!hip_ok(hipEventCreateWithFlags(&ctx->stage_filled[i], hipEventDisableTiming))) return false;
+    ctx->have_event[i] = true;
+    if (!hip_ok(hipEventCreateWithFlags(&ctx->stage_free[i], hipEventDisableTiming))) return false;
+    ctx->have_event[2 + i] = true;
+  }
+  ctx->have_events = true;
+  return true;
+}
+void drop_events(dq_ctx *ctx) {
+  for (int i = 0; i < 2; ++i) {
+    if (ctx->have_event[i]) (void)hipEventDestroy(ctx->stage_filled[i]);
+    if (ctx->have_event[2 + i]) (void)hipEventDestroy(ctx->stage_free[i]);
+    ctx->have_event[i] = ctx->have_event[2 + i] = false;
+  }
+  ctx->have_events = false;
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -203,11 +251,16 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
   ctx->cfg = *cfg;
   ctx->blob_dev = nullptr;
   ctx->have_events = false;
+  for (int i = 0; i < 4; ++i) ctx->have_event[i] = false;
+  ctx->static_stage = nullptr;
   hipDeviceProp_t prop;
+  hipError_t sym_err = hipSuccess;
   if (!hip_ok(hipGetDevice(&ctx->device)) || !hip_ok(hipGetDeviceProperties(&prop, ctx->device)) ||
       !hip_ok(hipMalloc(&ctx->blob_dev, blob.size() * 4)) ||
-      !hip_ok(hipMemcpy(ctx->blob_dev, blob.data(), blob.size() * 4, hipMemcpyHostToDevice))) {
+      !hip_ok(hipMemcpy(ctx->blob_dev, blob.data(), blob.size() * 4, hipMemcpyHostToDevice)) ||
+      ((ctx->static_stage = resolve_scratch(ctx->device, &sym_err)), !hip_ok(sym_err)) || !make_events(ctx)) {
     if (ctx->blob_dev) (void)hipFree(ctx->blob_dev);
+    drop_events(ctx);
     delete ctx;
     return DQ_EHIP;
   }
@@ -238,11 +291,7 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
 void dq_destroy(dq_ctx *ctx) {
   if (!ctx) return;
   if (ctx->blob_dev) (void)hipFree(ctx->blob_dev);
-  if (ctx->have_events)
-    for (int i = 0; i < 2; ++i) {
-      (void)hipEventDestroy(ctx->stage_filled[i]);
-      (void)hipEventDestroy(ctx->stage_free[i]);
-    }
+  drop_events(ctx);
   delete ctx;
 }
 
@@ -375,7 +424,41 @@ size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg) {
   return 2 * biggest;
 }
 
+static dq_status pipelined_hop(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
+                               uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
+                               void *copy_stream);
+
 dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
+                               uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
+                               void *copy_stream) {
+  return pipelined_hop(ctx, wire_in, local, chunk, rank, block_sg, stage, wire_out, compute_stream, copy_stream);
+}
+
+dq_status dq_dar_hop_pipelined_static(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
+                                      uint32_t rank, uint32_t block_sg, void *wire_out, void *compute_stream,
+                                      void *copy_stream) {
+  if (!ctx || !chunk || block_sg == 0) return DQ_EINVAL;
+  const size_t need = dq_pipelined_stage_bytes(chunk, block_sg);
+  if (need > (size_t)DQ_STATIC_STAGE_BYTES) {
+    g_hip_error = "dq_dar_hop_pipelined_static: two blocks of " + std::to_string(block_sg) + " super-groups need " +
+                  std::to_string(need) + " bytes of staging, the static scratch holds " +
+                  std::to_string((size_t)DQ_STATIC_STAGE_BYTES) + ": use smaller blocks or dq_dar_hop_pipelined";
+    return DQ_EUNSUPPORTED;
+  }
+  int device = -1;
+  if (!hip_ok(hipGetDevice(&device))) return DQ_EHIP;
+  if (device != ctx->device) {  // the scratch pointer kept in the context belongs to the context's GPU
+    g_hip_error = "dq_dar_hop_pipelined_static: the context was made on another device than the current one";
+    return DQ_EINVAL;
+  }
+  if (!ctx->static_stage || !ctx->have_events) {
+    g_hip_error = "dq_dar_hop_pipelined_static: no static scratch on this device ordinal";
+    return DQ_EUNSUPPORTED;
+  }
+  return pipelined_hop(ctx, wire_in, local, chunk, rank, block_sg, ctx->static_stage, wire_out, compute_stream, copy_stream);
+}
+
+static dq_status pipelined_hop(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
                                uint32_t rank, uint32_t block_sg, void *stage, void *wire_out, void *compute_stream,
                                void *copy_stream) {
   dq_status st = check_chunk(ctx, chunk, rank);
@@ -389,13 +472,7 @@ dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local 
   if ((st = take_local(local, &whole)) != DQ_OK) return st;
   const dq_dtype dtype = local->dtype;
   hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
-  if (!ctx->have_events) {
-    for (int i = 0; i < 2; ++i)
-      if (!hip_ok(hipEventCreateWithFlags(&ctx->stage_filled[i], hipEventDisableTiming)) ||
-          !hip_ok(hipEventCreateWithFlags(&ctx->stage_free[i], hipEventDisableTiming)))
-        return DQ_EHIP;
-    ctx->have_events = true;
-  }
+  if (!ctx->have_events) return DQ_EHIP;  // made in dq_create
   const size_t half = dq_pipelined_stage_bytes(chunk, block_sg) / 2;
   const size_t es = dtype == DQ_F32 ? 4 : 2;
   const uint64_t blocks = (n + block_sg - 1) / block_sg;

@@ -106,6 +106,8 @@ struct dq_ctx {
   uint32_t n_cu;
   uint32_t grid_blocks;  // n_cu x blocks per CU (6, or the DQ_BLOCKS_PER_CU environment variable at dq_create)
   int device;
-  hipEvent_t stage_filled[2], stage_free[2];  // block pipeline: created on first use, destroyed with the context
-  bool have_events;
+  hipEvent_t stage_filled[2], stage_free[2];  // block pipeline: created and destroyed with the context
+  bool have_event[4];                         // which of the four exist (filled 0, 1, free 0, 1)
+  bool have_events;                           // all four
+  void *static_stage;  // this device's copy of the library's static staging array (dq_dar_hop_pipelined_static), or null
 };
