@@ -179,9 +179,15 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
   std::vector<uint32_t> blob;
   dq::Params P;
   memset(&P, 0, sizeof(P));
-  // Blob layout: [common: reciprocals][2-bit: decode][4-bit: decode, sign spread, {T,D}, search]
-  // [8-bit: decode, {T,D}, search]; the fixed-size tables land on the constant offsets that
-  // dq_device.h declares.
+  // Blob layout: the fixed-size tables first, on the constant offsets that dq_device.h declares
+  // ([reciprocals][2-bit decode][4-bit decode][4-bit {T,D}][8-bit decode][8-bit {T,D}]), then the
+  // two search tables, whose size follows the level sets.
+  std::vector<uint32_t> lut[3];
+  auto range = [&](int r, uint32_t lo, uint32_t width) {
+    P.range_lo[r] = lo;
+    P.range_hi[r] = (uint32_t)blob.size();
+    P.range_width[r] = width;
+  };
   {
     std::vector<uint32_t> rec(256);
     for (int m = 0; m < 128; ++m) {
@@ -193,15 +199,14 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
     uint32_t off;
     append_aligned(blob, rec, &off);
     if (off != dq::kOffRec) return DQ_EINVAL;
-    P.reg_lo[3] = off;
-    P.reg_hi[3] = (uint32_t)blob.size();
+    range(0, off, 3);
   }
+  const uint32_t want_dec[3] = {dq::kOffDec2, dq::kOffDec4, dq::kOffDec8};
+  const uint32_t want_tab[3] = {0, dq::kOffTab4, dq::kOffTab8};
   for (int wi = 0; wi < 3; ++wi) {
     const int R = Rs[wi], b = 2 << wi;  // widths 2, 4, 8
     std::vector<float> T, D;
     if (!build_levels(R, gs[wi], T, D)) return DQ_EINVAL;
-    while (blob.size() % 4) blob.push_back(0);
-    P.reg_lo[wi] = (uint32_t)blob.size();
     // decode table indexed by one byte of packed codes: the 8/b signed levels it holds,
     // lowest bits first; a code is sign << (b-1) | r
     const int per_byte = 8 / b;
@@ -212,38 +217,34 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
         const float t = T[code & R];
         dec[(size_t)byte * per_byte + j] = fbits((code >> (b - 1)) ? -t : t);
       }
-    append_aligned(blob, dec, &P.off_dec[wi]);
-    if (wi == 1) {  // sign bit of entry k of a word -> bit 4k+3
-      std::vector<uint32_t> sp(256);
-      for (int byte = 0; byte < 256; ++byte) {
-        uint32_t w = 0;
-        for (int k = 0; k < 8; ++k)
-          if ((byte >> k) & 1) w |= 1u << (4 * k + 3);
-        sp[byte] = w;
-      }
-      uint32_t off;
-      append_aligned(blob, sp, &off);
-      if (off != dq::kOffSpread4) return DQ_EINVAL;
-    }
+    uint32_t off_dec = 0, off_tab = 0;
+    append_aligned(blob, dec, &off_dec);
+    if (off_dec != want_dec[wi]) return DQ_EINVAL;
     if (wi > 0) {  // levels {0,1} need no search
       std::vector<uint32_t> tab(2 * (size_t)(R + 1));
       for (int r = 0; r <= R; ++r) {
         tab[2 * r] = fbits(T[r]);
         tab[2 * r + 1] = fbits(D[r]);
       }
-      append_aligned(blob, tab, &P.off_tab[wi]);
+      append_aligned(blob, tab, &off_tab);
+      if (off_tab != want_tab[wi]) return DQ_EINVAL;
       int m = 0;
-      std::vector<uint32_t> lut;
-      if (!build_search(T, R, &m, lut)) return DQ_EUNSUPPORTED;
-      append_aligned(blob, lut, &P.off_lut[wi]);
+      if (!build_search(T, R, &m, lut[wi])) return DQ_EUNSUPPORTED;
       P.magic[wi] = (float)ldexp(1.0, 23 - m);
     }
     while (blob.size() % 4) blob.push_back(0);
-    P.reg_hi[wi] = (uint32_t)blob.size();
+    range(1 + wi, off_dec, (uint32_t)wi);
   }
-  if (P.off_dec[0] != dq::kOffDec2 || P.off_dec[1] != dq::kOffDec4 || P.off_tab[1] != dq::kOffTab4 ||
-      P.off_lut[1] != dq::kOffLut4)
-    return DQ_EINVAL;
+  {
+    uint32_t off;
+    append_aligned(blob, lut[1], &off);
+    if (off != dq::kOffLut4) return DQ_EINVAL;
+    while (blob.size() % 4) blob.push_back(0);
+    range(4, off, 1);
+    append_aligned(blob, lut[2], &P.off_lut8);
+    while (blob.size() % 4) blob.push_back(0);
+    range(5, P.off_lut8, 2);
+  }
   if (blob.size() * 4 > 60 * 1024) return DQ_EUNSUPPORTED;
 
   dq_ctx *ctx = new (std::nothrow) dq_ctx;
@@ -263,6 +264,16 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
     drop_events(ctx);
     delete ctx;
     return DQ_EHIP;
+  }
+  {  // the kernels address their tables from LDS byte 0: true as long as they have no static LDS
+    size_t static_lds = 0;
+    if (!hip_ok(dq::static_lds_bytes(&static_lds)) || static_lds != 0) {
+      if (static_lds != 0) g_hip_error = "codec kernels were built with static LDS: table addresses would be off";
+      (void)hipFree(ctx->blob_dev);
+      drop_events(ctx);
+      delete ctx;
+      return DQ_EHIP;
+    }
   }
   ctx->n_cu = (uint32_t)prop.multiProcessorCount;
   uint32_t per_cu = 6;

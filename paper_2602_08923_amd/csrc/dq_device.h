@@ -42,25 +42,27 @@ inline Job make_job(const uint8_t *in, const void *local, const float *mu, void 
   return j;
 }
 
-// Fixed part of the table blob (dword offsets).  The tables whose size does not depend on the
-// level sets sit at constant places, so the kernels address them with immediate offsets.
+// Table blob (dword offsets).  The tables whose size does not depend on the level sets come
+// first, at constant places, so that the kernels address them with immediate offsets; the two
+// search tables, whose size follows the level sets, come last.  The kernels take LDS byte address
+// 0 for the start of the blob: they use dynamic LDS only, which starts at 0 when a kernel has no
+// static LDS (checked once per context, see static_lds_bytes).
 constexpr uint32_t kOffRec = 0;        // 128 pairs {bits((1+m/128)/255), bits(255/(1+m/128))}
-constexpr uint32_t kOffDec2 = 256;     // 2-bit decode: 256 bytes x 4 levels
-constexpr uint32_t kOffDec4 = 1280;    // 4-bit decode: 256 bytes x 2 levels
-constexpr uint32_t kOffSpread4 = 1792; // 8 sign bits -> bits 4k+3
-constexpr uint32_t kOffTab4 = 2048;    // 8 pairs {T, D}
-constexpr uint32_t kOffLut4 = 2064;    // search table of the 4-bit set (size depends on the set)
+constexpr uint32_t kOffDec2 = 256;     // 2-bit decode: 256 bytes x 4 signed levels
+constexpr uint32_t kOffDec4 = 1280;    // 4-bit decode: 256 bytes x 2 signed levels
+constexpr uint32_t kOffTab4 = 1792;    // 8 pairs {T, D}
+constexpr uint32_t kOffDec8 = 1808;    // 8-bit decode: 256 signed levels
+constexpr uint32_t kOffTab8 = 2064;    // 128 pairs {T, D}
+constexpr uint32_t kOffLut4 = 2320;    // search table of the 4-bit set: (2^m + 1) pairs {next level, candidate index}
+constexpr int kRanges = 6;             // copy ranges: common, 2-bit, 4-bit fixed, 8-bit fixed, 4-bit search, 8-bit search
 
 // Everything the kernels need besides the job: PRNG key, worker count, table blob.
-// The blob holds one region per width (2, 4, 8 bits), each region = [decode table | search
-// table | level/gap table]; a block copies only the regions of the widths it will meet.
 struct Params {
   const uint32_t *blob;  // device copy of the table blob
   uint32_t blob_dwords;  // multiple of 4
-  uint32_t reg_lo[4], reg_hi[4];  // dword range of each width's region and of the common one (multiples of 4)
-  uint32_t off_dec[3];   // decode table indexed by one code BYTE: 8/b signed levels (+-T[r]) per entry
-  uint32_t off_lut[3];   // search table: (2^m + 1) pairs {next level, candidate index}
-  uint32_t off_tab[3];   // level/gap pairs {T[r], D[r]}, r = 0..R (D[R] = 0)
+  uint32_t range_lo[kRanges], range_hi[kRanges];  // dword ranges a block copies into LDS (multiples of 4) ...
+  uint32_t range_width[kRanges];                  // ... if it meets tiles of this width index (3: always)
+  uint32_t off_lut8;     // search table of the 8-bit set (dword offset; its size follows the set)
   float magic[3];        // 2^(23-m): adding it leaves round(x * 2^m) in the low mantissa bits
   uint32_t key0, key1, round;
   uint32_t n_workers;
@@ -81,6 +83,9 @@ hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, bool gather, 
 
 // 16 zero bytes at a 16-byte aligned device address, written by a kernel
 hipError_t clear16(void *p, hipStream_t stream);
+
+// Largest static LDS size over the codec kernels (must be 0: they address their tables from LDS byte 0)
+hipError_t static_lds_bytes(size_t *bytes);
 
 // DQ_OK, or DQ_EHIP after recording the error's text for dq_last_hip_error (dq_api.cpp)
 dq_status hip_status(hipError_t e);

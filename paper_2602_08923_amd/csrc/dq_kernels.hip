@@ -6,7 +6,7 @@
 // (SG), so the group maximum is in-lane and the SG maximum is four row-rotate DPP steps; a
 // wave64 processes 4 SGs per tile and a run of consecutive tiles per launch.  Codes travel as
 // one 32/64/128-bit access per lane (2/4/8-bit widths), the local slice as 128-bit accesses.
-// Level tables live in LDS (a block copies only the widths it meets):
+// Level tables live in LDS from byte 0 on (a block copies only the widths it meets):
 //   dec[byte]      the 8/b signed levels (+-T[r]) one byte of packed codes holds  -> decode
 //   lut[q]         {T[rc+1], rc} for q = round(x' * 2^m): rc is the level index at the
 //                  lower edge of the bin, and bins are narrower than any gap, so the
@@ -114,15 +114,6 @@ __device__ __forceinline__ float row_max16(float m) {
   return u2f(x);
 }
 
-// bit i of a 16-bit value -> bit 2i
-__device__ __forceinline__ uint32_t spread16(uint32_t x) {
-  x = (x | (x << 8)) & 0x00FF00FFu;
-  x = (x | (x << 4)) & 0x0F0F0F0Fu;
-  x = (x | (x << 2)) & 0x33333333u;
-  x = (x | (x << 1)) & 0x55555555u;
-  return x;
-}
-
 template <int B>
 struct Width;
 template <>
@@ -132,23 +123,23 @@ struct Width<4> { static constexpr int words = 2; };
 template <>
 struct Width<8> { static constexpr int words = 4; };
 
-// LDS byte addresses of the tables: constants for the fixed part of the blob (2- and 4-bit
-// sets), kernel parameters for the 8-bit set.
+// LDS byte addresses of the tables.  The blob sits at LDS byte 0 (these kernels have dynamic LDS
+// only), so the fixed-size tables are compile-time constants that the compiler folds into the
+// offset field of the LDS instructions; only the two search tables are found through parameters.
+constexpr uint32_t kLds0 = 0;
+constexpr uint32_t kRec0 = kLds0 + kOffRec * 4;
 template <int B>
-__device__ __forceinline__ uint32_t dec_addr(const Params &P, uint32_t lds0) {
-  if constexpr (B == 2) return lds0 + kOffDec2 * 4;
-  else if constexpr (B == 4) return lds0 + kOffDec4 * 4;
-  else return lds0 + P.off_dec[2] * 4;
+__device__ __forceinline__ constexpr uint32_t dec_addr() {
+  return kLds0 + (B == 2 ? kOffDec2 : (B == 4 ? kOffDec4 : kOffDec8)) * 4;
 }
 template <int B>
-__device__ __forceinline__ uint32_t tab_addr(const Params &P, uint32_t lds0) {
-  if constexpr (B == 4) return lds0 + kOffTab4 * 4;
-  else return lds0 + P.off_tab[2] * 4;
+__device__ __forceinline__ constexpr uint32_t tab_addr() {
+  return kLds0 + (B == 4 ? kOffTab4 : kOffTab8) * 4;
 }
 template <int B>
-__device__ __forceinline__ uint32_t lut_addr(const Params &P, uint32_t lds0) {
-  if constexpr (B == 4) return lds0 + kOffLut4 * 4;
-  else return lds0 + P.off_lut[2] * 4;
+__device__ __forceinline__ uint32_t lut_addr(const Params &P) {
+  if constexpr (B == 4) return kLds0 + kOffLut4 * 4;
+  else return kLds0 + P.off_lut8 * 4;
 }
 
 // Where a tile (index t in the job's concatenated 2-, 4-, 8-, 16-bit tile sequence) sits.
@@ -304,11 +295,10 @@ __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePo
 }
 
 // One wave tile of compress / DAR after the fetch: up to 4 super-groups of width B.
-//   lds0     : LDS byte address of the table blob
 //   stage    : LDS byte address of this tile's 8 parked draws (row r: [2r] = permutation
 //              stream, [2r+1] = group-scale stream), 16 bytes each
 template <int B, Kind KIND, typename LT>
-__device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_t lds0, uint32_t stage,
+__device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_t stage,
                                         const TilePos pos, const Fetch<B, KIND, LT> &f) {
   using W = Width<B>;
   static_assert(KIND != kDecompress, "decompress has its own tile function");
@@ -319,7 +309,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const bool active = row <= tb.last_row;
   const uint32_t rowc = min(row, tb.last_row);
   const uint32_t lg = rowc * 16 + g;
-  const uint32_t rec0 = lds0 + kOffRec * 4;
+  constexpr uint32_t rec0 = kRec0;
 
   float v[16];
   widen_local<LT>(f.loc, v);
@@ -328,7 +318,7 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   if constexpr (KIND == kDar) {
     // decode: sf_G = r_G * (sf_SG / 255); estimate = +-T[r] * sf_G, accumulated by one fma
     const float sfg = (float)f.rg_in * sf_over_255(f.sf_in, rec0);
-    const uint32_t dec0 = dec_addr<B>(P, lds0);
+    constexpr uint32_t dec0 = dec_addr<B>();
 #pragma unroll
     for (int j = 0; j < 2 * B; ++j) {  // one table entry per code byte
       const uint32_t byte = (f.cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
@@ -378,57 +368,49 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const float inv = rg ? 1.0f / m : 0.0f;
 
   // ------------------------------------------------------------------ entries
-  // level indices and sign bits are collected separately: the sign bits by one funnel shift
-  // per entry (entry 0 last, so it lands in bit 0), spread to their code positions at the end
+  // x' = |v| * inv needs no clamp: |v| <= m and inv is the correctly rounded 1/m, so the exact
+  // product is at most 1 + 2^-24, which rounds to 1.  The product is taken with v's sign (xs): the
+  // magnitude serves the search and the rounding through source modifiers, the top bit is the
+  // code's sign bit (for inv = 0 the product is a zero with v's sign).
+  // The code words grow from the top: entry 15 first, each step shifts the word by one code and
+  // appends sign and level index, so the lowest entry of a word ends in its low bits.  A group
+  // whose scale rounded to zero has inv = 0, hence x' = 0 and level 0 throughout: only signs remain.
   uint32_t ow[W::words];
-  uint32_t sbits = 0;
+#pragma unroll
+  for (int i = 0; i < W::words; ++i) ow[i] = 0;
   const uint32_t gw[4] = {gam.x, gam.y, gam.z, gam.w};
   if constexpr (B == 2) {
-    // levels {0,1}: T + u*D = u, so the level bit is [u < x']
-    uint32_t rbits = 0;
+    // levels {0,1}: T + u*D = u, so the level bit is [u < x'] -- the sign bit of u - x' (the
+    // difference of two different binary32 numbers is never zero)
 #pragma unroll
     for (int k = 15; k >= 0; --k) {
-      const float x = __builtin_amdgcn_fmed3f(fabsf(v[k]) * inv, 0.0f, 1.0f);
+      const float xs = v[k] * inv;
       const uint32_t byte = (gw[k >> 2] >> (8 * (k & 3))) & 0xFFu;
       const float u = __builtin_fmaf((float)byte, P.s_n, o_pi);
-      rbits = rbits + rbits + ((u < x) ? 1u : 0u);
-      sbits = __builtin_amdgcn_alignbit(sbits, f2u(v[k]), 31);  // (sbits << 1) | sign
+      const float d = u - fabsf(xs);
+      ow[0] = __builtin_amdgcn_alignbit(ow[0], f2u(xs), 31);  // (word << 1) | sign
+      ow[0] = __builtin_amdgcn_alignbit(ow[0], f2u(d), 31);   // (word << 1) | level
     }
-    ow[0] = (rg ? spread16(rbits) : 0u) | (spread16(sbits & 0xFFFFu) << 1);
   } else {
     const float magic = P.magic[B == 4 ? 1 : 2];
     // byte address of lut[q] is lut0 + 8*q with q = bits(x + magic) - bits(magic)
-    const uint32_t lut_k = lut_addr<B>(P, lds0) - (f2u(magic) << 3);
-    const uint32_t tab0 = tab_addr<B>(P, lds0);
+    uint32_t lut_k = lut_addr<B>(P) - (f2u(magic) << 3);
+    asm("" : "+s"(lut_k));  // one scalar: (bits << 3) + lut_k is then a single shift-add per entry
+    constexpr uint32_t tab0 = tab_addr<B>();
     constexpr int per_word = 32 / B;
 #pragma unroll
-    for (int i = 0; i < W::words; ++i) ow[i] = 0;
-#pragma unroll
     for (int k = 15; k >= 0; --k) {
-      const float x = __builtin_amdgcn_fmed3f(fabsf(v[k]) * inv, 0.0f, 1.0f);
+      const float xs = v[k] * inv;
+      const float x = fabsf(xs);
       const uint32_t byte = (gw[k >> 2] >> (8 * (k & 3))) & 0xFFu;
       const float u = __builtin_fmaf((float)byte, P.s_n, o_pi);
       const u32x2 e = lds_ld2((f2u(x + magic) << 3) + lut_k);
-      const uint32_t rlo = e.y + ((x >= u2f(e.x)) ? 1u : 0u);
+      uint32_t rlo = e.y + ((x >= u2f(e.x)) ? 1u : 0u);
+      asm("" : "+v"(rlo));  // keep r = rlo + [..] below from being re-derived as e.y + [..] + [..]
       const u32x2 td = lds_ld2(tab0 + rlo * 8);
-      const uint32_t r = rlo + ((__builtin_fmaf(u, u2f(td.y), u2f(td.x)) < x) ? 1u : 0u);
-      ow[k / per_word] |= r << ((k % per_word) * B);
-      sbits = __builtin_amdgcn_alignbit(sbits, f2u(v[k]), 31);
-    }
-    if constexpr (B == 4) {
-      // sign of entry k -> bit 4k+3: a 256-entry table spreads 8 sign bits over a word
-      const uint32_t sp0 = lds0 + kOffSpread4 * 4;
-      const uint32_t s0 = lds_ld1(sp0 + (sbits & 0xFFu) * 4), s1 = lds_ld1(sp0 + ((sbits >> 8) & 0xFFu) * 4);
-      ow[0] = (rg ? ow[0] : 0u) | s0;
-      ow[1] = (rg ? ow[1] : 0u) | s1;
-    } else {
-      // sign of entry k -> bit 8k+7: x * 0x00204081 puts bit i of a nibble at bit 7i (+...), masked to bytes
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t nib = (sbits >> (4 * i)) & 0xFu;
-        const uint32_t sp = ((nib * 0x00204081u) & 0x01010101u) << 7;
-        ow[i] = (rg ? ow[i] : 0u) | sp;
-      }
+      const uint32_t up = (__builtin_fmaf(u, u2f(td.y), u2f(td.x)) < x) ? 1u : 0u;
+      const uint32_t w = __builtin_amdgcn_alignbit(ow[k / per_word], f2u(xs), 31);  // (word << 1) | sign
+      ow[k / per_word] = (w << (B - 1)) + rlo + up;  // level index r_lo + [rounded up] <= R: no carry into the sign
     }
   }
 
@@ -487,7 +469,7 @@ __device__ __forceinline__ void store_tile_f32(const Job &job, const Params &P, 
 // through a per-wave LDS area so that every store instruction writes 1 KB of contiguous memory.
 //   xpose : LDS byte address of this wave's 4 KB transpose area
 template <int B, typename LT>
-__device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_t lds0, uint32_t xpose,
+__device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_t xpose,
                                         const TilePos pos) {
   using W = Width<B>;
   constexpr bool kHasLocal = !__is_same(LT, NoLocal);
@@ -495,8 +477,8 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t rowc = min(lane >> 4, tb.last_row);
   const uint32_t lg = rowc * 16 + (lane & 15u);
-  const uint32_t rec0 = lds0 + kOffRec * 4;
-  const uint32_t dec0 = dec_addr<B>(P, lds0);
+  constexpr uint32_t rec0 = kRec0;
+  constexpr uint32_t dec0 = dec_addr<B>();
 
   // the incoming words first: with job.src the local loads wait for an index
   uint32_t cw[W::words];
@@ -607,13 +589,15 @@ __device__ __forceinline__ void tile16(const Job &job, const Params &P, uint32_t
 
 // `len` consecutive tiles of width B starting at `pos` (their parked draws 128 bytes apart).
 // Fetch and compute are separate steps, but measurements showed no gain from fetching a tile
-// ahead: the kernel is bound by instruction issue, not by memory latency.
+// ahead, nor from touching a wave's first tiles before the block waits for its tables (one load
+// per 128-byte line, values unused: a config-2 launch got 1 us slower): the kernel is bound by
+// instruction issue, not by memory latency.
 template <int B, Kind KIND, typename LT>
-__device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint32_t lds0, uint32_t stage, TilePos pos,
+__device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint32_t stage, TilePos pos,
                                           uint32_t len) {
   for (uint32_t i = 0; i < len; ++i) {
     const Fetch<B, KIND, LT> f = fetch<B, KIND, LT>(job, pos);
-    compute<B, KIND, LT>(job, P, lds0, stage + i * 128, pos, f);
+    compute<B, KIND, LT>(job, P, stage + i * 128, pos, f);
     pos.tile_first += kWaveSGs;
   }
 }
@@ -661,16 +645,16 @@ __device__ __forceinline__ void park_draws(const Job &job, const Params &P, uint
 
 // Tiles [t_first, t_first + nb) of the job, whose draws are parked from `area` on.
 template <Kind KIND, typename LT>
-__device__ __forceinline__ void run_range(const Job &job, const Params &P, uint32_t lds0, uint32_t area,
+__device__ __forceinline__ void run_range(const Job &job, const Params &P, uint32_t area,
                                           uint32_t t_first, uint32_t nb) {
   for (uint32_t j = 0; j < nb;) {
     const TilePos p = locate(job, t_first + j);
     const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;  // tiles to the segment's end
     const uint32_t len = min(nb - j, left);
     const uint32_t stage = area + j * 128;
-    if (p.wi == 0) run_tiles<2, KIND, LT>(job, P, lds0, stage, p, len);
-    else if (p.wi == 1) run_tiles<4, KIND, LT>(job, P, lds0, stage, p, len);
-    else if (p.wi == 2) run_tiles<8, KIND, LT>(job, P, lds0, stage, p, len);
+    if (p.wi == 0) run_tiles<2, KIND, LT>(job, P, stage, p, len);
+    else if (p.wi == 1) run_tiles<4, KIND, LT>(job, P, stage, p, len);
+    else if (p.wi == 2) run_tiles<8, KIND, LT>(job, P, stage, p, len);
     else {
       TilePos q = p;
       for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<KIND, LT>(job, P, 0u, q);
@@ -695,7 +679,7 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   const uint32_t b_lo = bw * q + min(bw, r);
   const uint32_t b_hi = (bw + kBlockWaves) * q + min(bw + kBlockWaves, r);
   if (b_lo >= b_hi) return;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t *)lds;
+  constexpr uint32_t lds0 = kLds0;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t wv = bw + wave;
   const uint32_t w_lo = wv * q + min(wv, r);
@@ -706,28 +690,31 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   // instead of one call per wave (waves of a small job hold only a tile or two each)
   const bool block_draws = KIND != kDecompress && (b_hi - b_lo) <= 8u * kBlockWaves;
 
-  // copy the common tables and the table regions of the widths this block meets; the first
-  // 16 bytes per thread of every region are requested together (one round trip, not four)
-  const bool need[4] = {b_lo < t0, b_lo < t0 + t1 && b_hi > t0, b_lo < t0 + t1 + t2 && b_hi > t0 + t1, true};
-  uint4 first[4];
-  bool has[4];
+  // copy the common tables and the table ranges of the widths this block meets; the first
+  // 16 bytes per thread of every range are requested together (one round trip, not six)
+  const bool meets[4] = {b_lo < t0, b_lo < t0 + t1 && b_hi > t0, b_lo < t0 + t1 + t2 && b_hi > t0 + t1, true};
+  constexpr int kEarly = kRanges;
+  uint4 first[kEarly];
+  bool need[kRanges], has[kEarly];
 #pragma unroll
-  for (int wi = 0; wi < 4; ++wi) {
-    const uint32_t i = P.reg_lo[wi] + threadIdx.x * 4;
-    has[wi] = need[wi] && i < P.reg_hi[wi];
-    if (has[wi]) first[wi] = gld16(&P.blob[i]);
+  for (int r = 0; r < kRanges; ++r) need[r] = meets[P.range_width[r] & 3u];
+#pragma unroll
+  for (int r = 0; r < kEarly; ++r) {
+    const uint32_t i = P.range_lo[r] + threadIdx.x * 4;
+    has[r] = need[r] && i < P.range_hi[r];
+    if (has[r]) first[r] = gld16(&P.blob[i]);
   }
   if constexpr (KIND != kDecompress) {
     if (block_draws && 8u * wave < b_hi - b_lo)
       park_draws(job, P, b_lo + 8u * wave, min(8u, b_hi - b_lo - 8u * wave), park0 + wave * 1024);
   }
 #pragma unroll
-  for (int wi = 0; wi < 4; ++wi)
-    if (has[wi]) *reinterpret_cast<uint4 *>(&lds[P.reg_lo[wi] + threadIdx.x * 4]) = first[wi];
+  for (int r = 0; r < kEarly; ++r)
+    if (has[r]) *reinterpret_cast<uint4 *>(&lds[P.range_lo[r] + threadIdx.x * 4]) = first[r];
 #pragma unroll
-  for (int wi = 0; wi < 4; ++wi)
-    if (need[wi])
-      for (uint32_t i = P.reg_lo[wi] + (kBlockThreads + threadIdx.x) * 4; i < P.reg_hi[wi]; i += kBlockThreads * 4)
+  for (int r = 0; r < kRanges; ++r)
+    if (need[r])
+      for (uint32_t i = P.range_lo[r] + ((r < kEarly ? kBlockThreads : 0) + threadIdx.x) * 4; i < P.range_hi[r]; i += kBlockThreads * 4)
         *reinterpret_cast<uint4 *>(&lds[i]) = gld16(&P.blob[i]);
   __syncthreads();
 
@@ -736,25 +723,26 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
     const uint32_t xpose = park0 + wave * (64 * 64);
     for (uint32_t t = w_lo; t < w_hi; ++t) {
       const TilePos p = locate(job, t);
-      if (p.wi == 0) tile_da<2, LT>(job, P, lds0, xpose, p);
-      else if (p.wi == 1) tile_da<4, LT>(job, P, lds0, xpose, p);
-      else if (p.wi == 2) tile_da<8, LT>(job, P, lds0, xpose, p);
+      if (p.wi == 0) tile_da<2, LT>(job, P, xpose, p);
+      else if (p.wi == 1) tile_da<4, LT>(job, P, xpose, p);
+      else if (p.wi == 2) tile_da<8, LT>(job, P, xpose, p);
       else tile16<kDecompress, LT>(job, P, xpose, p);
     }
   } else if (block_draws) {
-    run_range<KIND, LT>(job, P, lds0, park0 + (w_lo - b_lo) * 128, w_lo, w_hi - w_lo);
+    run_range<KIND, LT>(job, P, park0 + (w_lo - b_lo) * 128, w_lo, w_hi - w_lo);
   } else {
     const uint32_t area = park0 + wave * 1024;
     for (uint32_t tb = w_lo; tb < w_hi; tb += kBatch) {
       const uint32_t nb = min((uint32_t)kBatch, w_hi - tb);
       park_draws(job, P, tb, nb, area);
       __builtin_amdgcn_wave_barrier();
-      run_range<KIND, LT>(job, P, lds0, area, tb, nb);
+      run_range<KIND, LT>(job, P, area, tb, nb);
       __builtin_amdgcn_wave_barrier();
     }
   }
 }
 
+// Six blocks of four waves are resident per CU (the launcher's grid): at most 80 vector registers.
 template <Kind KIND, typename LT>
 __global__ __launch_bounds__(kBlockThreads) void k_one(Job job, Params P) {
   run_job<KIND, LT>(job, P);
@@ -848,6 +836,36 @@ hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, bool gather, 
 #undef ARGS
 }
 #undef DQ_DISPATCH_LOCAL
+
+namespace {
+template <typename K>
+hipError_t add_static_lds(K kernel, size_t *bytes) {
+  hipFuncAttributes attr;
+  const hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(kernel));
+  if (e == hipSuccess && attr.sharedSizeBytes > *bytes) *bytes = attr.sharedSizeBytes;
+  return e;
+}
+template <Kind KIND, typename LT>
+hipError_t add_static_lds_of(size_t *bytes) {
+  const hipError_t e = add_static_lds(k_one<KIND, LT>, bytes);
+  return e != hipSuccess ? e : add_static_lds(k_batch<KIND, LT>, bytes);
+}
+}  // namespace
+
+hipError_t static_lds_bytes(size_t *bytes) {
+  *bytes = 0;
+  hipError_t e = add_static_lds_of<kDecompress, NoLocal>(bytes);
+#define DQ_ONE_KIND(KINDV)                                                             \
+  if (e == hipSuccess) e = add_static_lds_of<KINDV, float>(bytes);                     \
+  if (e == hipSuccess) e = add_static_lds_of<KINDV, uint16_t>(bytes);                  \
+  if (e == hipSuccess) e = add_static_lds_of<KINDV, Gathered<float>>(bytes);           \
+  if (e == hipSuccess) e = add_static_lds_of<KINDV, Gathered<uint16_t>>(bytes);
+  DQ_ONE_KIND(kCompress)
+  DQ_ONE_KIND(kDar)
+  DQ_ONE_KIND(kDecompress)
+#undef DQ_ONE_KIND
+  return e;
+}
 
 hipError_t clear16(void *p, hipStream_t s) {
   hipLaunchKernelGGL(k_clear16, dim3(1), dim3(64), 0, s, static_cast<uint4 *>(p));
