@@ -176,6 +176,8 @@ typedef struct {
   uint32_t inputs_in_original_order; /* 1 (needs origin; ring and butterfly): worker_grads hold the ORIGINAL
                           tensors and every kernel that reads a worker's gradient gathers its super-groups
                           through origin (dq_local.sg_index): no reorder pass at all.  0: reordered inputs. */
+  uint32_t n_grads;    /* how many pointers worker_grads holds: must equal the context's n_workers
+                          (0: not stated, the array is trusted to hold n_workers pointers) */
 } dq_replay_desc;
 
 /* Device scratch the replay needs (job tables, packed messages, fp32 keep-buffers). */
@@ -194,10 +196,24 @@ dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream);
 /* Enqueue steps first .. first+count-1 only (so that a caller can bracket a run of hop steps
  * with its own events); running all steps in order is the same as dq_replay_run. */
 dq_status dq_replay_run_steps(dq_replay *plan, uint32_t first, uint32_t count, void *hip_stream);
-/* Per step: kind (0 compress, 1 DAR, 2 decompress-accumulate, 3 DAR + decompress-accumulate
- * in one launch) and the entries it processes, for throughput accounting. */
+/* Enqueue ONE kernel launch of a step: a butterfly step in which nodes both forward and keep
+ * (kind 3 below) is two launches, 0 = the re-encoding one (compress at the first step, DAR after),
+ * 1 = the decompress-accumulate into the keep-buffers; every other step is launch 0 alone.  Running a
+ * step's launches in order is dq_replay_run_steps(plan, step, 1); a caller uses this to time the DAR
+ * launch of such a step on its own.  DQ_EINVAL if the step has no such launch. */
+dq_status dq_replay_run_launch(dq_replay *plan, uint32_t step, uint32_t launch, void *hip_stream);
+/* Per step: kind (0 compress, 1 DAR, 2 decompress-accumulate, 3 DAR and decompress-accumulate,
+ * two launches) and the entries it processes, for throughput accounting. */
 dq_status dq_replay_step_info(const dq_replay *plan, uint32_t step, uint32_t *kind, uint64_t *entries_dar,
                               uint64_t *entries_other);
+/* DQ_RING / DQ_CHAIN: where the packed message that step `step` writes for chunk `chunk` of bucket
+ * `bucket` sits inside scratch, and its size (dq_packed_bytes of that chunk) -- what the worker that ran
+ * the step would hand to the transport (Section 3.4: the compressed partial sum sent to the next hop).
+ * It stays intact until step + 2 has run (two message sets, written alternately).  DQ_EINVAL for the
+ * last step (it writes fp32 sums, not a message) or indices out of range; DQ_EUNSUPPORTED for a
+ * butterfly plan. */
+dq_status dq_replay_message(const dq_replay *plan, uint32_t step, uint32_t bucket, uint32_t chunk, const void **ptr,
+                            size_t *bytes);
 void dq_replay_destroy(dq_replay *plan);
 
 /* ---------------------------------------------------------------------------------------
@@ -291,6 +307,13 @@ dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local 
 dq_status dq_dar_hop_pipelined_static(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,
                                       uint32_t rank, uint32_t block_sg, void *wire_out, void *compute_stream,
                                       void *copy_stream);
+
+/* ---- Measurement aid, not part of the method: a streaming kernel that reads in_bytes and writes
+ * out_bytes (out[j] = xor of the input's 16-byte words j, j + n_out, j + 2 n_out, ...; both sizes
+ * multiples of 16, 0 < out_bytes <= in_bytes, buffers 16-byte aligned and not overlapping).  With
+ * the read : write ratio of a DAR hop (packed partial sum and local slice in, packed partial sum
+ * out) its rate is the practical ceiling the benchmark sets that hop against. */
+dq_status dq_stream_probe(dq_ctx *ctx, const void *in, size_t in_bytes, void *out, size_t out_bytes, void *hip_stream);
 
 const char *dq_status_str(dq_status s);
 /* Last HIP error string seen by this library on the calling thread (for DQ_EHIP). */

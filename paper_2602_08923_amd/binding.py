@@ -22,7 +22,7 @@ EXPORTS = [
     "dq_decompress_restore",
     "dq_mx_packed_bytes", "dq_mx_compress", "dq_mx_dar_hop", "dq_mx_decompress",
     "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_run_steps",
-    "dq_replay_step_info",
+    "dq_replay_step_info", "dq_replay_message", "dq_replay_run_launch", "dq_stream_probe",
     "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
     "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_reorder", "dq_reorder_mean", "dq_restore",
     "dq_pipelined_wire_bytes", "dq_pipelined_stage_bytes", "dq_dar_hop_pipelined", "dq_dar_hop_pipelined_static",
@@ -47,7 +47,7 @@ class ReplayDesc(C.Structure):
     _fields_ = [("topology", C.c_int), ("codec", C.c_int), ("dtype", C.c_int), ("n_buckets", C.c_uint32),
                 ("n_sg_bucket", C.c_uint64), ("n_sg_by_width", C.POINTER(C.c_uint32)), ("first_sg", C.c_uint64),
                 ("all_gather", C.c_uint32), ("mu", C.c_void_p), ("origin", C.c_void_p),
-                ("inputs_in_original_order", C.c_uint32)]
+                ("inputs_in_original_order", C.c_uint32), ("n_grads", C.c_uint32)]
 
 
 class Local(C.Structure):
@@ -93,6 +93,9 @@ def lib():
         L.dq_replay_run.argtypes = [vp, C.POINTER(C.c_float), vp]
         L.dq_replay_run_steps.argtypes = [vp, u32, u32, vp]
         L.dq_replay_step_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(u64), C.POINTER(u64)]
+        L.dq_replay_message.argtypes = [vp, u32, u32, u32, C.POINTER(vp), C.POINTER(C.c_size_t)]
+        L.dq_replay_run_launch.argtypes = [vp, u32, u32, vp]
+        L.dq_stream_probe.argtypes = [vp, vp, C.c_size_t, vp, C.c_size_t, vp]
         L.dq_replay_destroy.argtypes = [vp]
         L.dq_replay_destroy.restype = None
         L.dq_sg_stats.argtypes = [vp, i, u64, vp, vp, vp]
@@ -299,6 +302,8 @@ class Replay:
         if mu is not None and (mu.dtype != torch.float32 or mu.numel() != n_buckets * n_sg_bucket):
             raise DqError("mu is float32, one per super-group")
         self.grads = list(worker_grads)
+        if len(self.grads) != ctx.n_workers:
+            raise DqError(f"{len(self.grads)} worker gradients for a context of {ctx.n_workers} workers")
         dev = self.grads[0].device
         n = len(self.grads)
         flat = (C.c_uint32 * (4 * n_buckets))()
@@ -308,7 +313,7 @@ class Replay:
                     flat[4 * b + k] = int(n_sg_by_width[b][k])
         self._widths = flat
         desc = ReplayDesc(topology, codec, _dtype(self.grads[0]), n_buckets, n_sg_bucket, flat, first_sg,
-                          1 if all_gather else 0, _ptr(mu), _ptr(origin), 1 if inputs_in_original_order else 0)
+                          1 if all_gather else 0, _ptr(mu), _ptr(origin), 1 if inputs_in_original_order else 0, n)
         self.desc = desc
         entries = n_sg_bucket * 256 * n_buckets
         for g in self.grads:
@@ -336,10 +341,20 @@ class Replay:
     def run_steps(self, first, count):
         _check(lib().dq_replay_run_steps(self.h, first, count, _stream()))
 
+    def run_launch(self, step, launch):
+        _check(lib().dq_replay_run_launch(self.h, step, launch, _stream()))
+
     def step_info(self, step):
         kind, a, b = C.c_uint32(), C.c_uint64(), C.c_uint64()
         _check(lib().dq_replay_step_info(self.h, step, C.byref(kind), C.byref(a), C.byref(b)))
         return kind.value, a.value, b.value
+
+    def message(self, step, bucket, chunk):
+        """The packed message step `step` wrote for (bucket, chunk): a view into the scratch (ring, chain)."""
+        ptr, nbytes = C.c_void_p(), C.c_size_t()
+        _check(lib().dq_replay_message(self.h, step, bucket, chunk, C.byref(ptr), C.byref(nbytes)))
+        off = ptr.value - self.scratch.data_ptr()
+        return self.scratch[off:off + nbytes.value]
 
     def close(self):
         if getattr(self, "h", None) and _lib is not None:
@@ -467,3 +482,9 @@ def dq_dar_hop_pipelined_static(ctx, wire_in, local, chunk, rank, block_sg, comp
                                              C.c_void_p(compute_stream.cuda_stream),
                                              C.c_void_p(copy_stream.cuda_stream)), detail=True)
     return wire_out
+
+
+def dq_stream_probe(ctx, src, dst):
+    """Streaming probe: reads all of src, writes all of dst (uint8 tensors, sizes multiples of 16, dst <= src)."""
+    _check(lib().dq_stream_probe(ctx.h, _ptr(src), src.numel() * src.element_size(), _ptr(dst),
+                                 dst.numel() * dst.element_size(), _stream()))

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdq.so")
-SOURCES = ["dq_kernels.hip", "mx_kernels.hip", "pp_kernels.hip", "dq_api.cpp", "dq_replay.cpp"]
+SOURCES = ["dq_kernels.hip", "mx_kernels.hip", "pp_kernels.hip", "probe_kernels.hip", "dq_api.cpp", "dq_replay.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt",

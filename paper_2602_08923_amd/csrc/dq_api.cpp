@@ -226,6 +226,9 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
         tab[2 * r] = fbits(T[r]);
         tab[2 * r + 1] = fbits(D[r]);
       }
+      // at the top level nothing rounds up: T + u*D is held above every x' the kernels can form (they
+      // do not clamp x' to 1; it can exceed 1 by an ulp when the reciprocal of the group maximum is denormal)
+      tab[2 * R] = fbits(2.0f);
       append_aligned(blob, tab, &off_tab);
       if (off_tab != want_tab[wi]) return DQ_EINVAL;
       int m = 0;
@@ -304,6 +307,13 @@ void dq_destroy(dq_ctx *ctx) {
   if (ctx->blob_dev) (void)hipFree(ctx->blob_dev);
   drop_events(ctx);
   delete ctx;
+}
+
+dq_status dq_stream_probe(dq_ctx *ctx, const void *in, size_t in_bytes, void *out, size_t out_bytes, void *hip_stream) {
+  if (!ctx || !in || !out || in_bytes == 0 || out_bytes == 0 || out_bytes > in_bytes) return DQ_EINVAL;
+  if ((in_bytes | out_bytes) & 15u) return DQ_EINVAL;
+  if (!aligned16(in) || !aligned16(out)) return DQ_EALIGN;
+  return dq::hip_status(dq::stream_probe(in, in_bytes, out, out_bytes, ctx->n_cu, (hipStream_t)hip_stream));
 }
 
 dq_status dq_set_round(dq_ctx *ctx, uint32_t round) {

@@ -87,6 +87,9 @@ hipError_t clear16(void *p, hipStream_t stream);
 // Largest static LDS size over the codec kernels (must be 0: they address their tables from LDS byte 0)
 hipError_t static_lds_bytes(size_t *bytes);
 
+// streaming probe (probe_kernels.hip): reads in_bytes, writes out_bytes (multiples of 16, out <= in)
+hipError_t stream_probe(const void *in, size_t in_bytes, void *out, size_t out_bytes, uint32_t n_cu, hipStream_t stream);
+
 // DQ_OK, or DQ_EHIP after recording the error's text for dq_last_hip_error (dq_api.cpp)
 dq_status hip_status(hipError_t e);
 

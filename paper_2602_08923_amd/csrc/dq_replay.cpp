@@ -49,6 +49,12 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Plan {
   std::vector<Step> steps;
   size_t scratch_bytes = 0;
+  // ring and chain only: where the message of (bucket, chunk) sits inside a message set, its size, and
+  // the two sets' starts (step t writes set t & 1); what dq_replay_message answers from
+  std::vector<size_t> ring_slot, ring_bytes;
+  uint8_t *ring_msg[2] = {nullptr, nullptr};
+  uint32_t ring_chunks = 0;   // chunks per bucket (0: not a ring or chain)
+  uint32_t ring_message_steps = 0;  // steps 0 .. this-1 write messages
 };
 
 bool is_mx(dq_codec c) { return c == DQ_MXFP8_E4M3 || c == DQ_MXFP6_E3M2 || c == DQ_MXFP4_E2M1; }
@@ -174,6 +180,13 @@ dq_status build_plan(const dq_ctx *ctx, const dq_replay_desc *d, const void *con
     }
     uint8_t *msg[2] = {base + off, base + off + set_bytes};
     off += 2 * set_bytes;
+    plan->ring_slot = slot;
+    plan->ring_bytes.resize(ci.size());
+    for (size_t i = 0; i < ci.size(); ++i) plan->ring_bytes[i] = ci[i].bytes;
+    plan->ring_msg[0] = msg[0];
+    plan->ring_msg[1] = msg[1];
+    plan->ring_chunks = n_chunks;
+    plan->ring_message_steps = n - 1;
     const uint32_t hops = n;  // steps 0 .. n-1
     for (uint32_t t = 0; t < hops; ++t) {
       Step st;
@@ -351,6 +364,7 @@ dq_status dq_replay_create(dq_ctx *ctx, const dq_replay_desc *desc, const void *
                            size_t scratch_bytes, float *out, dq_replay **plan_out) {
   if (!ctx || !desc || !worker_grads || !scratch || !out || !plan_out) return DQ_EINVAL;
   *plan_out = nullptr;
+  if (desc->n_grads != 0 && desc->n_grads != ctx->cfg.n_workers) return DQ_EINVAL;
   if ((reinterpret_cast<uintptr_t>(scratch) & 255u) || (reinterpret_cast<uintptr_t>(out) & 15u)) return DQ_EALIGN;
   for (uint32_t w = 0; w < ctx->cfg.n_workers; ++w) {
     if (!worker_grads[w]) return DQ_EINVAL;
@@ -419,9 +433,13 @@ dq_status dq_replay_step_info(const dq_replay *plan, uint32_t step, uint32_t *ki
   return DQ_OK;
 }
 
-static dq_status run_step(dq_replay *plan, size_t i, hipStream_t s) {
+// only: -1 = every launch of the step, else the index of the one launch to enqueue
+static dq_status run_step(dq_replay *plan, size_t i, hipStream_t s, int only = -1) {
   const bool mx = plan->codec != DQ_DYNAMIQ;
+  int index = -1;
   for (const Launch &L : plan->plan.steps[i].launches) {
+    ++index;
+    if (only >= 0 && index != only) continue;
     if (L.n_jobs == 0) continue;
     hipError_t e;
     if (mx)
@@ -445,6 +463,11 @@ dq_status dq_replay_run_steps(dq_replay *plan, uint32_t first, uint32_t count, v
   return DQ_OK;
 }
 
+dq_status dq_replay_run_launch(dq_replay *plan, uint32_t step, uint32_t launch, void *hip_stream) {
+  if (!plan || step >= plan->plan.steps.size() || launch >= plan->plan.steps[step].launches.size()) return DQ_EINVAL;
+  return run_step(plan, step, (hipStream_t)hip_stream, (int)launch);
+}
+
 dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream) {
   if (!plan) return DQ_EINVAL;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -465,6 +488,18 @@ dq_status dq_replay_run(dq_replay *plan, float *step_ms, void *hip_stream) {
   for (size_t i = 0; step_ms && i < ns && he == hipSuccess; ++i)
     he = hipEventElapsedTime(&step_ms[i], plan->events[i], plan->events[i + 1]);
   return dq::hip_status(he);
+}
+
+dq_status dq_replay_message(const dq_replay *plan, uint32_t step, uint32_t bucket, uint32_t chunk, const void **ptr,
+                            size_t *bytes) {
+  if (!plan || !ptr || !bytes) return DQ_EINVAL;
+  const Plan &p = plan->plan;
+  if (p.ring_chunks == 0) return DQ_EUNSUPPORTED;
+  const size_t i = (size_t)bucket * p.ring_chunks + chunk;
+  if (step >= p.ring_message_steps || chunk >= p.ring_chunks || i >= p.ring_slot.size()) return DQ_EINVAL;
+  *ptr = p.ring_msg[step & 1] + p.ring_slot[i];
+  *bytes = p.ring_bytes[i];
+  return DQ_OK;
 }
 
 void dq_replay_destroy(dq_replay *plan) {

@@ -57,3 +57,15 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert L.dq_reorder_mean(None, None, None, 4, 1, None, None, None) == B.DQ_EINVAL
     assert L.dq_mx_compress(1, None, 0, 256, None, None) == B.DQ_EINVAL
     assert L.dq_replay_n_steps(None) == 0
+
+
+def test_replay_binding_checks_the_worker_count():
+    """A context of 8 workers and 3 gradient tensors: refused before anything reads past the list."""
+    import torch
+
+    class FakeCtx:
+        n_workers = 8
+        h = None
+
+    with pytest.raises(B.DqError, match="3 worker gradients for a context of 8"):
+        B.Replay(FakeCtx(), B.DQ_RING, B.DQ_DYNAMIQ, [torch.zeros(256 * 8, dtype=torch.bfloat16)] * 3, 8, [[0, 8, 0]])

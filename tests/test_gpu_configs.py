@@ -37,12 +37,25 @@ def test_config2_ring8_bf16_25mb_full(dev):
     assert sum(counts) == n_sg and counts[0] > 0 and counts[1] > 0   # ~4 bits: a mix of 2- and 4-bit SGs
     seed = 2024
     mu = prep.mean_per_super_group(re)                                # as bench.py runs it: means subtracted
+    trace = {}
     want = np.concatenate(O.ring_reduce_scatter(O.Oracle(n, seed=seed), [workloads.to_numpy(g) for g in re], counts,
-                                                mu=mu.numpy()))
+                                                mu=mu.numpy(), trace=trace))
     ctx = B.Context(n, seed=seed)
     rp = B.Replay(ctx, B.DQ_RING, B.DQ_DYNAMIQ, [g.to(dev) for g in re], n_sg, [counts], mu=mu.to(dev))
     assert rp.n_steps == 8 and [rp.step_info(i)[0] for i in range(8)] == [0, 1, 1, 1, 1, 1, 1, 2]
-    rp.run()
+    # every hop's packed message (codes, group scales, super-group scales) at full size, in the launch
+    # shape the benchmark times: one step at a time, all 8 chunks of the step against the oracle's trace
+    for t in range(n - 1):
+        rp.run_steps(t, 1)
+        torch.cuda.synchronize()
+        for c in range(n):
+            assert np.array_equal(host(rp.message(t, 0, c)), trace[(t, c)]), f"message of step {t}, chunk {c}"
+    with pytest.raises(B.DqError):
+        rp.message(n - 1, 0, 0)                                       # the last step writes sums, not a message
+    rp.run_steps(n - 1, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+    rp.run()                                                          # and the whole schedule in one go, as timed
     torch.cuda.synchronize()
     got = host(rp.out)
     assert np.array_equal(got, want)

@@ -112,7 +112,8 @@ def test_new_round_draws_new_numbers(dev):
 
 def test_degenerate_inputs(dev):
     """All-zero chunk, signed zeros, values below the flush threshold, denormal groups,
-    one huge outlier, exact powers of two."""
+    one huge outlier, exact powers of two, magnitudes whose reciprocal is denormal (there the
+    normalised maximum can exceed 1 by an ulp before the rule's clamp)."""
     n, n_sg = 4, [2, 2, 2]
     entries = 6 * 256
     rng = np.random.default_rng(31)
@@ -130,6 +131,11 @@ def test_degenerate_inputs(dev):
     variants.append(o)
     p = np.ldexp(1.0, rng.integers(-20, 3, entries)).astype(np.float32) * rng.choice([-1.0, 1.0], entries).astype(np.float32)
     variants.append(p)
+    h = (rng.standard_normal(entries) * 2e37).astype(np.float32)
+    big = np.array([0x7F4006EE], np.uint32).view(np.float32)[0]   # 2.55e38: big * fp32(1/big) = 1 + 2^-22
+    assert np.float32(big * (np.float32(1.0) / big)) > 1.0
+    h[5::256] = 1.5e38; h[6::256] = -1.5e38; h[40::256] = big; h[41::256] = -big; h[100::256] = big
+    variants.append(h)
     prev_o = prev_g = None
     for v in variants:
         w = orc.compress(och, 2, v)
