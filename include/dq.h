@@ -15,8 +15,10 @@
  *     and return without synchronising; the library allocates device memory only in
  *     dq_create / dq_replay_create and never per call.
  *   - Errors are return codes only; on any error nothing has been enqueued.  Inputs
- *     must be finite and partial sums must stay below the largest bf16; otherwise the
- *     codes are unspecified (but no access leaves the buffers).
+ *     must be finite and partial sums must stay below the largest bf16: the library does
+ *     not check this, and the result for other inputs is unspecified.  (Addresses in device
+ *     memory are computed from the descriptors alone, never from data values; the lookups
+ *     in the on-chip tables are indexed by the normalised values and rely on finite inputs.)
  *   - The result of a call is a pure function of (config, chunk descriptor, rank,
  *     input bytes): it does not depend on grid size, batching or call order.
  *

@@ -602,9 +602,6 @@ __device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint3
   }
 }
 
-// The job's tiles are split evenly over all waves of the grid row (4 * gridDim.x waves):
-// wave w takes [w*T/W, (w+1)*T/W).  The launcher sizes the grid to what the GPU holds at
-// once, so a wave lives for the whole launch and the table copy is paid once.
 // The shared random permutation pi of 0..n-1 (Section 3.3 "Correlated rounding") at one worker
 // index, from the four words of the super-group's shared draw: three rounds of
 //   y <- reverse_k(((w_t | 1) * y + (w_t >> 16)) mod 2^k),  k = ceil(log2 n)
@@ -663,6 +660,9 @@ __device__ __forceinline__ void run_range(const Job &job, const Params &P, uint3
   }
 }
 
+// The job's tiles are split evenly over all waves of the grid row (4 * gridDim.x waves):
+// wave w takes [w*T/W, (w+1)*T/W).  The launcher sizes the grid to what the GPU holds at
+// once, so a wave lives for the whole launch and the table copy is paid once.
 template <Kind KIND, typename LT>
 __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   extern __shared__ uint4 lds_raw[];
