@@ -297,14 +297,19 @@ dq_status dq_restore(const float *sum, const uint32_t *pos, const float *mu_main
  * decompress-accumulate-recompress, its transfer begins while subsequent blocks are processed).
  * One hop of one chunk, cut every block_sg super-groups; on the wire each block is a packed chunk
  * of its own (first_sg advanced, widths as they fall), the blocks back to back, each starting
- * at a multiple of 256 bytes: dq_pipelined_wire_bytes in all.  Block i is (re-)encoded on
- * compute_stream into one half of `stage` (dq_pipelined_stage_bytes, two blocks) and copied from
- * there to its place in wire_out on copy_stream -- a device-to-device copy standing in for the
- * network -- while block i+1 is being encoded.  wire_in NULL: the first hop (compress).  `local`
- * describes the whole chunk (means and indices per super-group of the whole chunk).  The two
- * streams must differ; when the call returns, compute_stream has been made to wait for the last
- * copies, so synchronising it is enough.  The events that order the two streams belong to the
- * context (made in dq_create): one pipelined call at a time per context. */
+ * at a multiple of 256 bytes: dq_pipelined_wire_bytes in all.  Block i is (re-)encoded into half
+ * i mod 2 of `stage` (dq_pipelined_stage_bytes, two blocks) and copied from there to its place in
+ * wire_out -- a device-to-device copy standing in for the network, which also writes the block's
+ * padding bytes as zero -- both on stream i mod 2 of the two streams given (compute_stream takes
+ * the even blocks, copy_stream the odd ones): the order inside a stream protects a half until it
+ * has left, and the encoding of block i+1 overlaps the transfer of block i with two runtime calls
+ * per block and no event.  wire_in NULL: the first hop (compress).  `local` describes the whole
+ * chunk (means and indices per super-group of the whole chunk).  The two streams must differ;
+ * copy_stream is first made to wait for what compute_stream holds at the call (the inputs), and
+ * when the call returns compute_stream has been made to wait for copy_stream, so synchronising
+ * compute_stream is enough.  The two events of that fork and join belong to the context (made
+ * in dq_create): one pipelined call at a time per context.  The bytes of wire_out between the
+ * blocks (up to the next multiple of 256) are not written. */
 size_t dq_pipelined_wire_bytes(const dq_chunk *chunk, uint32_t block_sg);
 size_t dq_pipelined_stage_bytes(const dq_chunk *chunk, uint32_t block_sg);
 dq_status dq_dar_hop_pipelined(dq_ctx *ctx, const void *wire_in, const dq_local *local, const dq_chunk *chunk,

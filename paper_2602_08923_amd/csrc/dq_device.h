@@ -82,7 +82,9 @@ hipError_t launch_batch(Kind kind, dq_dtype dtype, bool has_local, bool gather, 
                         hipStream_t stream);
 
 // 16 zero bytes at a 16-byte aligned device address, written by a kernel
-hipError_t clear16(void *p, hipStream_t stream);
+// dst[0..bytes) = src[0..bytes) in 16-byte words (bytes a multiple of 16), except that the bytes from `valid`
+// on are written as zero: the copy that stands in for the wire puts a packed block's padding down itself
+hipError_t wire_copy(void *dst, const void *src, size_t bytes, size_t valid, hipStream_t stream);
 
 // Largest static LDS size over the codec kernels (must be 0: they address their tables from LDS byte 0)
 hipError_t static_lds_bytes(size_t *bytes);
@@ -114,8 +116,8 @@ struct dq_ctx {
   uint32_t n_cu;
   uint32_t grid_blocks;  // n_cu x blocks per CU (6, or the DQ_BLOCKS_PER_CU environment variable at dq_create)
   int device;
-  hipEvent_t stage_filled[2], stage_free[2];  // block pipeline: created and destroyed with the context
-  bool have_event[4];                         // which of the four exist (filled 0, 1, free 0, 1)
-  bool have_events;                           // all four
+  hipEvent_t pipe_event[2];  // block pipeline: fork (0) and join (1) of its two streams; made and destroyed with the context
+  bool have_event[2];        // which of the two exist
+  bool have_events;          // both
   void *static_stage;  // this device's copy of the library's static staging array (dq_dar_hop_pipelined_static), or null
 };

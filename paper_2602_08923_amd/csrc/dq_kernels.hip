@@ -753,10 +753,23 @@ __global__ __launch_bounds__(kBlockThreads) void k_batch(const Job *jobs, Params
   run_job<KIND, LT>(job, P);
 }
 
-// 16 zero bytes at p (16-byte aligned): a fill kernel instead of a memset node, so that callers may
-// capture the launches around it in a graph
-__global__ void k_clear16(uint4 *p) {
-  if (threadIdx.x == 0) *p = uint4{0u, 0u, 0u, 0u};
+// Copy of a packed block in 16-byte words; the bytes from `valid` on (the padding at the block's end,
+// which the codec kernels never write) are put down as zero.
+__global__ void __launch_bounds__(256) k_wire_copy(const uint4 *src, uint4 *dst, uint64_t words, uint64_t valid) {
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (uint64_t)gridDim.x * 256) {
+    uint4 w = src[i];
+    if ((i + 1) * 16 > valid) {
+      uint32_t x[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint64_t at = i * 16 + 4 * k;  // first byte of this dword
+        const uint32_t keep = at >= valid ? 0u : (valid - at >= 4 ? 0xFFFFFFFFu : (1u << (8 * (uint32_t)(valid - at))) - 1u);
+        x[k] &= keep;
+      }
+      w = uint4{x[0], x[1], x[2], x[3]};
+    }
+    dst[i] = w;
+  }
 }
 
 uint32_t job_tiles(const Job &j) {
@@ -867,8 +880,13 @@ hipError_t static_lds_bytes(size_t *bytes) {
   return e;
 }
 
-hipError_t clear16(void *p, hipStream_t s) {
-  hipLaunchKernelGGL(k_clear16, dim3(1), dim3(64), 0, s, static_cast<uint4 *>(p));
+hipError_t wire_copy(void *dst, const void *src, size_t bytes, size_t valid, hipStream_t s) {
+  const uint64_t words = bytes / 16;
+  if (words == 0) return hipSuccess;
+  const uint64_t want = (words + 1023) / 1024;  // four words per thread
+  const uint32_t blocks = (uint32_t)(want < 2048 ? want : 2048);
+  hipLaunchKernelGGL(k_wire_copy, dim3(blocks), dim3(256), 0, s, static_cast<const uint4 *>(src), static_cast<uint4 *>(dst),
+                     words, (uint64_t)valid);
   return hipGetLastError();
 }
 

@@ -538,8 +538,10 @@ def test_pipelined_hops_match_blockwise_oracle(dev, block_sg):
     assert B.dq_pipelined_wire_bytes(gch, block_sg) == want.size
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     wire = None
+    # a stage full of ones: a block's padding must reach the wire as zero all the same
+    stage = torch.full((B.dq_pipelined_stage_bytes(gch, block_sg),), 0xFF, dtype=torch.uint8, device=dev)
     for hop, x in enumerate(xs):
-        wire = B.dq_dar_hop_pipelined(ctx, wire, to_dev(x, dev), gch, hop, block_sg, s1, s2)
+        wire = B.dq_dar_hop_pipelined(ctx, wire, to_dev(x, dev), gch, hop, block_sg, s1, s2, stage=stage)
         s1.synchronize()
     assert np.array_equal(host(wire), want)
     with pytest.raises(B.DqError):
