@@ -217,6 +217,48 @@ def test_ring_replay_config1_full(dev):
     assert np.array_equal(host(rp.out), want)
 
 
+@pytest.mark.parametrize("topology", ["ring", "butterfly"])
+def test_replay_captured_in_a_graph(dev, topology):
+    """A replay is kernel launches only (no memset, no copy, no event), so a caller may capture it in
+    a HIP graph.  The graph is replayed three times, with eager work of the program and
+    synchronisations between the replays (the gradients change in place); every replay must equal the
+    eager replay on the same inputs, and the first the oracle."""
+    n, n_sg, counts = 8, 64, [[20, 36, 8]]
+    rng = np.random.default_rng(31)
+    grads = [make_local(rng, n_sg * 256, "bf16") for _ in range(n)]
+    dev_grads = [to_dev(g, dev) for g in grads]
+    topo = B.DQ_RING if topology == "ring" else B.DQ_BUTTERFLY
+    orc, ctx = O.Oracle(n, seed=41), B.Context(n, seed=41)
+    reduce = O.ring_reduce_scatter if topology == "ring" else O.butterfly_reduce_scatter
+    want = np.concatenate(reduce(orc, grads, counts[0]))
+    rp = B.Replay(ctx, topo, B.DQ_DYNAMIQ, dev_grads, n_sg, counts)
+    rp.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        rp.run()                                   # warm-up on the capturing stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            rp.run()
+    torch.cuda.synchronize()
+    for k in range(3):
+        for g in dev_grads:                        # eager work between the replays
+            g.mul_(-1.25 - k)
+        torch.cuda.synchronize()
+        rp.out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = host(rp.out).copy()
+        rp.out.zero_()
+        rp.run()
+        torch.cuda.synchronize()
+        assert np.array_equal(got, host(rp.out)), f"replay {k}"
+        assert np.abs(got).max() > 0
+
+
 @pytest.mark.parametrize("n,n_sg_bucket,counts,buckets", [(2, 8, [[2, 4, 2]], 1), (4, 12, [[3, 6, 3], [0, 12, 0]], 2),
                                                           (8, 40, [[7, 22, 11]], 1)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
