@@ -298,11 +298,6 @@ def prepost_context(W, reps):
     def f_alloc():
         state["w"], state["pos"], state["counts"] = B.dq_allocate(state["F"], n_sg, budget)
 
-    ws = torch.empty(max(16, B.lib().dq_allocate_wide_workspace_bytes(n_sg, 1)), dtype=torch.uint8, device=dev)
-
-    def f_alloc_wide():
-        state["wide"] = B.dq_allocate_wide(state["F"], n_sg, budget, workspace=ws)
-
     def f_mean():
         state["mu_main"] = B.dq_reorder_mean(state["mu"], state["pos"], n_sg, state["counts"])
 
@@ -326,8 +321,6 @@ def prepost_context(W, reps):
 
     t_stats, t_comb, t_alloc, t_mean = timed(f_stats), timed(f_combine), timed(f_alloc), timed(f_mean)
     t_reo, t_res = timed(f_reorder), timed(f_restore)
-    t_alloc_wide = timed(f_alloc_wide)
-    wide_same = all(bool(torch.equal(a, b)) for a, b in zip(state["wide"], (state["w"], state["pos"], state["counts"])))
     c = state["counts"].cpu().numpy()[0]
 
     # does the allocation of bucket k+1 hide beside the replay of bucket k?  `reps` replays on the current
@@ -336,14 +329,14 @@ def prepost_context(W, reps):
     side = torch.cuda.Stream()
     t_replay = timed(W.rp.run)
 
-    def both_total(alloc):
+    def both_total():
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             for _ in range(reps):
-                alloc()
+                f_alloc()
         for _ in range(reps):
             W.rp.run()
         torch.cuda.current_stream().wait_stream(side)
@@ -351,10 +344,8 @@ def prepost_context(W, reps):
         b.synchronize()
         return a.elapsed_time(b) * 1e3 / reps
 
-    both_total(f_alloc)
-    t_both = both_total(f_alloc)
-    both_total(f_alloc_wide)
-    t_both_wide = both_total(f_alloc_wide)
+    both_total()
+    t_both = both_total()
 
     def hidden(t_a, t_b):
         return round(max(0.0, min(1.0, (t_replay + t_a - t_b) / min(t_a, t_replay))), 3)
@@ -380,17 +371,13 @@ def prepost_context(W, reps):
     rp_fused.close()
     return {
         "stats_us": round(t_stats, 1), "stats_GBps": round(n * entries * dtype_bytes / t_stats / 1e3, 1),
-        "combine_us": round(t_comb, 1), "allocate_us": round(t_alloc, 1),
-        "allocate_wide_us": round(t_alloc_wide, 1), "allocate_wide_same_bits": wide_same, "reorder_mean_us": round(t_mean, 1),
+        "combine_us": round(t_comb, 1), "allocate_us": round(t_alloc, 1), "reorder_mean_us": round(t_mean, 1),
         "reorder_us": round(t_reo, 1), "reorder_GBps": round(n * entries * 2 * dtype_bytes / t_reo / 1e3, 1),
         "restore_us": round(t_res, 1), "restore_GBps": round(entries * 8 / t_res / 1e3, 1),
         "sg_by_width_2_4_8_gpu_allocation": [int(c[0]), int(c[1]), int(c[2])],   # W = {2,4,8}: c[3] (16-bit) is 0
         "allocate_beside_replay_us": {"replay_alone": round(t_replay, 1), "allocate_alone": round(t_alloc, 1),
                                       "both_on_two_streams": round(t_both, 1),
                                       "allocation_hidden_frac": hidden(t_alloc, t_both),
-                                      "allocate_wide_alone": round(t_alloc_wide, 1),
-                                      "wide_both_on_two_streams": round(t_both_wide, 1),
-                                      "wide_allocation_hidden_frac": hidden(t_alloc_wide, t_both_wide),
                                       "note": "per round, from one fork and one join around 20 rounds on each stream"},
         "reorder_replay_restore_us": {"three_passes": round(t_three, 1), "fused_into_the_replay": round(t_fused, 1),
                                       "same_bits": same},

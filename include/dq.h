@@ -249,24 +249,10 @@ dq_status dq_stats_combine(const float *mu_all, const float *F_all, uint32_t n_w
  *   pos[j]     its index inside the reordered bucket: all 2-bit super-groups first, then the
  *              4-bit, 8-bit and 16-bit ones, each class in original order (Section 3.5)
  *   counts[5b .. 5b+4] = {#2-bit, #4-bit, #8-bit, #16-bit, bit pattern of T48} of bucket b
- * One thread block per bucket. */
+ * The search runs in one thread block per bucket; for buckets of up to 65,536 super-groups the widths
+ * and positions are written by a second launch spread over the GPU. */
 dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
                       uint32_t max_width, uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream);
-
-/* Section 3.2 + Appendix A (the threshold search the round waits for): dq_allocate for callers that
- * allocate one bucket (or a few) at a time and wait for it: the same outputs, bit for bit, with the work spread over the GPU in four launches (two histogram levels
- * over the bit patterns of F that bracket T48, one block per bucket that finishes the search,
- * one launch for widths and positions) instead of one block per bucket.  Worth it below about
- * 30 buckets per call; with more, dq_allocate already fills the GPU.  `workspace`: device
- * memory, 16-byte aligned, at least dq_allocate_wide_workspace_bytes(...) bytes (about 0.5 MB per
- * bucket); its contents do not matter before the call and are unspecified after it, and calls
- * that share a workspace must not overlap.  max_width 16, more than 65,536 super-groups per
- * bucket or more than 65,535 buckets: the call runs dq_allocate (the workspace is not used).
- * Errors as dq_allocate; DQ_EINVAL also for a missing or short workspace. */
-size_t dq_allocate_wide_workspace_bytes(uint32_t n_sg_per_bucket, uint32_t n_buckets);
-dq_status dq_allocate_wide(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
-                           uint32_t max_width, uint8_t *widths, uint32_t *pos, uint32_t *counts, void *workspace,
-                           size_t workspace_bytes, void *hip_stream);
 
 /* Section 3.5: out[super-group pos[j] of the bucket] = x[super-group j]: whole super-groups
  * copied into increasing-width order.  out must not overlap x.  At most 2^24 super-groups per

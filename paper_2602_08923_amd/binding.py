@@ -24,7 +24,7 @@ EXPORTS = [
     "dq_replay_scratch_bytes", "dq_replay_create", "dq_replay_n_steps", "dq_replay_run", "dq_replay_run_steps",
     "dq_replay_step_info", "dq_replay_message", "dq_replay_run_launch", "dq_stream_probe",
     "dq_replay_destroy", "dq_status_str", "dq_last_hip_error",
-    "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_allocate_wide", "dq_allocate_wide_workspace_bytes", "dq_reorder", "dq_reorder_mean", "dq_restore",
+    "dq_sg_stats", "dq_stats_combine", "dq_allocate", "dq_reorder", "dq_reorder_mean", "dq_restore",
     "dq_pipelined_wire_bytes", "dq_pipelined_stage_bytes", "dq_dar_hop_pipelined", "dq_dar_hop_pipelined_static",
 ]
 DQ_STATIC_STAGE_BYTES = 8 << 20
@@ -101,9 +101,6 @@ def lib():
         L.dq_sg_stats.argtypes = [vp, i, u64, vp, vp, vp]
         L.dq_stats_combine.argtypes = [vp, vp, u32, u64, vp, vp, vp]
         L.dq_allocate.argtypes = [vp, u32, u32, u64, u32, vp, vp, vp, vp]
-        L.dq_allocate_wide.argtypes = [vp, u32, u32, u64, u32, vp, vp, vp, vp, C.c_size_t, vp]
-        L.dq_allocate_wide_workspace_bytes.argtypes = [u32, u32]
-        L.dq_allocate_wide_workspace_bytes.restype = C.c_size_t
         L.dq_reorder.argtypes = [vp, i, vp, u32, u32, vp, vp]
         L.dq_reorder_mean.argtypes = [vp, vp, vp, u32, u32, vp, vp, vp]
         L.dq_restore.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp]
@@ -403,23 +400,6 @@ def dq_allocate(F, n_sg_per_bucket, max_code_bits, max_width=8):
     counts = torch.empty((nb, 5), dtype=torch.int32, device=F.device)
     _check(lib().dq_allocate(_ptr(F), n_sg_per_bucket, nb, int(max_code_bits), int(max_width), _ptr(widths), _ptr(pos),
                              _ptr(counts), _stream()))
-    return widths, pos, counts
-
-
-def dq_allocate_wide(F, n_sg_per_bucket, max_code_bits, max_width=8, workspace=None):
-    """dq_allocate's outputs from the launches spread over the GPU; `workspace` (uint8, device) is
-    made here when not given."""
-    if F.dtype != torch.float32 or F.numel() % n_sg_per_bucket:
-        raise DqError("F is float32 with a whole number of buckets")
-    nb = F.numel() // n_sg_per_bucket
-    need = lib().dq_allocate_wide_workspace_bytes(n_sg_per_bucket, nb)
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=F.device)
-    widths = torch.empty(F.numel(), dtype=torch.uint8, device=F.device)
-    pos = torch.empty(F.numel(), dtype=torch.int32, device=F.device)
-    counts = torch.empty((nb, 5), dtype=torch.int32, device=F.device)
-    _check(lib().dq_allocate_wide(_ptr(F), n_sg_per_bucket, nb, int(max_code_bits), int(max_width), _ptr(widths),
-                                  _ptr(pos), _ptr(counts), _ptr(workspace), workspace.numel(), _stream()))
     return widths, pos, counts
 
 

@@ -128,233 +128,24 @@ __device__ __forceinline__ int32_t p16_from(uint32_t pattern, bool allow16) {
   return allow16 ? (int32_t)f2u(u2f(pattern) * (131072.0f / 257.0f)) : kNever;
 }
 
-// ---- the same search spread over the GPU (dq_allocate_wide).  The threshold T_{4,8} is bracketed by
-// histograms that many blocks build together: a level takes the bracket (lo, hi) -- lo does not
-// fit or is 0, hi fits -- and counts, in kNB bins each, the patterns that can still change the
-// number at or above T_{4,8} (those strictly inside (lo, hi)) and the number at or above T_{2,4}
-// (those in [p4(lo), p4(hi))).  On a bin boundary t the first number is exact and the second lies
-// between two suffix counts, which gives a cost that surely fits and one that surely does not:
-// the next, tighter bracket.  Two levels bring a bracket of 2^31 patterns down to about 2^9; one
-// block then finishes the bisection over the few patterns left, and a last launch writes the
-// positions.  Every block of a level writes its own counts and the next launch adds them up: no
-// atomics on global memory, nothing to clear, the same result whatever the grid.
-constexpr uint32_t kNB = 2048;                 // bins per level and threshold
-constexpr uint32_t kPartWords = 2 * kNB + 2;   // a block's record: 8-bit bins, 4-bit bins, counts at or above hi and p4(hi)
-constexpr int kLevelThreads = 1024;
-constexpr uint32_t kMaxLevelBlocks = 8;        // blocks per bucket and level: that many records are added up per bin
-constexpr uint32_t kInfPattern = 0x7F800000u;
-
-struct Ranges {
-  uint32_t lo, hi, lo4, hi4;  // patterns; bins: (v - lo) >> s8 for lo < v < hi, (v - lo4) >> s4 for lo4 <= v < hi4
-  uint32_t s8, s4;
-};
-__device__ __forceinline__ uint32_t p4_pattern(uint32_t pattern) { return f2u(u2f(pattern) * (17.0f / 512.0f)); }
-__device__ __forceinline__ uint32_t shift_for(uint32_t span) {  // smallest s with (span - 1) >> s below kNB
-  uint32_t s = 0;
-  while (((span - 1) >> s) >= kNB) ++s;
-  return s;
-}
-__device__ __forceinline__ Ranges ranges_of(uint32_t lo, uint32_t hi) {
-  Ranges r;
-  r.lo = lo; r.hi = hi; r.lo4 = p4_pattern(lo); r.hi4 = p4_pattern(hi);
-  r.s8 = hi > lo ? shift_for(hi - lo) : 0u;
-  r.s4 = r.hi4 > r.lo4 ? shift_for(r.hi4 - r.lo4) : 0u;
-  return r;
-}
-
-// h[0..kNB) bin counts in LDS -> suffix counts h[i] = members of bins i and above, h[kNB] = h[kNB+1] = 0.
-// Thread t of T owns kNB / T consecutive bins; `wsum` has T / 64 words.  Ends with a barrier.
-template <int T>
-__device__ __forceinline__ void to_suffix(uint32_t *h, uint32_t *wsum, uint32_t tid) {
-  constexpr int kPer = kNB / T;
-  const uint32_t lane = tid & 63u, wave = tid >> 6;
-  uint32_t v[kPer], sum = 0;
-#pragma unroll
-  for (int k = 0; k < kPer; ++k) {
-    v[k] = h[tid * kPer + k];
-    sum += v[k];
-  }
-  uint32_t inc = sum;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t up = __shfl_up(inc, d, 64);
-    if (lane >= (uint32_t)d) inc += up;
-  }
-  if (lane == 63) wsum[wave] = inc;
-  __syncthreads();
-  uint32_t before = 0, all = 0;
-#pragma unroll
-  for (int w = 0; w < T / 64; ++w) {
-    const uint32_t t = wsum[w];
-    before += (uint32_t)w < wave ? t : 0u;
-    all += t;
-  }
-  uint32_t s = all - (before + inc - sum);  // members of this thread's first bin and above
-#pragma unroll
-  for (int k = 0; k < kPer; ++k) {
-    h[tid * kPer + k] = s;
-    s -= v[k];
-  }
-  if (tid == 0) h[kNB] = h[kNB + 1] = 0;
-  __syncthreads();
-}
-
-// A level's records (G blocks of kPartWords words) added up into LDS: h8, h4 (kNB + 2 words each) and
-// base[0..1] = patterns at or above hi and p4(hi); then suffix counts, then the tighter bracket.
-// `ext`: two more LDS words.  Every thread of the block returns the same (lo, hi).
-template <int T>
-__device__ __forceinline__ void next_bracket(const uint32_t *part, uint32_t G, const Ranges &R, uint32_t J,
-                                             uint64_t max_code_bits, uint32_t *h8, uint32_t *h4, uint32_t *base,
-                                             uint32_t *wsum, uint32_t *ext, uint32_t tid, uint32_t &lo, uint32_t &hi) {
-  // five rounds of loads (40 per thread) are requested before the first is used: the sum is
-  // bound by latency, not by the 0.13 MB it reads
-  constexpr uint32_t kRounds = (kPartWords + T - 1) / T, kAhead = 5;
-#pragma unroll
-  for (uint32_t r0 = 0; r0 < kRounds; r0 += kAhead) {
-    uint32_t v[kAhead][kMaxLevelBlocks];
-#pragma unroll
-    for (uint32_t r = 0; r < kAhead; ++r) {
-      const uint32_t i = min((r0 + r) * T + tid, kPartWords - 1);
-#pragma unroll
-      for (uint32_t g = 0; g < kMaxLevelBlocks; ++g) v[r][g] = gld<uint32_t>(part + (uint64_t)min(g, G - 1) * kPartWords + i);
-    }
-#pragma unroll
-    for (uint32_t r = 0; r < kAhead; ++r) {
-      const uint32_t i = (r0 + r) * T + tid;
-      uint32_t s = 0;
-#pragma unroll
-      for (uint32_t g = 0; g < kMaxLevelBlocks; ++g) s += g < G ? v[r][g] : 0u;
-      if (i < kNB) h8[i] = s;
-      else if (i < 2 * kNB) h4[i - kNB] = s;
-      else if (i < kPartWords) base[i - 2 * kNB] = s;
-    }
-  }
-  __syncthreads();
-  to_suffix<T>(h8, wsum, tid);
-  to_suffix<T>(h4, wsum, tid);
-  lo = R.lo;
-  hi = R.hi;
-  if (R.hi - R.lo <= 1) return;
-  const uint32_t base8 = base[0], base4 = base[1];
-  // thresholds on bin boundaries inside the bracket: t_i = lo + (i << s8), i = 1..m
-  const uint32_t m = (R.hi - R.lo - 1) >> R.s8;
-  auto cost_bounds = [&](uint32_t i, uint64_t &c_min, uint64_t &c_max) {
-    const uint64_t fixed = 2ull * J + 4ull * (base8 + h8[i]);
-    const uint32_t q = p4_pattern(R.lo + (i << R.s8));  // not below lo4: the product is monotone
-    uint32_t a_min = 0, a_max = 0;
-    if (q < R.hi4) {
-      const uint32_t i4 = (q - R.lo4) >> R.s4;
-      a_min = h4[i4 + 1];
-      a_max = h4[i4];
-    }
-    c_min = fixed + 2ull * (base4 + a_min);
-    c_max = fixed + 2ull * (base4 + a_max);
-  };
-  // every boundary is tried at once (a bisection would be twenty dependent LDS round trips): the
-  // smallest that surely fits and the largest that surely does not; index 0 stands for lo, m + 1 for hi
-  if (tid == 0) {
-    ext[0] = m + 1;
-    ext[1] = 0;
-  }
-  __syncthreads();
-  uint32_t fit = m + 1, no = 0;
-  for (uint32_t i = tid + 1; i <= m; i += T) {
-    uint64_t c_min, c_max;
-    cost_bounds(i, c_min, c_max);
-    if (c_max <= max_code_bits) fit = min(fit, i);
-    if (c_min > max_code_bits) no = max(no, i);
-  }
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    fit = min(fit, (uint32_t)__shfl_xor(fit, d, 64));
-    no = max(no, (uint32_t)__shfl_xor(no, d, 64));
-  }
-  if ((tid & 63u) == 0) {
-    atomicMin(&ext[0], fit);
-    atomicMax(&ext[1], no);
-  }
-  __syncthreads();
-  fit = ext[0];
-  no = ext[1];
-  if (fit <= m) hi = R.lo + (fit << R.s8);
-  if (no >= 1) lo = R.lo + (no << R.s8);
-}
-
-// One level: grid (G, buckets).  FIRST counts inside the widest bracket, (0, +infinity); the
-// second level first reads the first level's records and tightens the bracket, which block 0 of
-// the bucket also leaves in ctl[0..1] for the kernel that finishes the search.
-template <bool FIRST>
-__global__ void __launch_bounds__(kLevelThreads) k_alloc_level(const float *F_all, uint32_t J, uint64_t max_code_bits,
-                                                               const uint32_t *part_in_all, uint32_t *part_out_all,
-                                                               uint32_t *ctl_all) {
-  __shared__ uint32_t h8[kNB + 2], h4[kNB + 2];
-  __shared__ uint32_t wsum[kLevelThreads / 64], base[2], red[2][kLevelThreads / 64];
-  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-  const uint32_t G = gridDim.x, bucket = blockIdx.y;
-  const float *F = F_all + (uint64_t)bucket * J;
-  Ranges R = ranges_of(0u, kInfPattern);
-  if constexpr (!FIRST) {
-    uint32_t lo, hi;
-    next_bracket<kLevelThreads>(part_in_all + (uint64_t)bucket * G * kPartWords, G, R, J, max_code_bits, h8, h4, base,
-                                wsum, &red[0][0], tid, lo, hi);
-    R = ranges_of(lo, hi);
-    if (blockIdx.x == 0 && tid == 0) {
-      gst<uint32_t>(ctl_all + 4ull * bucket, lo);
-      gst<uint32_t>(ctl_all + 4ull * bucket + 1, hi);
-    }
-    __syncthreads();  // h8 and h4 are cleared next
-  }
-  for (uint32_t i = tid; i < kNB; i += kLevelThreads) h8[i] = h4[i] = 0;
-  __syncthreads();
-  const uint32_t per = (J + G - 1) / G;
-  const uint32_t j0 = min(J, blockIdx.x * per), j1 = min(J, j0 + per);
-  uint32_t a8 = 0, a4 = 0;
-  for (uint32_t j = j0 + tid; j < j1; j += kLevelThreads) {
-    const uint32_t v = (uint32_t)pattern_of(gld<float>(F + j));
-    if (v > R.lo && v < R.hi) atomicAdd(&h8[(v - R.lo) >> R.s8], 1u);
-    if (v >= R.lo4 && v < R.hi4) atomicAdd(&h4[(v - R.lo4) >> R.s4], 1u);
-    a8 += v >= R.hi ? 1u : 0u;
-    a4 += v >= R.hi4 ? 1u : 0u;
-  }
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    a8 += __shfl_xor(a8, d, 64);
-    a4 += __shfl_xor(a4, d, 64);
-  }
-  if (lane == 0) {
-    red[0][wave] = a8;
-    red[1][wave] = a4;
-  }
-  __syncthreads();
-  uint32_t *out = part_out_all + ((uint64_t)bucket * G + blockIdx.x) * kPartWords;
-  for (uint32_t i = tid; i < kNB; i += kLevelThreads) {
-    gst<uint32_t>(out + i, h8[i]);
-    gst<uint32_t>(out + kNB + i, h4[i]);
-  }
-  if (tid < 2) {
-    uint32_t s = 0;
-#pragma unroll
-    for (int w = 0; w < kLevelThreads / 64; ++w) s += red[tid][w];
-    gst<uint32_t>(out + 2 * kNB + tid, s);
-  }
-}
-
 // Widths and positions once the threshold is known (counts[5b..5b+4] as the search left them):
 // grid (ceil(J / 1024), buckets).  A block first counts the members of each class among the
-// super-groups before its own 1024 (at most 64 rounds for the sizes this path takes), then ranks
+// super-groups before its own 1024 (at most 64 rows for the sizes this path takes), then ranks
 // its own: position = first place of the class + members before the block + members in earlier
 // waves + members in lower lanes.
-__global__ void __launch_bounds__(kAllocThreads) k_alloc_positions(const float *F_all, uint32_t J, const uint32_t *counts_all,
-                                                                   uint8_t *widths_all, uint32_t *pos_all) {
-  __shared__ uint32_t before[kAllocWaves][3], mine_w[kAllocWaves][3];
+__global__ void __launch_bounds__(kAllocThreads) k_alloc_positions(const float *F_all, uint32_t J, bool allow16,
+                                                                   const uint32_t *counts_all, uint8_t *widths_all,
+                                                                   uint32_t *pos_all) {
+  __shared__ uint32_t before[kAllocWaves][4], mine_w[kAllocWaves][4];
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   const uint64_t first = (uint64_t)blockIdx.y * J;
   const float *F = F_all + first;
   const uint32_t *cnt = counts_all + 5ull * blockIdx.y;
-  const int32_t p8 = (int32_t)gld<uint32_t>(cnt + 4), p4 = p4_from((uint32_t)p8);
-  const uint32_t n0 = gld<uint32_t>(cnt), n1 = gld<uint32_t>(cnt + 1);
-  const uint32_t start[3] = {0u, n0, n0 + n1};
-  uint32_t c[3] = {0u, 0u, 0u};
+  const uint32_t pattern = gld<uint32_t>(cnt + 4);
+  const int32_t p8 = (int32_t)pattern, p4 = p4_from(pattern), p16 = p16_from(pattern, allow16);
+  const uint32_t n0 = gld<uint32_t>(cnt), n1 = gld<uint32_t>(cnt + 1), n2 = gld<uint32_t>(cnt + 2);
+  const uint32_t start[4] = {0u, n0, n0 + n1, n0 + n1 + n2};
+  uint32_t c[4] = {0u, 0u, 0u, 0u};
   constexpr uint32_t kAhead = 32;  // rows of 1024 before this block, that many loads in flight
   for (uint32_t r0 = 0; r0 < blockIdx.x; r0 += kAhead) {
     float f[kAhead];
@@ -362,47 +153,46 @@ __global__ void __launch_bounds__(kAllocThreads) k_alloc_positions(const float *
     for (uint32_t r = 0; r < kAhead; ++r) f[r] = gld<float>(F + min(r0 + r, blockIdx.x - 1) * kAllocThreads + tid);
 #pragma unroll
     for (uint32_t r = 0; r < kAhead; ++r) {
-      const uint32_t k = r0 + r < blockIdx.x ? class_of(pattern_of(f[r]), p4, p8, kNever) : 4u;
-      c[0] += k == 0 ? 1u : 0u;
-      c[1] += k == 1 ? 1u : 0u;
-      c[2] += k == 2 ? 1u : 0u;
+      const uint32_t k = r0 + r < blockIdx.x ? class_of(pattern_of(f[r]), p4, p8, p16) : 4u;
+#pragma unroll
+      for (uint32_t i = 0; i < 4; ++i) c[i] += k == i ? 1u : 0u;
     }
   }
   const uint32_t j = blockIdx.x * kAllocThreads + tid;
-  const uint32_t k = j < J ? class_of(pattern_of(gld<float>(F + j)), p4, p8, kNever) : 4u;
-  const uint64_t b0 = __ballot(k == 0), b1 = __ballot(k == 1), b2 = __ballot(k == 2);
+  const uint32_t k = j < J ? class_of(pattern_of(gld<float>(F + j)), p4, p8, p16) : 4u;
+  const uint64_t b[4] = {__ballot(k == 0), __ballot(k == 1), __ballot(k == 2), __ballot(k == 3)};
 #pragma unroll
-  for (int i = 0; i < 3; ++i) {
+  for (int i = 0; i < 4; ++i) {
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) c[i] += __shfl_xor(c[i], d, 64);
   }
   if (lane == 0) {
 #pragma unroll
-    for (int i = 0; i < 3; ++i) before[wave][i] = c[i];
-    mine_w[wave][0] = (uint32_t)__builtin_popcountll(b0);
-    mine_w[wave][1] = (uint32_t)__builtin_popcountll(b1);
-    mine_w[wave][2] = (uint32_t)__builtin_popcountll(b2);
+    for (int i = 0; i < 4; ++i) {
+      before[wave][i] = c[i];
+      mine_w[wave][i] = (uint32_t)__builtin_popcountll(b[i]);
+    }
   }
   __syncthreads();
-  if (k < 3) {
+  if (k < 4) {
     uint32_t at = start[k];
 #pragma unroll
     for (int w = 0; w < kAllocWaves; ++w) at += before[w][k] + ((uint32_t)w < wave ? mine_w[w][k] : 0u);
-    const uint64_t mine = k == 0 ? b0 : (k == 1 ? b1 : b2);
+    const uint64_t mine = k == 0 ? b[0] : (k == 1 ? b[1] : (k == 2 ? b[2] : b[3]));
     at += __builtin_amdgcn_mbcnt_hi((uint32_t)(mine >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mine, 0u));
     gst<uint8_t>(widths_all + first + j, (uint8_t)(2u << k));
     gst<uint32_t>(pos_all + first + j, at);
   }
 }
 
-// WIDE: the bracket comes from the two histogram levels (their second level's records and
-// ctl[0..1]), the kernel ends once counts[5b..5b+4] are written, positions are another launch.
-template <bool IN_REGS, bool WIDE = false>
+// IN_REGS (buckets of at most 65,536 super-groups): the kernel ends once counts[5b..5b+4] are
+// written, widths and positions are another launch (k_alloc_positions, spread over the GPU: ranking
+// 64 rows in this one block took longer than the whole search and spilled registers); larger
+// buckets do them here, 64 rows of 1024 at a time, reading the norms again.
+template <bool IN_REGS>
 __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, uint32_t J, uint64_t max_code_bits,
                                                             bool allow16, uint8_t *widths_all, uint32_t *pos_all,
-                                                            uint32_t *counts_all, const uint32_t *part_all = nullptr,
-                                                            uint32_t n_part = 0, const uint32_t *ctl_all = nullptr) {
-  static_assert(!WIDE || IN_REGS, "the wide search keeps the bucket in registers");
+                                                            uint32_t *counts_all) {
   __shared__ uint32_t red[2][3][kAllocWaves];
   __shared__ uint32_t tot[kRegs * kAllocWaves][4];  // per (row, wave): class counts, then their exclusive scan
   __shared__ uint32_t wsum[kAllocWaves][4];
@@ -499,17 +289,6 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
   uint32_t base4 = 0, base8 = 0;
   if constexpr (IN_REGS) {
   if (!allow16) {  // with a third threshold in play everything is counted every round
-    uint32_t b_fit = 0;
-    if constexpr (WIDE) {
-      // the 4-bit bins share the memory of `tot`, which only the positions use
-      uint32_t *h4 = &tot[0][0];
-      static_assert(sizeof(tot) >= (kNB + 2) * sizeof(uint32_t) && kBins == kNB, "bins of the wide search");
-      const uint32_t *ctl = ctl_all + 4ull * blockIdx.x;
-      const Ranges R = ranges_of(gld<uint32_t>(ctl), gld<uint32_t>(ctl + 1));
-      next_bracket<kAllocThreads>(part_all + (uint64_t)blockIdx.x * n_part * kPartWords, n_part, R, J, max_code_bits, hist,
-                                  h4, ncand, &wsum[0][0], &red[0][0][0], tid, lo, hi);
-      __syncthreads();  // ncand (the two base counts) is cleared below
-    } else {
     // (1) Histogram of the patterns' top 11 bits (bin b = patterns [b << 20, (b+1) << 20);
     //     2040 << 20 is +infinity), turned into suffix counts S[b] = #{v : bin(v) >= b}.
     for (uint32_t b = tid; b < kBins + 2; b += kAllocThreads) hist[b] = 0;
@@ -551,8 +330,7 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
       c_min = fixed + 2ull * hist[bin4 + 1];
       c_max = fixed + 2ull * hist[bin4];
     };
-    uint32_t b_no = 0;
-    b_fit = kBins - 8;  // 2040: +infinity, everything at 2 bits
+    uint32_t b_no = 0, b_fit = kBins - 8;  // 2040: +infinity, everything at 2 bits
     while (b_fit - b_no > 1) {             // smallest bin boundary that surely fits
       const uint32_t mid = b_no + (b_fit - b_no) / 2;
       uint64_t c_min, c_max;
@@ -569,33 +347,17 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
     }
     lo = b_no << 20;
     hi = b_fit << 20;
-    }
     // (3) Only patterns strictly inside (lo, hi) can change c8 while the threshold moves in
     //     (lo, hi], and only patterns in [p4(lo), p4(hi)) can change c4: collect them in LDS.
     const int32_t lo8 = (int32_t)lo, hi8 = (int32_t)hi, lo4 = (int32_t)p4_of(lo), hi4 = (int32_t)p4_of(hi);
     if (tid < 2) ncand[tid] = 0;
     __syncthreads();
-    uint32_t always4 = 0, always8 = 0;
+    uint32_t always4 = 0;
 #pragma unroll
     for (int k = 0; k < kRegs; ++k) {
       const int32_t v = fr[k];
       const bool in8 = v > lo8 && v < hi8, in4 = v >= lo4 && v < hi4;
       always4 += v >= hi4 ? 1u : 0u;
-      if constexpr (WIDE) always8 += v >= hi8 ? 1u : 0u;
-      if constexpr (WIDE) {
-        // after two histogram levels a candidate is rare: one LDS atomic each, no wave-wide work
-        // (a count already past the capacity is not raised further: the search then counts everything)
-        const volatile uint32_t *seen = ncand;
-        if (in8 && seen[0] <= kCap) {
-          const uint32_t at = atomicAdd(&ncand[0], 1u);
-          if (at < kCap) cand[0][at] = v;
-        }
-        if (in4 && seen[1] <= kCap) {
-          const uint32_t at = atomicAdd(&ncand[1], 1u);
-          if (at < kCap) cand[1][at] = v;
-        }
-        continue;
-      }
       const uint64_t m8 = __ballot(in8), m4 = __ballot(in4);
       if (m8) {
         uint32_t at = 0;
@@ -611,22 +373,13 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
       }
     }
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      always4 += __shfl_xor(always4, d, 64);
-      if constexpr (WIDE) always8 += __shfl_xor(always8, d, 64);
-    }
-    if (lane == 0) {
-      red[0][0][wave] = always4;
-      if constexpr (WIDE) red[0][1][wave] = always8;
-    }
+    for (int d = 1; d < 64; d <<= 1) always4 += __shfl_xor(always4, d, 64);
+    if (lane == 0) red[0][0][wave] = always4;
     __syncthreads();
     const uint32_t n8 = ncand[0], n4 = ncand[1];
-    if constexpr (!WIDE) base8 = hist[b_fit];  // patterns at or above hi: exact, hi is a bin boundary
+    base8 = hist[b_fit];  // patterns at or above hi: exact, hi is a bin boundary
 #pragma unroll
-    for (int w = 0; w < kAllocWaves; ++w) {
-      base4 += red[0][0][w];
-      if constexpr (WIDE) base8 += red[0][1][w];
-    }
+    for (int w = 0; w < kAllocWaves; ++w) base4 += red[0][0][w];
     narrowed = n8 <= kCap && n4 <= kCap;  // otherwise (masses of equal values) count everything again
     __syncthreads();                      // red is reused below
     if (narrowed) {
@@ -669,7 +422,7 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
   block_counts(hi, s4, s8, s16);
   const int32_t p8 = (int32_t)hi, p4 = p4_from(hi), p16 = p16_from(hi, allow16);
   const uint32_t n_class[4] = {J - s4, s4 - s8, s8 - s16, s16};
-  if constexpr (WIDE) {
+  if constexpr (IN_REGS) {
     if (tid == 0) {
       uint32_t *cnt = counts_all + 5ull * blockIdx.x;
       gst<uint32_t>(cnt, n_class[0]);
@@ -683,39 +436,24 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
   // first position of each class in the reordered bucket, advanced chunk by chunk
   uint32_t next[4] = {0, n_class[0], n_class[0] + n_class[1], n_class[0] + n_class[1] + n_class[2]};
 
-  // Positions of the stable reorder, 64 rows of 1024 super-groups at a time: the rank of a
-  // super-group inside its class is (members in earlier rows and waves) + (members in lower lanes).
+  // Positions of the stable reorder (buckets too large for registers), 64 rows of 1024 super-groups
+  // at a time, the norms read again: the rank of a super-group inside its class is (members in
+  // earlier rows and waves) + (members in lower lanes).
   for (uint32_t r0 = 0; r0 < rows; r0 += kRegs) {
     const uint32_t nr = min((uint32_t)kRegs, rows - r0);
-    auto slot = [&](uint32_t k) -> int32_t {  // buckets too large for registers: read again
+    auto slot = [&](uint32_t k) -> int32_t {
       const uint32_t j = (r0 + k) * kAllocThreads + tid;
       return j < J ? pattern_of(gld<float>(F + j)) : -1;
     };
     // pass 1: class counts of every (row, wave)
-    if constexpr (IN_REGS) {
-#pragma unroll
-      for (int k = 0; k < kRegs; ++k) {
-        if ((uint32_t)k < nr) {
-          const uint32_t c = class_of(fr[k], p4, p8, p16);
-          const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2), b3 = __ballot(c == 3);
-          if (lane == 0) {
-            tot[k * kAllocWaves + wave][0] = (uint32_t)__builtin_popcountll(b0);
-            tot[k * kAllocWaves + wave][1] = (uint32_t)__builtin_popcountll(b1);
-            tot[k * kAllocWaves + wave][2] = (uint32_t)__builtin_popcountll(b2);
-            tot[k * kAllocWaves + wave][3] = (uint32_t)__builtin_popcountll(b3);
-          }
-        }
-      }
-    } else {
-      for (uint32_t k = 0; k < nr; ++k) {
-        const uint32_t c = class_of(slot(k), p4, p8, p16);
-        const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2), b3 = __ballot(c == 3);
-        if (lane == 0) {
-          tot[k * kAllocWaves + wave][0] = (uint32_t)__builtin_popcountll(b0);
-          tot[k * kAllocWaves + wave][1] = (uint32_t)__builtin_popcountll(b1);
-          tot[k * kAllocWaves + wave][2] = (uint32_t)__builtin_popcountll(b2);
-          tot[k * kAllocWaves + wave][3] = (uint32_t)__builtin_popcountll(b3);
-        }
+    for (uint32_t k = 0; k < nr; ++k) {
+      const uint32_t c = class_of(slot(k), p4, p8, p16);
+      const uint64_t b0 = __ballot(c == 0), b1 = __ballot(c == 1), b2 = __ballot(c == 2), b3 = __ballot(c == 3);
+      if (lane == 0) {
+        tot[k * kAllocWaves + wave][0] = (uint32_t)__builtin_popcountll(b0);
+        tot[k * kAllocWaves + wave][1] = (uint32_t)__builtin_popcountll(b1);
+        tot[k * kAllocWaves + wave][2] = (uint32_t)__builtin_popcountll(b2);
+        tot[k * kAllocWaves + wave][3] = (uint32_t)__builtin_popcountll(b3);
       }
     }
     __syncthreads();
@@ -759,13 +497,7 @@ __global__ void __launch_bounds__(kAllocThreads) k_allocate(const float *F_all, 
         gst<uint32_t>(pos + j, tot[k * kAllocWaves + wave][c] + rank);
       }
     };
-    if constexpr (IN_REGS) {
-#pragma unroll
-      for (int k = 0; k < kRegs; ++k)
-        if ((uint32_t)k < nr) emit(k, fr[k]);
-    } else {
-      for (uint32_t k = 0; k < nr; ++k) emit(k, slot(k));
-    }
+    for (uint32_t k = 0; k < nr; ++k) emit(k, slot(k));
 #pragma unroll
     for (int c = 0; c < 4; ++c) next[c] += chunk_total[c];
     __syncthreads();  // tot and wsum are reused by the next chunk
@@ -901,6 +633,17 @@ dq_status dq_stats_combine(const float *mu_all, const float *F_all, uint32_t n_w
   return launched();
 }
 
+// k_alloc_positions over all buckets, 65,535 (the grid's second dimension) per launch
+static void launch_positions(const float *F, uint32_t J, uint32_t n_buckets, bool allow16, const uint32_t *counts,
+                             uint8_t *widths, uint32_t *pos, hipStream_t s) {
+  for (uint32_t b0 = 0; b0 < n_buckets; b0 += 65535u) {
+    const uint32_t nb = n_buckets - b0 < 65535u ? n_buckets - b0 : 65535u;
+    const uint64_t off = (uint64_t)b0 * J;
+    hipLaunchKernelGGL(k_alloc_positions, dim3((J + kAllocThreads - 1) / kAllocThreads, nb), dim3(kAllocThreads), 0, s,
+                       F + off, J, allow16, counts + 5ull * b0, widths + off, pos + off);
+  }
+}
+
 dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
                       uint32_t max_width, uint8_t *widths, uint32_t *pos, uint32_t *counts, void *hip_stream) {
   if (n_sg_per_bucket == 0 || n_buckets == 0) return DQ_OK;
@@ -908,53 +651,14 @@ dq_status dq_allocate(const float *F, uint32_t n_sg_per_bucket, uint32_t n_bucke
   if (max_code_bits < 2ull * n_sg_per_bucket) return DQ_EINVAL;  // fewer than 2 code bits per coordinate
   if (!aligned(F, 4) || !aligned(pos, 4) || !aligned(counts, 4)) return DQ_EALIGN;
   hipStream_t s = (hipStream_t)hip_stream;
-  if (n_sg_per_bucket <= (uint32_t)kRegs * kAllocThreads)
+  if (n_sg_per_bucket <= (uint32_t)kRegs * kAllocThreads) {
+    // the search in one block per bucket, the norms in registers; widths and positions on a grid
     hipLaunchKernelGGL(k_allocate<true>, dim3(n_buckets), dim3(kAllocThreads), 0, s, F, n_sg_per_bucket, max_code_bits,
                        max_width == 16, widths, pos, counts);
-  else
+    launch_positions(F, n_sg_per_bucket, n_buckets, max_width == 16, counts, widths, pos, s);
+  } else
     hipLaunchKernelGGL(k_allocate<false>, dim3(n_buckets), dim3(kAllocThreads), 0, s, F, n_sg_per_bucket, max_code_bits,
                        max_width == 16, widths, pos, counts);
-  return launched();
-}
-
-// Blocks per bucket of the two histogram levels: one per 4096 super-groups, at most 8 (the next
-// launch adds up that many records per block).
-static uint32_t wide_blocks(uint32_t n_sg_per_bucket) {
-  const uint32_t g = (n_sg_per_bucket + 4095u) / 4096u;
-  return g < 1 ? 1 : (g > kMaxLevelBlocks ? kMaxLevelBlocks : g);
-}
-static bool wide_applies(uint32_t n_sg_per_bucket, uint32_t n_buckets, uint32_t max_width) {
-  return max_width == 8 && n_sg_per_bucket <= (uint32_t)kRegs * kAllocThreads && n_buckets <= 65535u;
-}
-
-size_t dq_allocate_wide_workspace_bytes(uint32_t n_sg_per_bucket, uint32_t n_buckets) {
-  const size_t words = 2 * (size_t)wide_blocks(n_sg_per_bucket) * kPartWords + 4;  // two levels' records, the bracket
-  return (size_t)n_buckets * words * sizeof(uint32_t);
-}
-
-dq_status dq_allocate_wide(const float *F, uint32_t n_sg_per_bucket, uint32_t n_buckets, uint64_t max_code_bits,
-                           uint32_t max_width, uint8_t *widths, uint32_t *pos, uint32_t *counts, void *workspace,
-                           size_t workspace_bytes, void *hip_stream) {
-  if (n_sg_per_bucket == 0 || n_buckets == 0) return DQ_OK;
-  if (!wide_applies(n_sg_per_bucket, n_buckets, max_width))
-    return dq_allocate(F, n_sg_per_bucket, n_buckets, max_code_bits, max_width, widths, pos, counts, hip_stream);
-  if (!F || !widths || !pos || !counts || !workspace) return DQ_EINVAL;
-  if (max_code_bits < 2ull * n_sg_per_bucket) return DQ_EINVAL;
-  if (workspace_bytes < dq_allocate_wide_workspace_bytes(n_sg_per_bucket, n_buckets)) return DQ_EINVAL;
-  if (!aligned(F, 4) || !aligned(pos, 4) || !aligned(counts, 4) || !aligned(workspace, 16)) return DQ_EALIGN;
-  hipStream_t s = (hipStream_t)hip_stream;
-  const uint32_t G = wide_blocks(n_sg_per_bucket);
-  uint32_t *part1 = static_cast<uint32_t *>(workspace);
-  uint32_t *part2 = part1 + (size_t)n_buckets * G * kPartWords;
-  uint32_t *ctl = part2 + (size_t)n_buckets * G * kPartWords;
-  hipLaunchKernelGGL(k_alloc_level<true>, dim3(G, n_buckets), dim3(kLevelThreads), 0, s, F, n_sg_per_bucket, max_code_bits,
-                     (const uint32_t *)nullptr, part1, ctl);
-  hipLaunchKernelGGL(k_alloc_level<false>, dim3(G, n_buckets), dim3(kLevelThreads), 0, s, F, n_sg_per_bucket, max_code_bits,
-                     (const uint32_t *)part1, part2, ctl);
-  hipLaunchKernelGGL((k_allocate<true, true>), dim3(n_buckets), dim3(kAllocThreads), 0, s, F, n_sg_per_bucket, max_code_bits,
-                     false, widths, pos, counts, (const uint32_t *)part2, G, (const uint32_t *)ctl);
-  hipLaunchKernelGGL(k_alloc_positions, dim3((n_sg_per_bucket + kAllocThreads - 1) / kAllocThreads, n_buckets),
-                     dim3(kAllocThreads), 0, s, F, n_sg_per_bucket, (const uint32_t *)counts, widths, pos);
   return launched();
 }
 

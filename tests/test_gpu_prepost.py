@@ -92,19 +92,15 @@ def test_stats_combine(dev):
 
 # ---------------------------------------------------------------- allocation
 def check_allocate(dev, F, J, budget, max_width=8):
-    """Both entry points (one block per bucket; the search spread over the GPU) against the oracle."""
     nb = F.size // J
-    want = []
+    widths, pos, counts = B.dq_allocate(torch.from_numpy(F).to(dev), J, budget, max_width=max_width)
+    widths, pos, counts = host(widths), host(pos).view(np.uint32), host(counts).view(np.uint32)
     for b in range(nb):
         w, tbits = P.allocate(F[b * J:(b + 1) * J], budget, max_width=max_width)
-        want.append((w, tbits) + P.positions(w))
-    for entry in (B.dq_allocate, B.dq_allocate_wide):
-        widths, pos, counts = entry(torch.from_numpy(F).to(dev), J, budget, max_width=max_width)
-        widths, pos, counts = host(widths), host(pos).view(np.uint32), host(counts).view(np.uint32)
-        for b, (w, tbits, p, c) in enumerate(want):
-            assert np.array_equal(widths[b * J:(b + 1) * J], w), f"{entry.__name__} bucket {b}"
-            assert np.array_equal(pos[b * J:(b + 1) * J], p), f"{entry.__name__} bucket {b}"
-            assert counts[b].tolist() == c + [tbits], f"{entry.__name__} bucket {b}"
+        p, c = P.positions(w)
+        assert np.array_equal(widths[b * J:(b + 1) * J], w), f"bucket {b}"
+        assert np.array_equal(pos[b * J:(b + 1) * J], p), f"bucket {b}"
+        assert counts[b].tolist() == c + [tbits], f"bucket {b}"
     return counts
 
 
@@ -151,10 +147,9 @@ def test_allocate_masses_of_equal_values(dev, bits):
     check_allocate(dev, np.full(J, 3.25e-7, f32), J, int(math.floor(prep.code_bits(bits) * J)))
 
 
-def test_allocate_wide_narrow_brackets_and_workspace(dev):
-    """Inputs that leave the histogram levels little or nothing to do, or everything: values one
-    pattern apart around the threshold, two distinct values, a single super-group per block of a
-    level; a dirty workspace used twice; a workspace that is too small."""
+def test_allocate_narrow_value_ranges(dev):
+    """Norms one bit pattern apart around the threshold, two distinct values tied by the threshold
+    ratio, several small buckets per call."""
     J = 20000
     base = np.float32(1.5e-3)
     pat = base.view(np.uint32) + np.arange(J, dtype=np.uint32) % 300          # 300 neighbouring patterns
@@ -164,19 +159,9 @@ def test_allocate_wide_narrow_brackets_and_workspace(dev):
     F2 = np.where(np.arange(J) % 3 == 0, np.float32(2.0), np.float32(2.0 * 17.0 / 512.0)).astype(f32)
     for bits in (2.8, 3.5, 4.0, 6.0):
         check_allocate(dev, F2, J, int(math.floor(prep.code_bits(bits) * J)))
+        check_allocate(dev, F2, J, int(math.floor(prep.code_bits(bits) * J)), max_width=16)
     F3 = lognormal_F(8, 3 * 4097)
-    check_allocate(dev, F3, 4097, int(math.floor(prep.code_bits(4.0) * 4097)))   # 3 buckets, 3 blocks per level
-    Fd = torch.from_numpy(F).to(dev)
-    need = B.lib().dq_allocate_wide_workspace_bytes(J, 1)
-    ws = torch.full((need,), 0xA5, dtype=torch.uint8, device=dev)
-    budget = int(math.floor(prep.code_bits(4.0) * J))
-    first = [host(t).copy() for t in B.dq_allocate_wide(Fd, J, budget, workspace=ws)]
-    again = [host(t) for t in B.dq_allocate_wide(Fd, J, budget, workspace=ws)]
-    ref = [host(t) for t in B.dq_allocate(Fd, J, budget)]
-    for a, b2, c in zip(first, again, ref):
-        assert np.array_equal(a, c) and np.array_equal(b2, c)
-    with pytest.raises(B.DqError):
-        B.dq_allocate_wide(Fd, J, budget, workspace=ws[:need - 16])
+    check_allocate(dev, F3, 4097, int(math.floor(prep.code_bits(4.0) * 4097)))   # 3 buckets, 5 rows each, ragged
 
 
 def test_allocate_budget_edges(dev):
