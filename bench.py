@@ -378,7 +378,7 @@ def prepost_context(W, reps):
         "allocate_beside_replay_us": {"replay_alone": round(t_replay, 1), "allocate_alone": round(t_alloc, 1),
                                       "both_on_two_streams": round(t_both, 1),
                                       "allocation_hidden_frac": hidden(t_alloc, t_both),
-                                      "note": "per round, from one fork and one join around 20 rounds on each stream"},
+                                      "note": "per repetition, from one fork and one join around 20 repetitions on each stream"},
         "reorder_replay_restore_us": {"three_passes": round(t_three, 1), "fused_into_the_replay": round(t_fused, 1),
                                       "same_bits": same},
         "note": "all workers per figure (stats and reorder: one launch per worker); GB/s = bytes read + written",
