@@ -268,7 +268,7 @@ struct Fetch {
   uint32_t rg_in, sf_in;               // DAR: incoming group scale (u8) and SG scale (bf16 pattern)
 };
 
-template <int B, Kind KIND, typename LT>
+template <int B, Kind KIND, typename LT, bool MU>
 __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePos pos) {
   const TileBase<B> tb(job, pos);
   const uint32_t lane = threadIdx.x & 63u;
@@ -289,7 +289,8 @@ __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePo
     f.rg_in = gld<uint8_t>(job.in + tb.gs_off + lg);
     f.sf_in = gld<uint16_t>(job.in + tb.sf_off + rowc * 2);
   }
-  f.mu = local_mean(job, tb.first_entry, rowc);
+  if constexpr (MU) f.mu = local_mean(job, tb.first_entry, rowc);
+  else f.mu = 0.0f;
   load_local<LT>(job, tb.first_entry, rowc, lane & 15u, f.loc);
   return f;
 }
@@ -297,7 +298,7 @@ __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePo
 // One wave tile of compress / DAR after the fetch: up to 4 super-groups of width B.
 //   stage    : LDS byte address of this tile's 8 parked draws (row r: [2r] = permutation
 //              stream, [2r+1] = group-scale stream), 16 bytes each
-template <int B, Kind KIND, typename LT>
+template <int B, Kind KIND, typename LT, bool MU>
 __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_t stage,
                                         const TilePos pos, const Fetch<B, KIND, LT> &f) {
   using W = Width<B>;
@@ -311,9 +312,31 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const uint32_t lg = rowc * 16 + g;
   constexpr uint32_t rec0 = kRec0;
 
+  // ------------------------------------------------------------------ random numbers
+  // (first: they need nothing from memory, so a wave that still waits for its tile has them done;
+  // the empty asm ties the tile's first use to them, or the scheduler would sink them below the wait)
+  const uint64_t gi = (tb.G0 + rowc) * 16 + g;  // global group index
+  // stream 0: one byte per entry, private to the worker
+  const U4 gam = philox4x32_10((uint32_t)gi, (uint32_t)(gi >> 32), P.round, job.rank & 0xFFFFu, P.key0, P.key1);
+  // parked per-SG draws: this worker's slot pi_rank of the shared permutation (group g of the
+  // super-group uses pi_rank + g mod n); byte g of the private stream -> this group's scale dither
+  const uint32_t slot0 = lds_ld1(stage + rowc * 32);
+  const uint32_t sc_word = lds_ld1(stage + rowc * 32 + 16 + (g >> 2) * 4);
+  const uint32_t scale_byte = (sc_word >> (8 * (g & 3u))) & 0xFFu;
+  uint32_t slot = slot0 + g;  // below n + 16
+  slot = (P.n_mask != 0xFFFFFFFFu) ? (slot & P.n_mask) : (slot % P.n_workers);
+  const float o_pi = ((float)slot + (1.0f / 512.0f)) * P.inv_n;
+
+  uint4 loc[sizeof(LT) == 4 ? 4 : 2];
+#pragma unroll
+  for (int i = 0; i < (sizeof(LT) == 4 ? 4 : 2); ++i) loc[i] = f.loc[i];
+  asm volatile("" : "+v"(loc[0].x) : "v"(gam.x), "v"(gam.y), "v"(gam.z), "v"(gam.w), "v"(o_pi), "v"(scale_byte));
   float v[16];
-  widen_local<LT>(f.loc, v);
-  subtract_mean(job, f.mu, v);
+  widen_local<LT>(loc, v);
+  if constexpr (MU) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = v[k] - f.mu;
+  }
 
   if constexpr (KIND == kDar) {
     // decode: sf_G = r_G * (sf_SG / 255); estimate = +-T[r] * sf_G, accumulated by one fma
@@ -337,19 +360,6 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
       }
     }
   }
-
-  // ------------------------------------------------------------------ random numbers
-  const uint64_t gi = (tb.G0 + rowc) * 16 + g;  // global group index
-  // stream 0: one byte per entry, private to the worker
-  const U4 gam = philox4x32_10((uint32_t)gi, (uint32_t)(gi >> 32), P.round, job.rank & 0xFFFFu, P.key0, P.key1);
-  // parked per-SG draws: this worker's slot pi_rank of the shared permutation (group g of the
-  // super-group uses pi_rank + g mod n); byte g of the private stream -> this group's scale dither
-  const uint32_t slot0 = lds_ld1(stage + rowc * 32);
-  const uint32_t sc_word = lds_ld1(stage + rowc * 32 + 16 + (g >> 2) * 4);
-  const uint32_t scale_byte = (sc_word >> (8 * (g & 3u))) & 0xFFu;
-  uint32_t slot = slot0 + g;  // below n + 16
-  slot = (P.n_mask != 0xFFFFFFFFu) ? (slot & P.n_mask) : (slot % P.n_workers);
-  const float o_pi = ((float)slot + (1.0f / 512.0f)) * P.inv_n;
 
   // ------------------------------------------------------------------ scales
   float m = 0.0f;
@@ -592,12 +602,12 @@ __device__ __forceinline__ void tile16(const Job &job, const Params &P, uint32_t
 // ahead, nor from touching a wave's first tiles before the block waits for its tables (one load
 // per 128-byte line, values unused: a config-2 launch got 1 us slower): the kernel is bound by
 // instruction issue, not by memory latency.
-template <int B, Kind KIND, typename LT>
+template <int B, Kind KIND, typename LT, bool MU>
 __device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint32_t stage, TilePos pos,
                                           uint32_t len) {
   for (uint32_t i = 0; i < len; ++i) {
-    const Fetch<B, KIND, LT> f = fetch<B, KIND, LT>(job, pos);
-    compute<B, KIND, LT>(job, P, stage + i * 128, pos, f);
+    const Fetch<B, KIND, LT> f = fetch<B, KIND, LT, MU>(job, pos);
+    compute<B, KIND, LT, MU>(job, P, stage + i * 128, pos, f);
     pos.tile_first += kWaveSGs;
   }
 }
@@ -649,10 +659,18 @@ __device__ __forceinline__ void run_range(const Job &job, const Params &P, uint3
     const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;  // tiles to the segment's end
     const uint32_t len = min(nb - j, left);
     const uint32_t stage = area + j * 128;
-    if (p.wi == 0) run_tiles<2, KIND, LT>(job, P, stage, p, len);
-    else if (p.wi == 1) run_tiles<4, KIND, LT>(job, P, stage, p, len);
-    else if (p.wi == 2) run_tiles<8, KIND, LT>(job, P, stage, p, len);
-    else {
+    // two builds of the tile loop, with and without means: a branch on job.mu inside a tile makes the
+    // path without means wait, at the branch's join, for the loads issued before it
+    if (job.mu) {
+      if (p.wi == 0) run_tiles<2, KIND, LT, true>(job, P, stage, p, len);
+      else if (p.wi == 1) run_tiles<4, KIND, LT, true>(job, P, stage, p, len);
+      else if (p.wi == 2) run_tiles<8, KIND, LT, true>(job, P, stage, p, len);
+    } else {
+      if (p.wi == 0) run_tiles<2, KIND, LT, false>(job, P, stage, p, len);
+      else if (p.wi == 1) run_tiles<4, KIND, LT, false>(job, P, stage, p, len);
+      else if (p.wi == 2) run_tiles<8, KIND, LT, false>(job, P, stage, p, len);
+    }
+    if (p.wi > 2) {
       TilePos q = p;
       for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<KIND, LT>(job, P, 0u, q);
     }
