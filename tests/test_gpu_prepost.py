@@ -164,6 +164,22 @@ def test_allocate_narrow_value_ranges(dev):
     check_allocate(dev, F3, 4097, int(math.floor(prep.code_bits(4.0) * 4097)))   # 3 buckets, 5 rows each, ragged
 
 
+def test_allocate_more_buckets_than_a_grid_dimension(dev):
+    """70,000 buckets of 5 super-groups: the positions launch is cut at 65,535 buckets (the grid's second
+    dimension); buckets on both sides of the cut must come out right."""
+    J, nb = 5, 70000
+    F = lognormal_F(17, J * nb)
+    budget = 4 * J + 2
+    widths, pos, counts = B.dq_allocate(torch.from_numpy(F).to(dev), J, budget)
+    widths, pos, counts = host(widths), host(pos).view(np.uint32), host(counts).view(np.uint32)
+    for b in list(range(0, nb, 997)) + [65534, 65535, 65536, nb - 1]:
+        w, tbits = P.allocate(F[b * J:(b + 1) * J], budget)
+        p, c = P.positions(w)
+        assert np.array_equal(widths[b * J:(b + 1) * J], w), f"bucket {b}"
+        assert np.array_equal(pos[b * J:(b + 1) * J], p), f"bucket {b}"
+        assert counts[b].tolist() == c + [tbits], f"bucket {b}"
+
+
 def test_allocate_budget_edges(dev):
     F = lognormal_F(5, 2000)
     c = check_allocate(dev, F, 2000, 2 * 2000)                       # exactly 2 bits each
