@@ -276,7 +276,9 @@ dq_status dq_create(const dq_config *cfg, dq_ctx **out) {
     }
   }
   ctx->n_cu = (uint32_t)prop.multiProcessorCount;
-  uint32_t per_cu = 6;
+  // five blocks of four waves per CU: measured against 4, 6 and 7 (fewer waves hide too little of each other's
+  // waits, more of them contend at the start of a short launch and pay the per-wave set-up more often)
+  uint32_t per_cu = 5;
   const char *env = getenv("DQ_BLOCKS_PER_CU");  // tuning / test knob, read once per context
   if (env && atoi(env) >= 1 && atoi(env) <= 64) per_cu = (uint32_t)atoi(env);
   ctx->grid_blocks = ctx->n_cu * per_cu;

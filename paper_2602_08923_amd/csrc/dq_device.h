@@ -114,7 +114,7 @@ struct dq_ctx {
   dq::Params params;
   uint32_t *blob_dev;
   uint32_t n_cu;
-  uint32_t grid_blocks;  // n_cu x blocks per CU (6, or the DQ_BLOCKS_PER_CU environment variable at dq_create)
+  uint32_t grid_blocks;  // n_cu x blocks per CU (5, or the DQ_BLOCKS_PER_CU environment variable at dq_create)
   int device;
   hipEvent_t pipe_event[2];  // block pipeline: fork (0) and join (1) of its two streams; made and destroyed with the context
   bool have_event[2];        // which of the two exist

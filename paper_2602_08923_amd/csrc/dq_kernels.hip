@@ -760,7 +760,8 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   }
 }
 
-// Six blocks of four waves are resident per CU (the launcher's grid): at most 80 vector registers.
+// Five blocks of four waves are resident per CU (the launcher's grid); the kernels stay within the 80 vector
+// registers that would still let six fit.
 template <Kind KIND, typename LT>
 __global__ __launch_bounds__(kBlockThreads) void k_one(Job job, Params P) {
   run_job<KIND, LT>(job, P);
