@@ -703,7 +703,8 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   const uint32_t w_lo = wv * q + min(wv, r);
   const uint32_t w_hi = w_lo + q + (wv < r ? 1u : 0u);
   // parking area for per-SG draws: 1 KB (8 tiles) per wave, the four areas contiguous
-  const uint32_t park0 = lds0 + P.blob_dwords * 4;
+  // (decompress needs no search tables: its blocks leave them out and are small enough for six per CU)
+  const uint32_t park0 = lds0 + (KIND == kDecompress ? kOffLut4 : P.blob_dwords) * 4;
   // a block with at most 32 tiles makes all its draws up front, 8 tiles per wave-wide call,
   // instead of one call per wave (waves of a small job hold only a tile or two each)
   const bool block_draws = KIND != kDecompress && (b_hi - b_lo) <= 8u * kBlockWaves;
@@ -715,7 +716,8 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   uint4 first[kEarly];
   bool need[kRanges], has[kEarly];
 #pragma unroll
-  for (int r = 0; r < kRanges; ++r) need[r] = meets[P.range_width[r] & 3u];
+  for (int r = 0; r < kRanges; ++r)
+    need[r] = meets[P.range_width[r] & 3u] && !(KIND == kDecompress && P.range_lo[r] >= kOffLut4);
 #pragma unroll
   for (int r = 0; r < kEarly; ++r) {
     const uint32_t i = P.range_lo[r] + threadIdx.x * 4;
@@ -808,7 +810,7 @@ uint32_t blocks_per_job(uint32_t max_tiles, uint32_t n_jobs, uint32_t grid_block
 
 // blob + per-wave area: 1 KB of parked draws (compress, DAR) or 4 KB for the transpose (decompress)
 size_t lds_bytes(const Params &p, Kind kind) {
-  return (size_t)p.blob_dwords * 4 + kBlockWaves * 64 * (kind == kDecompress ? 64 : 16);
+  return kind == kDecompress ? (size_t)kOffLut4 * 4 + kBlockWaves * 64 * 64 : (size_t)p.blob_dwords * 4 + kBlockWaves * 64 * 16;
 }
 
 template <Kind KIND, typename LT>
