@@ -298,9 +298,11 @@ __device__ __forceinline__ Fetch<B, KIND, LT> fetch(const Job &job, const TilePo
 // One wave tile of compress / DAR after the fetch: up to 4 super-groups of width B.
 //   stage    : LDS byte address of this tile's 8 parked draws (row r: [2r] = permutation
 //              stream, [2r+1] = group-scale stream), 16 bytes each
-template <int B, Kind KIND, typename LT, bool MU>
+//   ahead    : called once the tile's loaded data is used up, before the per-entry work: from there the
+//              next tile's loads have the longest time to arrive without holding two tiles' data at once
+template <int B, Kind KIND, typename LT, bool MU, typename Ahead>
 __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_t stage,
-                                        const TilePos pos, const Fetch<B, KIND, LT> &f) {
+                                        const TilePos pos, const Fetch<B, KIND, LT> &f, Ahead ahead) {
   using W = Width<B>;
   static_assert(KIND != kDecompress, "decompress has its own tile function");
   const TileBase<B> tb(job, pos);
@@ -376,6 +378,8 @@ __device__ __forceinline__ void compute(const Job &job, const Params &P, uint32_
   const uint32_t rg = sfb ? (uint32_t)fl + ((us < ts - fl) ? 1u : 0u) : 0u;
   // a group whose scale rounds to zero keeps only its signs; its entries are not normalised
   const float inv = rg ? 1.0f / m : 0.0f;
+
+  ahead();
 
   // ------------------------------------------------------------------ entries
   // x' = |v| * inv needs no clamp: |v| <= m and inv is the correctly rounded 1/m, so the exact
@@ -605,10 +609,20 @@ __device__ __forceinline__ void tile16(const Job &job, const Params &P, uint32_t
 template <int B, Kind KIND, typename LT, bool MU>
 __device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint32_t stage, TilePos pos,
                                           uint32_t len) {
+  // The next tile of the run is requested from inside the current one (see compute's `ahead`): with five waves
+  // per SIMD a wave's own wait for its tile is no longer covered by the others (measured: 3-7 % on the 25 MB
+  // and the 100-bucket configurations, nothing on the largest launches).
+  Fetch<B, KIND, LT> f = fetch<B, KIND, LT, MU>(job, pos);
   for (uint32_t i = 0; i < len; ++i) {
-    const Fetch<B, KIND, LT> f = fetch<B, KIND, LT, MU>(job, pos);
-    compute<B, KIND, LT, MU>(job, P, stage + i * 128, pos, f);
-    pos.tile_first += kWaveSGs;
+    Fetch<B, KIND, LT> next = f;
+    TilePos pos_next = pos;
+    pos_next.tile_first += kWaveSGs;
+    const bool more = i + 1 < len;
+    compute<B, KIND, LT, MU>(job, P, stage + i * 128, pos, f, [&] {
+      if (more) next = fetch<B, KIND, LT, MU>(job, pos_next);
+    });
+    f = next;
+    pos = pos_next;
   }
 }
 
@@ -762,8 +776,8 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   }
 }
 
-// Five blocks of four waves are resident per CU (the launcher's grid); the kernels stay within the 80 vector
-// registers that would still let six fit.
+// Five blocks of four waves are resident per CU (the launcher's grid): at most 96 vector registers (the kernels
+// with fp32 locals use 82-88 since a tile's successor is requested from inside the tile, the others at most 80).
 template <Kind KIND, typename LT>
 __global__ __launch_bounds__(kBlockThreads) void k_one(Job job, Params P) {
   run_job<KIND, LT>(job, P);
