@@ -35,7 +35,7 @@ sys.path.insert(0, ROOT)
 #            bytes on the same box: FETCH_SIZE counts half the bytes read (x2.0), WRITE_SIZE all (x1.0).
 #   valu:    vector-ALU wave instructions per DAR launch (SQ_INSTS_VALU); one is 64 lane operations.
 MEASURED = {
-    (2, 0): {"traffic": int((16261.5 * 2.0 + 6241.1 * 1.0) * 1024), "valu": 5_246_820, "profile": "profiles/dq_dar_hop_cfg2_pmc.txt"},
+    (2, 0): {"traffic": int((16261.1 * 2.0 + 6228.8 * 1.0) * 1024), "valu": 5_244_460, "profile": "profiles/dq_dar_hop_cfg2_pmc.txt"},
 }
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: lane operations per second the vector ALUs can issue
 VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
