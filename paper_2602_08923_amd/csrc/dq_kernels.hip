@@ -542,6 +542,47 @@ __device__ __forceinline__ void tile_da(const Job &job, const Params &P, uint32_
   store_tile_f32(job, P, v, xpose, tb.first_entry, tb.last_row);
 }
 
+// Decompress-accumulate over `len` consecutive tiles of width B: the tile's operands are those of a DAR
+// hop (fetch<.., kDar, ..>); the next tile is requested before the current one's transpose and stores.
+template <int B, typename LT, bool MU>
+__device__ __forceinline__ void run_tiles_da(const Job &job, const Params &P, uint32_t xpose, TilePos pos, uint32_t len) {
+  constexpr uint32_t rec0 = kRec0;
+  constexpr uint32_t dec0 = dec_addr<B>();
+  Fetch<B, kDar, LT> f = fetch<B, kDar, LT, MU>(job, pos);
+  for (uint32_t i = 0; i < len; ++i) {
+    const TileBase<B> tb(job, pos);
+    float v[16];
+    widen_local<LT>(f.loc, v);
+    if constexpr (MU) {
+#pragma unroll
+      for (int k = 0; k < 16; ++k) v[k] = v[k] - f.mu;
+    }
+    const float sfg = (float)f.rg_in * sf_over_255(f.sf_in, rec0);
+#pragma unroll
+    for (int j = 0; j < 2 * B; ++j) {  // one table entry per code byte
+      const uint32_t byte = (f.cw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+      if constexpr (B == 2) {
+        const u32x4 e = lds_ld4(dec0 + byte * 16);
+        v[4 * j] = __builtin_fmaf(u2f(e.x), sfg, v[4 * j]);
+        v[4 * j + 1] = __builtin_fmaf(u2f(e.y), sfg, v[4 * j + 1]);
+        v[4 * j + 2] = __builtin_fmaf(u2f(e.z), sfg, v[4 * j + 2]);
+        v[4 * j + 3] = __builtin_fmaf(u2f(e.w), sfg, v[4 * j + 3]);
+      } else if constexpr (B == 4) {
+        const u32x2 e = lds_ld2(dec0 + byte * 8);
+        v[2 * j] = __builtin_fmaf(u2f(e.x), sfg, v[2 * j]);
+        v[2 * j + 1] = __builtin_fmaf(u2f(e.y), sfg, v[2 * j + 1]);
+      } else {
+        v[j] = __builtin_fmaf(u2f(lds_ld1(dec0 + byte * 4)), sfg, v[j]);
+      }
+    }
+    TilePos pos_next = pos;
+    pos_next.tile_first += kWaveSGs;
+    if (i + 1 < len) f = fetch<B, kDar, LT, MU>(job, pos_next);
+    store_tile_f32(job, P, v, xpose, tb.first_entry, tb.last_row);
+    pos = pos_next;
+  }
+}
+
 // One wave tile of uncompressed (16-bit) super-groups: the packed values are raw bf16
 // ("16 bits corresponds to uncompressed values", Section 3.2).  Compress rounds the local entries
 // to bf16 (nearest even); a DAR hop adds the local entry to the widened incoming value in fp32
@@ -602,10 +643,6 @@ __device__ __forceinline__ void tile16(const Job &job, const Params &P, uint32_t
 }
 
 // `len` consecutive tiles of width B starting at `pos` (their parked draws 128 bytes apart).
-// Fetch and compute are separate steps, but measurements showed no gain from fetching a tile
-// ahead, nor from touching a wave's first tiles before the block waits for its tables (one load
-// per 128-byte line, values unused: a config-2 launch got 1 us slower): the kernel is bound by
-// instruction issue, not by memory latency.
 template <int B, Kind KIND, typename LT, bool MU>
 __device__ __forceinline__ void run_tiles(const Job &job, const Params &P, uint32_t stage, TilePos pos,
                                           uint32_t len) {
@@ -755,12 +792,34 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   if constexpr (KIND == kDecompress) {
     // per-wave transpose area: 64 lanes x 64 bytes
     const uint32_t xpose = park0 + wave * (64 * 64);
-    for (uint32_t t = w_lo; t < w_hi; ++t) {
-      const TilePos p = locate(job, t);
-      if (p.wi == 0) tile_da<2, LT>(job, P, xpose, p);
-      else if (p.wi == 1) tile_da<4, LT>(job, P, xpose, p);
-      else if (p.wi == 2) tile_da<8, LT>(job, P, xpose, p);
-      else tile16<kDecompress, LT>(job, P, xpose, p);
+    if constexpr (__is_same(LT, NoLocal)) {
+      for (uint32_t t = w_lo; t < w_hi; ++t) {
+        const TilePos p = locate(job, t);
+        if (p.wi == 0) tile_da<2, LT>(job, P, xpose, p);
+        else if (p.wi == 1) tile_da<4, LT>(job, P, xpose, p);
+        else if (p.wi == 2) tile_da<8, LT>(job, P, xpose, p);
+        else tile16<kDecompress, LT>(job, P, xpose, p);
+      }
+    } else {
+      for (uint32_t t = w_lo; t < w_hi;) {  // runs of one width, as in run_range
+        const TilePos p = locate(job, t);
+        const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;
+        const uint32_t len = min(w_hi - t, left);
+        if (job.mu) {
+          if (p.wi == 0) run_tiles_da<2, LT, true>(job, P, xpose, p, len);
+          else if (p.wi == 1) run_tiles_da<4, LT, true>(job, P, xpose, p, len);
+          else if (p.wi == 2) run_tiles_da<8, LT, true>(job, P, xpose, p, len);
+        } else {
+          if (p.wi == 0) run_tiles_da<2, LT, false>(job, P, xpose, p, len);
+          else if (p.wi == 1) run_tiles_da<4, LT, false>(job, P, xpose, p, len);
+          else if (p.wi == 2) run_tiles_da<8, LT, false>(job, P, xpose, p, len);
+        }
+        if (p.wi > 2) {
+          TilePos q = p;
+          for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<kDecompress, LT>(job, P, xpose, q);
+        }
+        t += len;
+      }
     }
   } else if (block_draws) {
     run_range<KIND, LT>(job, P, park0 + (w_lo - b_lo) * 128, w_lo, w_hi - w_lo);
