@@ -217,6 +217,47 @@ def test_ring_replay_config1_full(dev):
     assert np.array_equal(host(rp.out), want)
 
 
+def test_replay_launch_by_launch_equals_the_whole_replay(dev):
+    """dq_replay_run_launch: every launch of every step, in order, is the replay (a butterfly step in
+    which nodes forward and keep is two launches); a launch a step does not have is refused."""
+    n, n_sg, counts = 8, 48, [[10, 30, 8]]
+    rng = np.random.default_rng(77)
+    grads = [to_dev(make_local(rng, n_sg * 256, "bf16"), dev) for _ in range(n)]
+    ctx = B.Context(n, seed=9)
+    rp = B.Replay(ctx, B.DQ_BUTTERFLY, B.DQ_DYNAMIQ, grads, n_sg, counts)
+    rp.run()
+    torch.cuda.synchronize()
+    want = host(rp.out).copy()
+    rp.out.zero_()
+    kinds = [rp.step_info(t)[0] for t in range(rp.n_steps)]
+    assert 3 in kinds                                   # some step both forwards and keeps
+    for t, kind in enumerate(kinds):
+        rp.run_launch(t, 0)
+        if kind == 3:
+            rp.run_launch(t, 1)
+        else:
+            with pytest.raises(B.DqError):
+                rp.run_launch(t, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(rp.out), want)
+
+
+def test_stream_probe_reads_and_writes_every_word(dev):
+    """The measurement aid: out word j = xor of in words j, j + n_out, j + 2 n_out, ... (16-byte words)."""
+    ctx = B.Context(4, seed=1)
+    rng = np.random.default_rng(5)
+    for n_in, n_out in ((64, 64), (1000, 64), (4096 + 3, 1024), (130, 129)):
+        src = rng.integers(0, 2 ** 32, size=(n_in, 4), dtype=np.uint32)
+        want = np.zeros((n_out, 4), np.uint32)
+        for j in range(n_out):
+            want[j] = np.bitwise_xor.reduce(src[j::n_out], axis=0)
+        s = torch.from_numpy(src.view(np.uint8).reshape(-1).copy()).to(dev)
+        d = torch.full((n_out * 16,), 0xEE, dtype=torch.uint8, device=dev)
+        B.dq_stream_probe(ctx, s, d)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(d).view(np.uint32).reshape(n_out, 4), want), (n_in, n_out)
+
+
 @pytest.mark.parametrize("topology", ["ring", "butterfly"])
 def test_replay_captured_in_a_graph(dev, topology):
     """A replay is kernel launches only (no memset, no copy, no event), so a caller may capture it in
