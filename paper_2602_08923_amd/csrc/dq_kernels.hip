@@ -729,6 +729,41 @@ __device__ __forceinline__ void run_range(const Job &job, const Params &P, uint3
   }
 }
 
+// Decompress(+accumulate) over the job's tiles [w_lo, w_hi): tile by tile without a local slice, in
+// runs of one width (the next tile requested ahead) with one.
+template <typename LT>
+__device__ __forceinline__ void da_range(const Job &job, const Params &P, uint32_t xpose, uint32_t w_lo, uint32_t w_hi) {
+  if constexpr (__is_same(LT, NoLocal)) {
+    for (uint32_t t = w_lo; t < w_hi; ++t) {
+      const TilePos p = locate(job, t);
+      if (p.wi == 0) tile_da<2, LT>(job, P, xpose, p);
+      else if (p.wi == 1) tile_da<4, LT>(job, P, xpose, p);
+      else if (p.wi == 2) tile_da<8, LT>(job, P, xpose, p);
+      else tile16<kDecompress, LT>(job, P, xpose, p);
+    }
+  } else {
+    for (uint32_t t = w_lo; t < w_hi;) {  // runs of one width, as in run_range
+      const TilePos p = locate(job, t);
+      const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;
+      const uint32_t len = min(w_hi - t, left);
+      if (job.mu) {
+        if (p.wi == 0) run_tiles_da<2, LT, true>(job, P, xpose, p, len);
+        else if (p.wi == 1) run_tiles_da<4, LT, true>(job, P, xpose, p, len);
+        else if (p.wi == 2) run_tiles_da<8, LT, true>(job, P, xpose, p, len);
+      } else {
+        if (p.wi == 0) run_tiles_da<2, LT, false>(job, P, xpose, p, len);
+        else if (p.wi == 1) run_tiles_da<4, LT, false>(job, P, xpose, p, len);
+        else if (p.wi == 2) run_tiles_da<8, LT, false>(job, P, xpose, p, len);
+      }
+      if (p.wi > 2) {
+        TilePos q = p;
+        for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<kDecompress, LT>(job, P, xpose, q);
+      }
+      t += len;
+    }
+  }
+}
+
 // The job's tiles are split evenly over all waves of the grid row (4 * gridDim.x waves):
 // wave w takes [w*T/W, (w+1)*T/W).  The launcher sizes the grid to what the GPU holds at
 // once, so a wave lives for the whole launch and the table copy is paid once.
@@ -792,35 +827,7 @@ __device__ __forceinline__ void run_job(const Job &job, const Params &P) {
   if constexpr (KIND == kDecompress) {
     // per-wave transpose area: 64 lanes x 64 bytes
     const uint32_t xpose = park0 + wave * (64 * 64);
-    if constexpr (__is_same(LT, NoLocal)) {
-      for (uint32_t t = w_lo; t < w_hi; ++t) {
-        const TilePos p = locate(job, t);
-        if (p.wi == 0) tile_da<2, LT>(job, P, xpose, p);
-        else if (p.wi == 1) tile_da<4, LT>(job, P, xpose, p);
-        else if (p.wi == 2) tile_da<8, LT>(job, P, xpose, p);
-        else tile16<kDecompress, LT>(job, P, xpose, p);
-      }
-    } else {
-      for (uint32_t t = w_lo; t < w_hi;) {  // runs of one width, as in run_range
-        const TilePos p = locate(job, t);
-        const uint32_t left = (p.n_seg - p.tile_first + kWaveSGs - 1) / kWaveSGs;
-        const uint32_t len = min(w_hi - t, left);
-        if (job.mu) {
-          if (p.wi == 0) run_tiles_da<2, LT, true>(job, P, xpose, p, len);
-          else if (p.wi == 1) run_tiles_da<4, LT, true>(job, P, xpose, p, len);
-          else if (p.wi == 2) run_tiles_da<8, LT, true>(job, P, xpose, p, len);
-        } else {
-          if (p.wi == 0) run_tiles_da<2, LT, false>(job, P, xpose, p, len);
-          else if (p.wi == 1) run_tiles_da<4, LT, false>(job, P, xpose, p, len);
-          else if (p.wi == 2) run_tiles_da<8, LT, false>(job, P, xpose, p, len);
-        }
-        if (p.wi > 2) {
-          TilePos q = p;
-          for (uint32_t i = 0; i < len; ++i, q.tile_first += kWaveSGs) tile16<kDecompress, LT>(job, P, xpose, q);
-        }
-        t += len;
-      }
-    }
+    da_range<LT>(job, P, xpose, w_lo, w_hi);
   } else if (block_draws) {
     run_range<KIND, LT>(job, P, park0 + (w_lo - b_lo) * 128, w_lo, w_hi - w_lo);
   } else {
@@ -845,6 +852,37 @@ template <Kind KIND, typename LT>
 __global__ __launch_bounds__(kBlockThreads) void k_batch(const Job *jobs, Params P) {
   const Job job = jobs[blockIdx.y];
   run_job<KIND, LT>(job, P);
+}
+// Launches of thousands of jobs of at most kBatch tiles each (a replay of thousands of simulated workers:
+// a tile or two per chunk): one job per WAVE, so that a block's table copy and its place on a CU serve
+// four jobs instead of one wave's worth of one.
+template <Kind KIND, typename LT>
+__global__ __launch_bounds__(kBlockThreads) void k_batch_small(const Job *jobs, uint32_t n_jobs, Params P) {
+  extern __shared__ uint4 lds_raw[];
+  uint32_t *lds = reinterpret_cast<uint32_t *>(lds_raw);
+  // every table range: the block's four jobs may meet any width (decompress never needs the search tables)
+#pragma unroll
+  for (int r = 0; r < kRanges; ++r)
+    if (!(KIND == kDecompress && P.range_lo[r] >= kOffLut4))
+      for (uint32_t i = P.range_lo[r] + threadIdx.x * 4; i < P.range_hi[r]; i += kBlockThreads * 4)
+        *reinterpret_cast<uint4 *>(&lds[i]) = gld16(&P.blob[i]);
+  __syncthreads();
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t j = __builtin_amdgcn_readfirstlane(blockIdx.x * kBlockWaves + wave);
+  if (j >= n_jobs) return;
+  const Job job = jobs[j];
+  const uint32_t tiles = (job.n_sg[0] + kWaveSGs - 1) / kWaveSGs + (job.n_sg[1] + kWaveSGs - 1) / kWaveSGs +
+                         (job.n_sg[2] + kWaveSGs - 1) / kWaveSGs + (job.n_sg[3] + kWaveSGs - 1) / kWaveSGs;
+  if (tiles == 0) return;
+  const uint32_t park0 = kLds0 + (KIND == kDecompress ? kOffLut4 : P.blob_dwords) * 4;
+  if constexpr (KIND == kDecompress) {
+    da_range<LT>(job, P, park0 + wave * (64 * 64), 0u, tiles);
+  } else {
+    const uint32_t area = park0 + wave * 1024;
+    park_draws(job, P, 0u, tiles, area);
+    __builtin_amdgcn_wave_barrier();
+    run_range<KIND, LT>(job, P, area, 0u, tiles);
+  }
 }
 
 // Copy of a packed block in 16-byte words; the bytes from `valid` on (the padding at the block's end,
@@ -899,6 +937,11 @@ hipError_t go_batch(const Job *jobs, uint32_t n_jobs, uint32_t max_tiles, uint64
                     uint32_t grid_blocks, hipStream_t s) {
   if (n_jobs == 0 || max_tiles == 0) return hipSuccess;
   (void)total_tiles;
+  if (max_tiles <= (uint32_t)kBatch && n_jobs >= grid_blocks) {  // so many small jobs that a block per job would queue up
+    hipLaunchKernelGGL((k_batch_small<KIND, LT>), dim3((n_jobs + kBlockWaves - 1) / kBlockWaves), dim3(kBlockThreads),
+                       lds_bytes(p, KIND), s, jobs, n_jobs, p);
+    return hipGetLastError();
+  }
   const uint32_t blocks = blocks_per_job(max_tiles, n_jobs, grid_blocks);
   // the grid's y dimension (one row per job) holds at most 65,535 rows: more jobs take more launches
   for (uint32_t first = 0; first < n_jobs; first += kMaxGridRows) {
